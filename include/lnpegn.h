@@ -1,0 +1,131 @@
+/*
+ * lnpegn -- LayerNorm backward fused with per-example gradient norms, and the
+ * gradient-noise-scale estimator they feed.  C ABI of the MI355X (gfx950) library.
+ *
+ * Notation.  Activations x and upstream gradients dy are row-major contiguous
+ * [B,T,D]: B examples, T positions per example (every dimension between the
+ * first and the last is flattened into T), D features.  N = B*T rows.  For a
+ * row r:  mu = mean_d x,  var = mean_d (x-mu)^2 (biased),
+ * rstd = 1/sqrt(var+eps),  xhat = (x-mu)*rstd,  y = gamma*xhat + beta.
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer is a DEVICE pointer unless it says "host".  The caller owns
+ *     every buffer, the workspace included.  The library allocates nothing,
+ *     frees nothing, keeps no state between calls and never synchronises.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it and the call returns before it completes.
+ *   - Outputs are overwritten, never accumulated into.
+ *   - The return value is a lnpegn_status.  On any status other than LNPEGN_OK
+ *     nothing was launched and no output was touched.
+ *   - Results are bitwise reproducible from call to call for a fixed shape:
+ *     no floating-point atomics are used anywhere.
+ *   - Index arithmetic is 64-bit; B*T*D may exceed 2^31.
+ *   - Any D >= 1 is computed correctly.  The bandwidth-tuned kernels need
+ *     D % 8 == 0 (bf16) or D % 4 == 0 (fp32), D <= 8192
+ *     and 16-byte aligned x, dy, dx; other cases take a slower generic kernel.
+ */
+#ifndef LNPEGN_H
+#define LNPEGN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LNPEGN_OK = 0,
+    LNPEGN_EINVAL = 1,       /* null required pointer, B/T/D <= 0, eps < 0, misaligned pointer ... */
+    LNPEGN_EUNSUPPORTED = 2, /* unknown dtype */
+    LNPEGN_EWORKSPACE = 3,   /* workspace NULL or smaller than lnpegn_workspace_bytes() */
+    LNPEGN_EHIP = 4          /* a HIP launch reported an error */
+} lnpegn_status;
+
+/* Storage type of x, dy, dx (and of gamma, see gamma_dt).  Arithmetic is fp32 either way;
+ * dx is rounded to the storage type with round-to-nearest-even. */
+typedef enum { LNPEGN_F32 = 0, LNPEGN_BF16 = 1 } lnpegn_dtype;
+
+/* Host function, touches no device.  Bytes of workspace that ln_bwd and ln_bwd_pegn need for
+ * this shape (the same buffer serves both).  Returns 0 for invalid arguments.  The workspace
+ * must be 256-byte aligned; its contents before and after a call are unspecified. */
+size_t lnpegn_workspace_bytes(int B, int T, int D, lnpegn_dtype dt);
+
+/* Short English text for a status code (host pointer to a static string). */
+const char *lnpegn_status_string(int status);
+
+/*
+ * LayerNorm row statistics, the part of the forward pass the backward needs.
+ *   x     [N,D] in dt
+ *   mean  [N] fp32   mu_r
+ *   rstd  [N] fp32   1/sqrt(var_r + eps), biased variance
+ * (LayerNorm of Ba et al. 2016, the layer whose backward Section 5.1 of the paper fuses
+ * with the per-example norms; two-pass variance in fp32.)
+ */
+int ln_fwd_stats(const void *x, float *mean, float *rstd, int B, int T, int D, lnpegn_dtype dt,
+                 float eps, void *stream);
+
+/*
+ * Plain LayerNorm backward (no per-example outputs): the comparison kernel for the paper's
+ * "zero overhead" claim of Section 5.1.
+ *   x, dy     [B,T,D] in dt
+ *   gamma     [D] in gamma_dt
+ *   mean,rstd [N] fp32 from ln_fwd_stats, or BOTH NULL to recompute them from x with eps
+ *   dx        [B,T,D] in dt:  rstd*(dyh - mean_d(dyh) - xhat*mean_d(dyh*xhat)),  dyh = dy*gamma.
+ *             dx may alias dy (in place); it must not alias x.
+ *   dgamma    [D] fp32:  sum_{b,t} dy*xhat
+ *   dbeta     [D] fp32:  sum_{b,t} dy
+ *   workspace >= lnpegn_workspace_bytes(B,T,D,dt) bytes
+ */
+int ln_bwd(const void *x, const void *dy, const void *gamma, const float *mean, const float *rstd,
+           void *dx, float *dgamma, float *dbeta, int B, int T, int D, lnpegn_dtype dt,
+           lnpegn_dtype gamma_dt, float eps, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * LayerNorm backward fused with per-example gradient norms: Appendix B, algorithm
+ * "Layernorm Simultaneous Per-Example Gradient Norm Computation", steps 1-3 and 5-7, in the
+ * same single pass over x and dy that produces dx (Section 5.1).  All of ln_bwd's arguments
+ * and results, plus
+ *   pe_gamma_sq [B] fp32   s_gamma[b] = || sum_t dy[b,t,:]*xhat[b,t,:] ||^2   (steps 1-2)
+ *   pe_beta_sq  [B] fp32   s_beta[b]  = || sum_t dy[b,t,:] ||^2               (steps 5-6)
+ *   big_sq      [2] fp32   ||dgamma||^2, ||dbeta||^2; may be NULL
+ * The per-example squared norms are RAW: the mean over b and the B^2 correction of steps 4
+ * and 8 are applied by gns_estimate (pe_scale).
+ */
+int ln_bwd_pegn(const void *x, const void *dy, const void *gamma, const float *mean,
+                const float *rstd, void *dx, float *dgamma, float *dbeta, float *pe_gamma_sq,
+                float *pe_beta_sq, float *big_sq, int B, int T, int D, lnpegn_dtype dt,
+                lnpegn_dtype gamma_dt, float eps, void *workspace, size_t workspace_bytes,
+                void *stream);
+
+/*
+ * Gradient-noise-scale estimate from per-example norms: Section 2.1, Eq. 4 (unbiased |G|^2),
+ * Eq. 5 (S ~ tr Sigma) and Eq. 3 (B_simple = S / |G|^2) with B_small = 1 and B_big = B, after
+ * steps 4 and 8 of the Appendix B algorithm (mean over examples, times pe_scale^2).
+ *   pe_sq    [n_groups,B] fp32  raw per-example squared norms; every parameter group (each
+ *                               layer's gamma and beta) is one row.  Groups are combined by
+ *                               adding squared norms, i.e. as one concatenated gradient.
+ *   big_sq   [n_groups] fp32    squared norm of each group's summed gradient
+ *   pe_scale                    factor that turns a stored per-example gradient into the
+ *                               gradient of that example's own loss: B for a mean-reduced
+ *                               loss, 1 for a sum-reduced loss
+ *   out      [5] fp32           |G_small|^2, |G_big|^2, G2 (Eq. 4), S (Eq. 5), B_simple (Eq. 3)
+ * Sums and the estimator are evaluated in fp64.  Nothing is clamped: a non-positive G2 yields
+ * the IEEE-754 result (negative, inf or NaN).  B == 1 makes Eq. 4/5 divide by zero and is
+ * rejected with LNPEGN_EINVAL.
+ */
+int gns_estimate(const float *pe_sq, const float *big_sq, int n_groups, int B, float pe_scale,
+                 float *out, void *stream);
+
+/*
+ * Benchmarking aid.  Overrides launch-shape heuristics process-wide; it never changes results
+ * beyond floating-point summation order.  key 0: target number of row chunks of ln_bwd_pegn
+ * (0 = automatic); key 1: the same for ln_bwd; key 2: waves per workgroup of the row kernel
+ * when one wave owns a row (0 = automatic, else 1..16).  Returns LNPEGN_EINVAL for an unknown key or a
+ * value out of range.  Not thread-safe against concurrent launches.
+ */
+int lnpegn_set_tuning(int key, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LNPEGN_H */

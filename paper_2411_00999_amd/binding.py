@@ -1,0 +1,174 @@
+"""Thin ctypes binding of the lnpegn C ABI (include/lnpegn.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.
+Tensors are torch tensors on the GPU (torch is used for device memory and streams and for
+nothing else); results are returned in freshly allocated torch tensors unless the caller
+passes output buffers.  A missing or unloadable library raises -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+from . import build as _build
+
+F32, BF16 = 0, 1
+STATUS = {0: "LNPEGN_OK", 1: "LNPEGN_EINVAL", 2: "LNPEGN_EUNSUPPORTED", 3: "LNPEGN_EWORKSPACE",
+          4: "LNPEGN_EHIP"}
+EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "ln_fwd_stats", "ln_bwd",
+           "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning")
+
+_lib = None
+
+
+class LnpegnError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn} returned {STATUS.get(status, status)}")
+
+
+def lib_path() -> str:
+    return _build.LIB
+
+
+def load() -> ctypes.CDLL:
+    """Load liblnpegn.so (building it only when no library exists yet)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.ensure_built()
+    lib = ctypes.CDLL(path)
+    vp, fp, i, f, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.lnpegn_workspace_bytes.argtypes = [i, i, i, i]
+    lib.lnpegn_workspace_bytes.restype = sz
+    lib.lnpegn_status_string.argtypes = [i]
+    lib.lnpegn_status_string.restype = ctypes.c_char_p
+    lib.ln_fwd_stats.argtypes = [vp, fp, fp, i, i, i, i, f, vp]
+    lib.ln_bwd.argtypes = [vp, vp, vp, fp, fp, vp, fp, fp, i, i, i, i, i, f, vp, sz, vp]
+    lib.ln_bwd_pegn.argtypes = [vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, i, i, i, i, i, f, vp, sz, vp]
+    lib.gns_estimate.argtypes = [fp, fp, i, i, f, fp, vp]
+    lib.lnpegn_set_tuning.argtypes = [i, i]
+    for name in ("ln_fwd_stats", "ln_bwd", "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning"):
+        getattr(lib, name).restype = i
+    _lib = lib
+    return lib
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dt(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def _check3(x):
+    if x.dim() != 3 or not x.is_contiguous() or not x.is_cuda:
+        raise ValueError("expected a contiguous CUDA tensor [B,T,D]")
+    return x.shape
+
+
+def workspace_bytes(B: int, T: int, D: int, dtype: int) -> int:
+    return int(load().lnpegn_workspace_bytes(B, T, D, dtype))
+
+
+def alloc_workspace(B: int, T: int, D: int, dtype: int, device="cuda"):
+    torch = _torch()
+    return torch.empty(workspace_bytes(B, T, D, dtype), dtype=torch.uint8, device=device)
+
+
+def set_tuning(key: int, value: int) -> None:
+    rc = load().lnpegn_set_tuning(key, value)
+    if rc:
+        raise LnpegnError("lnpegn_set_tuning", rc)
+
+
+def ln_fwd_stats(x, eps: float, mean=None, rstd=None, stream=None):
+    """mean[B,T], rstd[B,T] (fp32) of x[B,T,D]."""
+    torch = _torch()
+    B, T, D = _check3(x)
+    mean = torch.empty((B, T), dtype=torch.float32, device=x.device) if mean is None else mean
+    rstd = torch.empty((B, T), dtype=torch.float32, device=x.device) if rstd is None else rstd
+    rc = load().ln_fwd_stats(_ptr(x), _ptr(mean), _ptr(rstd), B, T, D, _dt(x), eps, _stream(stream))
+    if rc:
+        raise LnpegnError("ln_fwd_stats", rc)
+    return mean, rstd
+
+
+def ln_bwd(x, dy, gamma, eps: float, mean=None, rstd=None, dx=None, dgamma=None, dbeta=None,
+           workspace=None, stream=None):
+    """Plain LayerNorm backward -> (dx, dgamma, dbeta)."""
+    torch = _torch()
+    B, T, D = _check3(x)
+    _check3(dy)
+    dx = torch.empty_like(x) if dx is None else dx
+    dgamma = torch.empty(D, dtype=torch.float32, device=x.device) if dgamma is None else dgamma
+    dbeta = torch.empty(D, dtype=torch.float32, device=x.device) if dbeta is None else dbeta
+    workspace = alloc_workspace(B, T, D, _dt(x), x.device) if workspace is None else workspace
+    rc = load().ln_bwd(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(dx),
+                       _ptr(dgamma), _ptr(dbeta), B, T, D, _dt(x), _dt(gamma), eps,
+                       _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise LnpegnError("ln_bwd", rc)
+    return dx, dgamma, dbeta
+
+
+def ln_bwd_pegn(x, dy, gamma, eps: float, mean=None, rstd=None, dx=None, dgamma=None, dbeta=None,
+                pe_gamma_sq=None, pe_beta_sq=None, big_sq=None, workspace=None, stream=None):
+    """Fused backward -> (dx, dgamma, dbeta, pe_gamma_sq[B], pe_beta_sq[B], big_sq[2])."""
+    torch = _torch()
+    B, T, D = _check3(x)
+    _check3(dy)
+    f32 = dict(dtype=torch.float32, device=x.device)
+    dx = torch.empty_like(x) if dx is None else dx
+    dgamma = torch.empty(D, **f32) if dgamma is None else dgamma
+    dbeta = torch.empty(D, **f32) if dbeta is None else dbeta
+    pe_gamma_sq = torch.empty(B, **f32) if pe_gamma_sq is None else pe_gamma_sq
+    pe_beta_sq = torch.empty(B, **f32) if pe_beta_sq is None else pe_beta_sq
+    big_sq = torch.empty(2, **f32) if big_sq is None else big_sq
+    workspace = alloc_workspace(B, T, D, _dt(x), x.device) if workspace is None else workspace
+    rc = load().ln_bwd_pegn(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(dx),
+                            _ptr(dgamma), _ptr(dbeta), _ptr(pe_gamma_sq), _ptr(pe_beta_sq),
+                            _ptr(big_sq), B, T, D, _dt(x), _dt(gamma), eps, _ptr(workspace),
+                            workspace.numel(), _stream(stream))
+    if rc:
+        raise LnpegnError("ln_bwd_pegn", rc)
+    return dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq
+
+
+def gns_estimate(pe_sq, big_sq, pe_scale: float, out=None, stream=None):
+    """pe_sq [n_groups,B] fp32, big_sq [n_groups] fp32 -> out[5] fp32 on the device:
+    |G_small|^2, |G_big|^2, G2, S, B_simple."""
+    torch = _torch()
+    if pe_sq.dim() == 1:
+        pe_sq = pe_sq[None]
+    if pe_sq.dtype != torch.float32 or big_sq.dtype != torch.float32:
+        raise TypeError("gns_estimate takes fp32 norms")
+    if not pe_sq.is_contiguous() or not big_sq.is_contiguous():
+        raise ValueError("gns_estimate takes contiguous tensors")
+    n_groups, B = pe_sq.shape
+    if big_sq.numel() != n_groups:
+        raise ValueError("big_sq must hold one value per group")
+    out = torch.empty(5, dtype=torch.float32, device=pe_sq.device) if out is None else out
+    rc = load().gns_estimate(_ptr(pe_sq), _ptr(big_sq), n_groups, B, pe_scale, _ptr(out),
+                             _stream(stream))
+    if rc:
+        raise LnpegnError("gns_estimate", rc)
+    return out

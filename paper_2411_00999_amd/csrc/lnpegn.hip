@@ -1,0 +1,350 @@
+// C ABI of the lnpegn library (declared in include/lnpegn.h): argument validation, launch
+// planning and kernel launches.  No allocation, no synchronisation, no state between calls
+// apart from the process-wide launch-shape overrides of lnpegn_set_tuning().
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/lnpegn.h"
+#include "lnpegn_finalize.h"
+#include "lnpegn_rows.h"
+
+namespace lnpegn {
+namespace {
+
+// launch-shape overrides (0 = automatic)
+int g_chunks_pegn = 0;
+int g_chunks_plain = 0;
+int g_waves = 0;
+
+constexpr int kDefaultChunks = 1024;
+constexpr int kMaxChunks = 16384;
+constexpr int kFanIn = 32;          // vectors summed per workgroup in the upper reduction levels
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+struct Plan {
+    // row kernel
+    bool fast;        // vectorised kernels usable (shape-wise; pointer alignment checked apart)
+    bool multi;       // several waves per row
+    int vpt;          // 16-byte vectors per lane
+    int waves;        // waves per workgroup
+    int max_threads;  // launch bound of the instantiation
+    int nvec;
+    int64_t Tp;       // rows per partition example
+    int C;            // chunks per partition example
+    int64_t n_slots;  // Bp * C
+    size_t lds_bytes;
+    // reduction levels
+    int ntile;
+    int64_t MA, MB;   // vectors in the two ping-pong buffers
+    // workspace layout (byte offsets)
+    size_t off_part, off_bufA, off_bufB, off_part_s, off_part_big, total;
+};
+
+Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn)
+{
+    Plan p{};
+    const int E = dt == LNPEGN_BF16 ? 8 : 4;
+    const int64_t N = (int64_t)B * T;
+    const int vpt_max = 16 / E;                      // at most 16 elements per lane
+    p.fast = (D % E == 0) && (D / E <= 64 * vpt_max * 8);
+    p.nvec = p.fast ? D / E : 0;
+    p.multi = false;
+    p.vpt = 1;
+    p.waves = 4;
+    p.max_threads = 256;
+    p.lds_bytes = 0;
+    if (p.fast) {
+        if (p.nvec <= 64 * vpt_max) {
+            p.vpt = ceil_div(p.nvec, 64);
+            const int lds_per_wave = 2 * p.vpt * E * kWave * (int)sizeof(float);
+            int w = g_waves > 0 ? g_waves : 4;
+            if (w > 4) w = 4;
+            p.waves = w;
+            p.lds_bytes = (size_t)w * lds_per_wave;
+        } else {
+            p.multi = true;
+            p.waves = ceil_div(p.nvec, 64 * vpt_max);
+            p.vpt = ceil_div(p.nvec, 64 * p.waves);
+            p.max_threads = p.waves <= 4 ? 256 : 512;
+            p.lds_bytes = 2 * 5 * 16 * sizeof(float);
+        }
+    }
+    int target = pegn ? g_chunks_pegn : g_chunks_plain;
+    if (target <= 0) target = kDefaultChunks;
+    const int rows_min = p.fast && !p.multi ? 2 * p.waves : 1;   // keep every wave busy
+    if (pegn) {
+        p.Tp = T;
+        int64_t c = target / B;
+        const int64_t cmax = T / rows_min > 1 ? T / rows_min : 1;
+        if (c > cmax) c = cmax;
+        if (c < 1) c = 1;
+        p.C = (int)c;
+        p.n_slots = (int64_t)B * p.C;
+    } else {
+        p.Tp = N;
+        int64_t c = target;
+        const int64_t cmax = N / rows_min > 1 ? N / rows_min : 1;
+        if (c > cmax) c = cmax;
+        p.C = (int)c;
+        p.n_slots = p.C;
+    }
+    p.ntile = ceil_div(D, kTile);
+    p.MA = pegn ? B : ceil_div(p.n_slots, kFanIn);
+    p.MB = ceil_div(p.MA, kFanIn);
+    const size_t vec_bytes = (size_t)2 * D * sizeof(float);
+    size_t off = 0;
+    p.off_part = off;      off += align_up((size_t)p.n_slots * vec_bytes);
+    p.off_bufA = off;      off += align_up((size_t)p.MA * vec_bytes);
+    p.off_bufB = off;      off += align_up((size_t)p.MB * vec_bytes);
+    p.off_part_s = off;    off += align_up((size_t)B * p.ntile * 2 * sizeof(double));
+    p.off_part_big = off;  off += align_up((size_t)p.ntile * 2 * sizeof(double));
+    p.total = off;
+    return p;
+}
+
+bool shape_ok(int B, int T, int D) { return B > 0 && T > 0 && D > 0; }
+bool dtype_ok(int dt) { return dt == LNPEGN_F32 || dt == LNPEGN_BF16; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ------------------------------------------------------------------------------------------
+// row kernel dispatch
+// ------------------------------------------------------------------------------------------
+template <typename T, int kVpt, bool kSaved>
+hipError_t launch_rows_vpt(const Plan &p, const RowArgs &a, hipStream_t s)
+{
+    const dim3 grid((unsigned)p.n_slots), block(64 * p.waves);
+    if (!p.multi)
+        ln_bwd_rows_kernel<T, kVpt, kSaved, false, 256><<<grid, block, p.lds_bytes, s>>>(a);
+    else if (p.max_threads == 256)
+        ln_bwd_rows_kernel<T, kVpt, kSaved, true, 256><<<grid, block, p.lds_bytes, s>>>(a);
+    else
+        ln_bwd_rows_kernel<T, kVpt, kSaved, true, 512><<<grid, block, p.lds_bytes, s>>>(a);
+    return hipGetLastError();
+}
+
+template <typename T, bool kSaved>
+hipError_t launch_rows(const Plan &p, bool fast, const RowArgs &a, hipStream_t s)
+{
+    if (!fast) {
+        ln_bwd_rows_generic_kernel<T, kSaved><<<dim3((unsigned)p.n_slots), dim3(256), 0, s>>>(a);
+        return hipGetLastError();
+    }
+    // at most 16 elements per lane: 2 vectors of 8 bf16, 4 vectors of 4 fp32
+    if constexpr (Vec<T>::kElems == 4) {
+        if (p.vpt == 3) return launch_rows_vpt<T, 3, kSaved>(p, a, s);
+        if (p.vpt == 4) return launch_rows_vpt<T, 4, kSaved>(p, a, s);
+    }
+    if (p.vpt == 1) return launch_rows_vpt<T, 1, kSaved>(p, a, s);
+    if (p.vpt == 2) return launch_rows_vpt<T, 2, kSaved>(p, a, s);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_col_sum(const float *src, int M, int gs, int D, float *dst0, float *dst1,
+                          int64_t dst_stride, double *part_sq, hipStream_t s)
+{
+    ColSumArgs c{src, dst0, dst1, part_sq, dst_stride, M, gs, D};
+    const dim3 grid((unsigned)ceil_div(M, gs), (unsigned)ceil_div(D, kTile));
+    col_sum_kernel<<<grid, dim3(kTile), 0, s>>>(c);
+    return hipGetLastError();
+}
+
+int run_bwd(bool pegn, const void *x, const void *dy, const void *gamma, const float *mean,
+            const float *rstd, void *dx, float *dgamma, float *dbeta, float *pe_gamma_sq,
+            float *pe_beta_sq, float *big_sq, int B, int T, int D, int dt, int gamma_dt, float eps,
+            void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
+    if (!dtype_ok(dt) || !dtype_ok(gamma_dt)) return LNPEGN_EUNSUPPORTED;
+    if (!x || !dy || !gamma || !dx || !dgamma || !dbeta) return LNPEGN_EINVAL;
+    if (pegn && (!pe_gamma_sq || !pe_beta_sq)) return LNPEGN_EINVAL;
+    if ((mean == nullptr) != (rstd == nullptr)) return LNPEGN_EINVAL;
+    if (dx == x) return LNPEGN_EINVAL;
+    const Plan p = make_plan(B, T, D, (lnpegn_dtype)dt, pegn);
+    if (!workspace || workspace_bytes < p.total) return LNPEGN_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return LNPEGN_EINVAL;
+    if (p.n_slots > INT32_MAX) return LNPEGN_EINVAL;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    float *part = reinterpret_cast<float *>(ws + p.off_part);
+    float *bufA = reinterpret_cast<float *>(ws + p.off_bufA);
+    float *bufB = reinterpret_cast<float *>(ws + p.off_bufB);
+    double *part_s = reinterpret_cast<double *>(ws + p.off_part_s);
+    double *part_big = reinterpret_cast<double *>(ws + p.off_part_big);
+
+    const bool fast = p.fast && aligned16(x) && aligned16(dy) && aligned16(dx);
+    RowArgs a{};
+    a.x = x; a.dy = dy; a.gamma = gamma; a.mean = mean; a.rstd = rstd; a.dx = dx;
+    a.part = part; a.Tp = p.Tp; a.C = p.C; a.D = D; a.nvec = p.nvec;
+    a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.eps = eps; a.inv_D = 1.0f / (float)D;
+
+    hipError_t e;
+    const bool saved = mean != nullptr;
+    if (dt == LNPEGN_BF16)
+        e = saved ? launch_rows<bf16_t, true>(p, fast, a, s) : launch_rows<bf16_t, false>(p, fast, a, s);
+    else
+        e = saved ? launch_rows<float, true>(p, fast, a, s) : launch_rows<float, false>(p, fast, a, s);
+    if (e != hipSuccess) return LNPEGN_EHIP;
+
+    // ---- upper levels: fixed-order sums of the chunk vectors ----
+    const int64_t vec = 2 * (int64_t)D;
+    const float *src = part;
+    int64_t M = p.n_slots;
+    float *ping = bufA, *pong = bufB;
+    if (pegn) {
+        // per-example sums (Appendix B steps 1, 5) and their squared norms per tile (steps 2, 6)
+        e = launch_col_sum(src, (int)M, p.C, D, ping, ping + D, vec, part_s, s);
+        if (e != hipSuccess) return LNPEGN_EHIP;
+        src = ping;
+        M = B;
+        float *t = ping; ping = pong; pong = t;
+    }
+    while (M > kFanIn) {
+        e = launch_col_sum(src, (int)M, kFanIn, D, ping, ping + D, vec, nullptr, s);
+        if (e != hipSuccess) return LNPEGN_EHIP;
+        src = ping;
+        M = ceil_div(M, kFanIn);
+        float *t = ping; ping = pong; pong = t;
+    }
+    // batch gradients (steps 3, 7) and, if asked for, their squared norms per tile
+    const bool want_big = pegn && big_sq != nullptr;
+    e = launch_col_sum(src, (int)M, (int)M, D, dgamma, dbeta, 0, want_big ? part_big : nullptr, s);
+    if (e != hipSuccess) return LNPEGN_EHIP;
+    if (pegn) {
+        ScalarsArgs sa{part_s, want_big ? part_big : nullptr, pe_gamma_sq, pe_beta_sq, big_sq, B, p.ntile};
+        scalars_kernel<<<dim3((unsigned)ceil_div(B > 2 ? B : 2, 256)), dim3(256), 0, s>>>(sa);
+        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    }
+    return LNPEGN_OK;
+}
+
+template <typename T>
+hipError_t launch_stats(const void *x, float *mean, float *rstd, int64_t N, int D, float eps,
+                        hipStream_t s)
+{
+    constexpr int E = Vec<T>::kElems;
+    StatsArgs a{x, mean, rstd, N, D, 0, eps, 1.0f / (float)D};
+    const bool fast = (D % E == 0) && (D / E <= 64 * (16 / E) * 8) && aligned16(x);
+    if (!fast) {
+        const unsigned grid = (unsigned)(N < 4096 ? N : 4096);
+        ln_stats_generic_kernel<T><<<dim3(grid), dim3(256), 0, s>>>(a);
+        return hipGetLastError();
+    }
+    a.nvec = D / E;
+    if (a.nvec <= 64 * (16 / E)) {
+        const int vpt = ceil_div(a.nvec, 64);
+        const int64_t want = (N + 3) / 4;
+        const dim3 grid((unsigned)(want < 4096 ? want : 4096)), block(256);
+        switch (vpt) {
+            case 1: ln_stats_kernel<T, 1, false><<<grid, block, 0, s>>>(a); break;
+            case 2: ln_stats_kernel<T, 2, false><<<grid, block, 0, s>>>(a); break;
+            case 3: ln_stats_kernel<T, 3, false><<<grid, block, 0, s>>>(a); break;
+            case 4: ln_stats_kernel<T, 4, false><<<grid, block, 0, s>>>(a); break;
+            default: return hipErrorInvalidValue;
+        }
+    } else {
+        const int waves = ceil_div(a.nvec, 64 * (16 / E));
+        const int vpt = ceil_div(a.nvec, 64 * waves);
+        const dim3 grid((unsigned)(N < 4096 ? N : 4096)), block(64 * waves);
+        switch (vpt) {
+            case 1: ln_stats_kernel<T, 1, true><<<grid, block, 0, s>>>(a); break;
+            case 2: ln_stats_kernel<T, 2, true><<<grid, block, 0, s>>>(a); break;
+            case 3: ln_stats_kernel<T, 3, true><<<grid, block, 0, s>>>(a); break;
+            case 4: ln_stats_kernel<T, 4, true><<<grid, block, 0, s>>>(a); break;
+            default: return hipErrorInvalidValue;
+        }
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+}  // namespace lnpegn
+
+using namespace lnpegn;
+
+extern "C" {
+
+size_t lnpegn_workspace_bytes(int B, int T, int D, lnpegn_dtype dt)
+{
+    if (!shape_ok(B, T, D) || !dtype_ok(dt)) return 0;
+    const size_t a = make_plan(B, T, D, dt, true).total;
+    const size_t b = make_plan(B, T, D, dt, false).total;
+    return a > b ? a : b;
+}
+
+const char *lnpegn_status_string(int status)
+{
+    switch (status) {
+        case LNPEGN_OK: return "ok";
+        case LNPEGN_EINVAL: return "invalid argument";
+        case LNPEGN_EUNSUPPORTED: return "unsupported dtype";
+        case LNPEGN_EWORKSPACE: return "workspace missing or too small";
+        case LNPEGN_EHIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int ln_fwd_stats(const void *x, float *mean, float *rstd, int B, int T, int D, lnpegn_dtype dt,
+                 float eps, void *stream)
+{
+    if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
+    if (!dtype_ok(dt)) return LNPEGN_EUNSUPPORTED;
+    if (!x || !mean || !rstd) return LNPEGN_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t N = (int64_t)B * T;
+    const hipError_t e = dt == LNPEGN_BF16 ? launch_stats<bf16_t>(x, mean, rstd, N, D, eps, s)
+                                           : launch_stats<float>(x, mean, rstd, N, D, eps, s);
+    return e == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+}
+
+int ln_bwd(const void *x, const void *dy, const void *gamma, const float *mean, const float *rstd,
+           void *dx, float *dgamma, float *dbeta, int B, int T, int D, lnpegn_dtype dt,
+           lnpegn_dtype gamma_dt, float eps, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_bwd(false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, nullptr, nullptr, nullptr, B, T,
+                   D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
+}
+
+int ln_bwd_pegn(const void *x, const void *dy, const void *gamma, const float *mean,
+                const float *rstd, void *dx, float *dgamma, float *dbeta, float *pe_gamma_sq,
+                float *pe_beta_sq, float *big_sq, int B, int T, int D, lnpegn_dtype dt,
+                lnpegn_dtype gamma_dt, float eps, void *workspace, size_t workspace_bytes,
+                void *stream)
+{
+    return run_bwd(true, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq,
+                   B, T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
+}
+
+int gns_estimate(const float *pe_sq, const float *big_sq, int n_groups, int B, float pe_scale,
+                 float *out, void *stream)
+{
+    if (!pe_sq || !big_sq || !out || n_groups <= 0 || B <= 1) return LNPEGN_EINVAL;
+    gns_estimate_kernel<<<dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+        pe_sq, big_sq, n_groups, B, pe_scale, out);
+    return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+}
+
+int lnpegn_set_tuning(int key, int value)
+{
+    if (value < 0) return LNPEGN_EINVAL;
+    switch (key) {
+        case 0:
+            if (value > kMaxChunks) return LNPEGN_EINVAL;
+            g_chunks_pegn = value;
+            return LNPEGN_OK;
+        case 1:
+            if (value > kMaxChunks) return LNPEGN_EINVAL;
+            g_chunks_plain = value;
+            return LNPEGN_OK;
+        case 2:
+            if (value > 16) return LNPEGN_EINVAL;
+            g_waves = value;
+            return LNPEGN_OK;
+        default: return LNPEGN_EINVAL;
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,114 @@
+"""Shared helpers of the GPU parity tests: upload, run through the C ABI, compare.
+
+Comparison rule (written out here because "relative 1e-5 / 2e-3" needs a definition where a
+zero-mean sum cancels and where the output itself is rounded to bf16):
+  for every output tensor, with ref the fp64 oracle value and rms = sqrt(mean(ref^2)),
+    (1)  ||out - ref||_2 / ||ref||_2                       <= tol
+    (2)  |out - ref| <= tol * (|ref| + rms) [+ half a bf16 ulp of ref for bf16 outputs]
+  tol = 1e-5 for fp32 inputs, 2e-3 for bf16 inputs.  Outputs that are fp32 sums (dgamma,
+  dbeta, per-example squared norms, big_sq) are held to 1e-5 for both input types, because
+  both sides read identical inputs and differ only in accumulation order.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+TOL_F32 = 1e-5
+TOL_BF16 = 2e-3
+TOL_SUMS = 1e-5
+TOL_GNS = 1e-4
+
+
+def to_device(arr32: np.ndarray, dtype: str):
+    """float32 host values -> device tensor of the workload's storage type (exact)."""
+    import torch
+    from paper_2411_00999_amd import workloads
+    if dtype == "bf16":
+        bits = workloads.bf16_bits(arr32)
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(arr32, dtype=np.float32)).cuda()
+
+
+def to_host64(t) -> np.ndarray:
+    """device tensor (fp32 or bf16) -> float64 numpy (exact)."""
+    import torch
+    if t.dtype == torch.bfloat16:
+        return t.float().cpu().numpy().astype(np.float64)
+    return t.cpu().numpy().astype(np.float64)
+
+
+def bf16_half_ulp(ref: np.ndarray) -> np.ndarray:
+    """Half the spacing of bf16 numbers around |ref| (8 significand bits)."""
+    a = np.abs(ref)
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** -126)))
+    return 0.5 * 2.0 ** (e - 7)
+
+
+def check_close(name, out, ref, tol, bf16_output=False):
+    out = np.asarray(out, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert out.shape == ref.shape, f"{name}: shape {out.shape} vs {ref.shape}"
+    assert np.all(np.isfinite(out)), f"{name}: non-finite output"
+    diff = np.abs(out - ref)
+    nref = np.linalg.norm(ref.ravel())
+    rms = nref / np.sqrt(max(ref.size, 1))
+    bound = tol * (np.abs(ref) + rms)
+    if bf16_output:
+        bound = bound + bf16_half_ulp(ref)
+    worst = int(np.argmax(diff - bound))
+    assert np.all(diff <= bound), (
+        f"{name}: |out-ref|={diff.ravel()[worst]:.3e} > bound {bound.ravel()[worst]:.3e} "
+        f"at flat index {worst} (ref {ref.ravel()[worst]:.6e}, out {out.ravel()[worst]:.6e})")
+    if nref > 0:
+        rel = np.linalg.norm((out - ref).ravel()) / nref
+        # the L2 bound gets the same output-rounding allowance as the elementwise one
+        allow = tol + (np.linalg.norm(bf16_half_ulp(ref).ravel()) / nref if bf16_output else 0.0)
+        assert rel <= allow, f"{name}: L2 relative error {rel:.3e} > {allow:.3e}"
+
+
+def gns_condition(B, g_big_sq, g_small_sq):
+    """Error amplification of Eq. 4 when the true gradient is (close to) zero."""
+    return (B * g_big_sq + g_small_sq) / max(abs(B * g_big_sq - g_small_sq), 1e-300)
+
+
+def run_gpu(inp, saved_stats=False, pegn=True, gamma_f32=False, in_place=False):
+    """Run the HIP path on an LNInputs through the C ABI; returns a dict of float64 numpy arrays."""
+    import torch
+    from paper_2411_00999_amd import binding
+    x = to_device(inp.x, inp.dtype)
+    dy = to_device(inp.dy, inp.dtype)
+    gamma = to_device(inp.gamma, "f32" if gamma_f32 else inp.dtype)
+    mean = rstd = None
+    if saved_stats:
+        mean, rstd = binding.ln_fwd_stats(x, inp.eps)
+    dx_buf = dy if in_place else None
+    res = {}
+    if pegn:
+        dx, dg, db, sg, sb, big = binding.ln_bwd_pegn(x, dy, gamma, inp.eps, mean=mean, rstd=rstd, dx=dx_buf)
+        res.update(s_gamma=to_host64(sg), s_beta=to_host64(sb), big_sq=to_host64(big))
+        res["_dev"] = dict(sg=sg, sb=sb, big=big)
+    else:
+        dx, dg, db = binding.ln_bwd(x, dy, gamma, inp.eps, mean=mean, rstd=rstd, dx=dx_buf)
+    torch.cuda.synchronize()
+    res.update(dx=to_host64(dx), dgamma=to_host64(dg), dbeta=to_host64(db))
+    if saved_stats:
+        res.update(mean=to_host64(mean), rstd=to_host64(rstd))
+    return res
+
+
+def compare_with_oracle(inp, res, ref, pegn=True, dx_rows=None):
+    """ref: dict from oracle.ln_bwd_pegn.  dx_rows: optional flat row indices to restrict dx."""
+    tol = TOL_BF16 if inp.dtype == "bf16" else TOL_F32
+    bf = inp.dtype == "bf16"
+    if ref.get("dx") is not None:
+        got = res["dx"].reshape(-1, inp.D)
+        want = ref["dx"].reshape(-1, inp.D)
+        if dx_rows is not None:
+            got, want = got[dx_rows], want
+        check_close("dx", got, want, tol, bf16_output=bf)
+    check_close("dgamma", res["dgamma"], ref["dgamma"], TOL_SUMS)
+    check_close("dbeta", res["dbeta"], ref["dbeta"], TOL_SUMS)
+    if pegn:
+        np.testing.assert_allclose(res["s_gamma"], ref["s_gamma"], rtol=TOL_SUMS, err_msg="s_gamma")
+        np.testing.assert_allclose(res["s_beta"], ref["s_beta"], rtol=TOL_SUMS, err_msg="s_beta")
+        np.testing.assert_allclose(res["big_sq"], ref["big_sq"], rtol=TOL_SUMS, err_msg="big_sq")

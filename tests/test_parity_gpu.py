@@ -1,0 +1,260 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the fp64 CPU oracle on the
+same seeded inputs, element by element.  Run with `pytest -m gpu` on an MI355X."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2411_00999_amd import workloads
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle(inp, want_dx=True):
+    return oracle.ln_bwd_pegn(inp.x, inp.dy, inp.gamma, inp.eps, want_dx=want_dx, want_pe=False)
+
+
+def _gns_both(res, ref, B):
+    """End-to-end estimate: GPU norms through the GPU estimator vs oracle norms through the oracle."""
+    import torch
+    from paper_2411_00999_amd import binding
+    d = res["_dev"]
+    out = binding.gns_estimate(torch.stack([d["sg"], d["sb"]]), d["big"], float(B))
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    want = oracle.gns_estimate(np.stack([ref["s_gamma"], ref["s_beta"]]), ref["big_sq"], float(B))
+    return got, want
+
+
+def _check_gns(got, want, B):
+    keys = ("g_small_sq", "g_big_sq", "G2", "S", "B_simple")
+    w = np.array([want[k] for k in keys])
+    # norms and S are well conditioned
+    np.testing.assert_allclose(got[:2], w[:2], rtol=pu.TOL_SUMS)
+    np.testing.assert_allclose(got[3], w[3], rtol=pu.TOL_GNS)
+    # G2 (Eq. 4) is a difference of nearly equal numbers when the true gradient is ~0: the
+    # synthetic dy is zero-mean.  kappa is the amplification of a relative error in the norms.
+    kappa = pu.gns_condition(B, want["g_big_sq"], want["g_small_sq"])
+    eps_norm = 2.0 ** -23       # the norms are handed over as fp32
+    rtol = max(pu.TOL_GNS, 4 * kappa * eps_norm)
+    assert got[2] == pytest.approx(w[2], rel=rtol), ("G2", kappa)
+    assert got[4] == pytest.approx(w[4], rel=2 * rtol), ("B_simple", kappa)
+
+
+# ------------------------------------------------------------------ workload 1, full size
+@pytest.mark.parametrize("saved", [False, True])
+@pytest.mark.parametrize("signal", [0.0, 1e-2])
+def test_workload1_fp32_pegn_and_gns(saved, signal):
+    inp = workloads.make_inputs(1, signal=signal)
+    ref = _oracle(inp)
+    res = pu.run_gpu(inp, saved_stats=saved)
+    pu.compare_with_oracle(inp, res, ref)
+    got, want = _gns_both(res, ref, inp.B)
+    _check_gns(got, want, inp.B)
+    if signal > 0:      # well conditioned: the plain 1e-4 bar holds on every output
+        keys = ("g_small_sq", "g_big_sq", "G2", "S", "B_simple")
+        np.testing.assert_allclose(got, [want[k] for k in keys], rtol=pu.TOL_GNS)
+        assert want["B_simple"] > 0
+    if saved:
+        m, r = oracle.ln_stats(inp.x, inp.eps)
+        pu.check_close("mean", res["mean"], m, pu.TOL_F32)
+        np.testing.assert_allclose(res["rstd"], r, rtol=pu.TOL_F32)
+
+
+def test_workload1_plain_matches_oracle_and_fused():
+    inp = workloads.make_inputs(1)
+    ref = _oracle(inp)
+    plain = pu.run_gpu(inp, pegn=False)
+    pu.compare_with_oracle(inp, plain, ref, pegn=False)
+    fused = pu.run_gpu(inp)
+    np.testing.assert_array_equal(plain["dx"], fused["dx"])     # same row arithmetic
+
+
+# ------------------------------------------------------------------ reduced shapes of 2..5
+REDUCED = [
+    # (workload, B, T, D): several chunks, several column tiles, ragged row counts
+    (2, 3, 37, 768),
+    (2, 2, 130, 576),
+    (2, 5, 19, 960),
+    (3, 2, 150, 2048),
+    (3, 3, 41, 4096),
+    (4, 16, 8, 1024),
+    (4, 70, 3, 1024),
+    (5, 2, 33, 8192),
+    (5, 1, 70, 6144),
+]
+
+
+@pytest.mark.parametrize("cfg,B,T,D", REDUCED)
+@pytest.mark.parametrize("saved", [False, True])
+def test_reduced_workloads_bf16(cfg, B, T, D, saved):
+    inp = workloads.make_inputs(cfg, B=B, T=T, D=D)
+    ref = _oracle(inp)
+    res = pu.run_gpu(inp, saved_stats=saved)
+    pu.compare_with_oracle(inp, res, ref)
+    if B > 1:
+        got, want = _gns_both(res, ref, B)
+        _check_gns(got, want, B)
+    plain = pu.run_gpu(inp, saved_stats=saved, pegn=False)
+    pu.compare_with_oracle(inp, plain, ref, pegn=False)
+
+
+@pytest.mark.parametrize("B,T,D,dtype", [
+    (2, 9, 1, "f32"), (3, 5, 5, "f32"), (2, 11, 257, "f32"), (2, 7, 258, "f32"), (2, 6, 1028, "f32"),
+    (2, 9, 1, "bf16"), (3, 5, 7, "bf16"), (2, 11, 257, "bf16"), (2, 5, 1001, "bf16"), (1, 4, 9000, "bf16"),
+    (2, 5, 12288, "bf16"), (2, 3, 2048, "f32"), (2, 3, 8192, "f32"), (2, 9, 64, "f32"), (2, 9, 8, "bf16"),
+])
+def test_any_D_is_correct(B, T, D, dtype):
+    """Generic kernel (odd D, D above the tuned range) and the small/large ends of the tuned ones."""
+    inp = workloads.make_inputs(1, B=B, T=T, D=D, dtype=dtype)
+    ref = _oracle(inp)
+    for saved in (False, True):
+        res = pu.run_gpu(inp, saved_stats=saved)
+        pu.compare_with_oracle(inp, res, ref)
+
+
+def test_gamma_fp32_with_bf16_activations():
+    inp = workloads.make_inputs(2, B=2, T=40, D=768)
+    ref = _oracle(inp)
+    res = pu.run_gpu(inp, gamma_f32=True)
+    pu.compare_with_oracle(inp, res, ref)
+
+
+# ------------------------------------------------------------------ edge cases
+def test_T1_and_B1():
+    for B, T in ((6, 1), (1, 50), (1, 1)):
+        inp = workloads.make_inputs(2, B=B, T=T, D=768)
+        ref = _oracle(inp)
+        res = pu.run_gpu(inp)
+        pu.compare_with_oracle(inp, res, ref)
+        if B == 1:   # one example: its squared norm IS the squared norm of the batch gradient
+            np.testing.assert_array_equal(res["s_gamma"][0], res["big_sq"][0])
+            np.testing.assert_array_equal(res["s_beta"][0], res["big_sq"][1])
+
+
+def test_constant_row_and_identical_examples():
+    inp = workloads.make_inputs(1, B=4, T=16, D=256)
+    inp.x[1, 3] = 2.5                                  # sigma^2 = 0 in one row
+    inp.x[:] = inp.x[0]
+    inp.dy[:] = inp.dy[0]                              # all examples identical
+    ref = _oracle(inp)
+    res = pu.run_gpu(inp)
+    pu.compare_with_oracle(inp, res, ref)
+    got, want = _gns_both(res, ref, inp.B)
+    big = want["g_big_sq"]
+    assert abs(got[3]) <= 1e-5 * big                   # S = 0: no noise
+    assert got[2] == pytest.approx(big, rel=1e-5)      # G2 = |G_big|^2
+
+
+def test_in_place_dx_over_dy():
+    inp = workloads.make_inputs(3, B=2, T=30, D=2048)
+    ref = _oracle(inp)
+    res = pu.run_gpu(inp, in_place=True)
+    pu.compare_with_oracle(inp, res, ref)
+
+
+def test_misaligned_pointers_take_the_generic_kernel():
+    import torch
+    from paper_2411_00999_amd import binding
+    inp = workloads.make_inputs(2, B=2, T=10, D=768)
+    ref = _oracle(inp)
+    n = inp.B * inp.T * inp.D
+
+    def shifted(a):
+        buf = torch.empty(n + 1, dtype=torch.bfloat16, device="cuda")
+        view = buf[1:].view(inp.B, inp.T, inp.D)          # 2-byte offset: not 16-byte aligned
+        view.copy_(pu.to_device(a, "bf16"))
+        return view
+
+    x, dy = shifted(inp.x), shifted(inp.dy)
+    gamma = pu.to_device(inp.gamma, "bf16")
+    dx, dg, db, sg, sb, big = binding.ln_bwd_pegn(x, dy, gamma, inp.eps)
+    torch.cuda.synchronize()
+    res = dict(dx=pu.to_host64(dx), dgamma=pu.to_host64(dg), dbeta=pu.to_host64(db),
+               s_gamma=pu.to_host64(sg), s_beta=pu.to_host64(sb), big_sq=pu.to_host64(big))
+    pu.compare_with_oracle(inp, res, ref)
+
+
+def test_bitwise_reproducible():
+    inp = workloads.make_inputs(3, B=4, T=64, D=2048)
+    a = pu.run_gpu(inp)
+    for _ in range(5):
+        b = pu.run_gpu(inp)
+        for k in ("dx", "dgamma", "dbeta", "s_gamma", "s_beta", "big_sq"):
+            np.testing.assert_array_equal(a[k], b[k], err_msg=k)
+
+
+def test_chunk_count_only_changes_summation_order():
+    from paper_2411_00999_amd import binding
+    inp = workloads.make_inputs(3, B=4, T=96, D=2048)
+    ref = _oracle(inp)
+    try:
+        for chunks in (4, 16, 64, 4096):
+            binding.set_tuning(0, chunks)
+            binding.set_tuning(1, chunks)
+            res = pu.run_gpu(inp)
+            pu.compare_with_oracle(inp, res, ref)
+            plain = pu.run_gpu(inp, pegn=False)
+            pu.compare_with_oracle(inp, plain, ref, pegn=False)
+    finally:
+        binding.set_tuning(0, 0)
+        binding.set_tuning(1, 0)
+
+
+# ------------------------------------------------------------------ estimator alone
+@pytest.mark.parametrize("n_groups,B", [(1, 2), (2, 8), (96, 16), (3, 513)])
+def test_gns_estimate_same_norms_both_sides(n_groups, B):
+    import torch
+    from paper_2411_00999_amd import binding
+    rng = np.random.default_rng(n_groups * 1000 + B)
+    mu = rng.standard_normal((n_groups, 1, 6)) * 0.7
+    g = mu + rng.standard_normal((n_groups, B, 6))
+    pe = np.sum((g / B) ** 2, -1).astype(np.float32)
+    big = np.sum(g.mean(1) ** 2, -1).astype(np.float32)
+    out = binding.gns_estimate(torch.from_numpy(pe).cuda(), torch.from_numpy(big).cuda(), float(B))
+    torch.cuda.synchronize()
+    want = oracle.gns_estimate(pe.astype(np.float64), big.astype(np.float64), float(B))
+    keys = ("g_small_sq", "g_big_sq", "G2", "S", "B_simple")
+    np.testing.assert_allclose(out.cpu().numpy(), [want[k] for k in keys], rtol=pu.TOL_GNS)
+
+
+# ------------------------------------------------------------------ full sizes
+def _sampled_dx_check(inp, res, n_rows=64, seed=0):
+    """dx of a row depends on that row alone: check sampled rows one by one at any size."""
+    rng = np.random.default_rng(seed)
+    N = inp.B * inp.T
+    rows = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, n_rows)]))
+    x2, dy2 = inp.x.reshape(N, inp.D), inp.dy.reshape(N, inp.D)
+    want = np.stack([oracle.ln_bwd_example(x2[r:r + 1], dy2[r:r + 1], inp.gamma, inp.eps)[0][0]
+                     for r in rows])
+    tol = pu.TOL_BF16 if inp.dtype == "bf16" else pu.TOL_F32
+    pu.check_close("dx(sampled rows)", res["dx"].reshape(N, inp.D)[rows], want, tol,
+                   bf16_output=inp.dtype == "bf16")
+    # property that holds for every row at any size: sum_d dx = 0 (up to output rounding)
+    dx = res["dx"].reshape(N, inp.D)
+    row_sum = np.abs(dx.sum(-1))
+    budget = (2.0 ** -8 if inp.dtype == "bf16" else 2.0 ** -20) * np.abs(dx).sum(-1) / np.sqrt(inp.D) * 8 + 1e-30
+    assert np.all(row_sum <= budget), float(np.max(row_sum / budget))
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_size_workloads(cfg):
+    inp = workloads.make_inputs(cfg)
+    ref = _oracle(inp, want_dx=False)
+    res = pu.run_gpu(inp, saved_stats=(cfg == 3))
+    pu.compare_with_oracle(inp, res, ref)
+    _sampled_dx_check(inp, res, seed=cfg)
+    got, want = _gns_both(res, ref, inp.B)
+    _check_gns(got, want, inp.B)
+    if cfg == 4:
+        # half of the examples are copies of example 0: their norms coincide exactly, and S
+        # equals the closed form  [ n/2 |a-ubar|^2 + sum_i |u_i-ubar|^2 ] / (2n-1)
+        n = inp.B // 2
+        assert np.all(res["s_gamma"][:n] == res["s_gamma"][0])
+        assert np.all(res["s_beta"][:n] == res["s_beta"][0])
+        o = oracle.ln_bwd_pegn(inp.x, inp.dy, inp.gamma, inp.eps, want_dx=False)
+        g = inp.B * np.concatenate([o["pe_gamma"], o["pe_beta"]], axis=1)
+        a, u = g[0], g[n:]
+        ubar = u.mean(0)
+        closed = ((n / 2.0) * np.sum((a - ubar) ** 2) + np.sum((u - ubar) ** 2)) / (2 * n - 1)
+        assert got[3] == pytest.approx(closed, rel=pu.TOL_GNS)
