@@ -229,7 +229,7 @@ def _sampled_dx_check(inp, res, n_rows=64, seed=0):
                      for r in rows])
     tol = pu.TOL_BF16 if inp.dtype == "bf16" else pu.TOL_F32
     pu.check_close("dx(sampled rows)", res["dx"].reshape(N, inp.D)[rows], want, tol,
-                   bf16_output=inp.dtype == "bf16")
+                   bf16_output=inp.dtype == "bf16", floor_rms=pu.dx_term_rms(inp, rows))
     # property that holds for every row at any size: sum_d dx = 0 (up to output rounding)
     dx = res["dx"].reshape(N, inp.D)
     row_sum = np.abs(dx.sum(-1))
