@@ -1,0 +1,284 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused LayerNorm-backward + per-example-gradient-norm path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 3] [--stats saved|recompute]
+
+One "step" is one pass of the whole hot path over one batch of synthetic input: for every
+LayerNorm layer of the workload, ln_bwd_pegn (dx, dgamma, dbeta, per-example squared norms),
+then one gns_estimate over all layers' norms.  Inputs are resident in HBM before the timed
+region starts.  Prints ONE JSON line (see the design doc for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import concurrent.futures as cf
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+
+
+# ----------------------------------------------------------------------------- HIP events
+class HipEvents:
+    """hipEvent_t pairs through the HIP runtime already loaded in this process (plumbing only:
+    torch.cuda.Event cannot be handed to the library as a raw handle before it is recorded)."""
+
+    def __init__(self):
+        path = None
+        with open("/proc/self/maps") as f:
+            for line in f:
+                if "libamdhip64" in line:
+                    path = line.split()[-1]
+                    break
+        self.hip = ctypes.CDLL(path or "libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        ev = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(ev))
+        if rc:
+            raise RuntimeError(f"hipEventCreate -> {rc}")
+        return ev
+
+    def elapsed_ms(self, a, b) -> float:
+        self.hip.hipEventSynchronize(b)
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc:
+            raise RuntimeError(f"hipEventElapsedTime -> {rc}")
+        return float(ms.value)
+
+    def destroy(self, ev):
+        self.hip.hipEventDestroy(ev)
+
+
+# ----------------------------------------------------------------------------- set-up
+def build_layers(cfg, n_layers, stats_mode, log):
+    import numpy as np
+    import torch
+    from paper_2411_00999_amd import binding, workloads
+
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import parity_util as pu
+
+    B, T, D, dtype, _ = workloads.SHAPES[cfg]
+    workers = max(1, min(16, os.cpu_count() or 1, n_layers))
+    layers, host0 = [], None
+    t0 = time.time()
+    with cf.ThreadPoolExecutor(max_workers=workers) as ex:
+        futs = [ex.submit(workloads.make_inputs, cfg, l) for l in range(n_layers)]
+        for l, fut in enumerate(futs):
+            inp = fut.result()
+            f32 = dict(dtype=torch.float32, device="cuda")
+            L = dict(x=pu.to_device(inp.x, dtype), dy=pu.to_device(inp.dy, dtype),
+                     gamma=pu.to_device(inp.gamma, dtype))
+            L["dx"] = torch.empty_like(L["x"])
+            L["dgamma"] = torch.empty(D, **f32)
+            L["dbeta"] = torch.empty(D, **f32)
+            L["mean"] = L["rstd"] = None
+            if stats_mode == "saved":
+                L["mean"], L["rstd"] = binding.ln_fwd_stats(L["x"], inp.eps)
+            layers.append(L)
+            if l == 0:
+                host0 = inp
+            futs[l] = None
+            if (l + 1) % 8 == 0 or l + 1 == n_layers:
+                log(f"inputs: {l + 1}/{n_layers} layers resident ({time.time() - t0:.1f}s)")
+    torch.cuda.synchronize()
+    dt_code = binding.BF16 if dtype == "bf16" else binding.F32
+    shared = dict(
+        ws=binding.alloc_workspace(B, T, D, dt_code),
+        pe_all=torch.zeros((2 * n_layers, B), dtype=torch.float32, device="cuda"),
+        big_all=torch.zeros(2 * n_layers, dtype=torch.float32, device="cuda"),
+        gns=torch.zeros(5, dtype=torch.float32, device="cuda"),
+    )
+    for l, L in enumerate(layers):     # views into the shared norm tables, made once
+        L["pe_g"], L["pe_b"] = shared["pe_all"][2 * l], shared["pe_all"][2 * l + 1]
+        L["big"] = shared["big_all"][2 * l:2 * l + 2]
+    return layers, shared, host0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=3, choices=[2, 3, 4, 5])
+    ap.add_argument("--layers", type=int, default=0, help="override the workload's layer count")
+    ap.add_argument("--stats", default="recompute", choices=["saved", "recompute"],
+                    help="row mean/rstd: recomputed inside the backward, or saved by ln_fwd_stats")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--quiet", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards along the batch dimension; see "
+              "DESIGN.md); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    def log(msg):
+        if not args.quiet:
+            print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    import numpy as np
+    import torch
+    from paper_2411_00999_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    binding.load()   # raises if the HIP library is missing: there is no fallback
+
+    cfg = args.workload
+    B, T, D, dtype, n_layers = workloads.SHAPES[cfg]
+    if args.layers > 0:
+        n_layers = args.layers
+    N = B * T
+    esz = 2 if dtype == "bf16" else 4
+    bytes_per_layer = 3 * N * D * esz          # read x + read dy + write dx
+    bytes_per_step = bytes_per_layer * n_layers
+    log(f"workload {cfg}: B={B} T={T} D={D} {dtype} x {n_layers} layers, "
+        f"{bytes_per_step / 1e9:.2f} GB algorithmic per step, stats={args.stats}")
+
+    layers, sh, host0 = build_layers(cfg, n_layers, args.stats, log)
+    eps = workloads.EPS
+
+    def fused_step():
+        for L in layers:
+            binding.ln_bwd_pegn(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"],
+                                dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"],
+                                pe_gamma_sq=L["pe_g"], pe_beta_sq=L["pe_b"], big_sq=L["big"],
+                                workspace=sh["ws"])
+        binding.gns_estimate(sh["pe_all"], sh["big_all"], float(B), out=sh["gns"])
+
+    def plain_step():
+        for L in layers:
+            binding.ln_bwd(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"],
+                           dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"], workspace=sh["ws"])
+
+    def timed(step, warmup, steps):
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    t_fused = timed(fused_step, args.warmup, args.steps)
+    log(f"fused : {t_fused * 1e3:.3f} ms/step  {bytes_per_step / t_fused / 1e9:.1f} GB/s")
+    t_plain = timed(plain_step, args.warmup, args.steps)
+    log(f"plain : {t_plain * 1e3:.3f} ms/step  {bytes_per_step / t_plain / 1e9:.1f} GB/s")
+
+    # ---- dominant kernel: HIP events around the row-streaming kernel, on its own stream ----
+    hip = HipEvents()
+    pairs = [(hip.create(), hip.create()) for _ in layers]
+
+    def kernel_avg_ms(plain):
+        tot, cnt = 0.0, 0
+        for _ in range(args.steps):
+            for l, L in enumerate(layers):
+                binding.set_profile_events(pairs[l][0], pairs[l][1])
+                if plain:
+                    binding.ln_bwd(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"],
+                                   dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"], workspace=sh["ws"])
+                else:
+                    binding.ln_bwd_pegn(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"],
+                                        dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"],
+                                        pe_gamma_sq=L["pe_g"], pe_beta_sq=L["pe_b"], big_sq=L["big"],
+                                        workspace=sh["ws"])
+            torch.cuda.synchronize()
+            for a, b in pairs:
+                tot += hip.elapsed_ms(a, b)
+                cnt += 1
+        return tot / cnt
+
+    k_fused_ms = kernel_avg_ms(False)
+    k_plain_ms = kernel_avg_ms(True)
+    for a, b in pairs:
+        hip.destroy(a)
+        hip.destroy(b)
+    achieved = bytes_per_layer / (k_fused_ms * 1e-3) / 1e9
+    log(f"row kernel: fused {k_fused_ms * 1e3:.1f} us ({achieved:.0f} GB/s), plain {k_plain_ms * 1e3:.1f} us")
+
+    gns = sh["gns"].cpu().numpy().astype(float)
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample (layer 0) ----
+    cpu_baseline = None
+    parity = None
+    if not args.no_cpu_baseline:
+        import oracle
+        x64 = host0.x.astype(np.float64)
+        dy64 = host0.dy.astype(np.float64)
+        g64 = host0.gamma.astype(np.float64)
+        threads = min(B, oracle.max_threads())
+        oracle.ln_bwd_pegn(x64[:1], dy64[:1], g64, eps)           # load + warm the library
+        t0 = time.perf_counter()
+        ref = oracle.ln_bwd_pegn(x64, dy64, g64, eps, want_dx=True, want_pe=False, nthreads=threads)
+        t_cpu = time.perf_counter() - t0
+        cpu_baseline = {
+            "value": round(bytes_per_layer / t_cpu / 1e9, 4), "unit": "GB/s", "cores": threads,
+            "kind": "oracle",
+            "sample": f"layer 0 of {n_layers} (B={B} T={T} D={D}, dx + per-example norms), "
+                      f"{t_cpu:.2f} s wall on {threads} threads of {os.cpu_count()} host cpus; "
+                      f"bytes counted as for the GPU ({esz} B/element)",
+            "seconds": round(t_cpu, 3),
+        }
+        log(f"oracle: {t_cpu:.2f} s for one layer on {threads} threads")
+        # spot parity of layer 0 against the oracle output just computed
+        L0 = layers[0]
+        dg = L0["dgamma"].cpu().numpy().astype(np.float64)
+        sg = sh["pe_all"][0].cpu().numpy().astype(np.float64)
+        err_dg = float(np.linalg.norm(dg - ref["dgamma"]) / np.linalg.norm(ref["dgamma"]))
+        err_sg = float(np.max(np.abs(sg / ref["s_gamma"] - 1.0)))
+        parity = {"layer0_dgamma_l2_rel": err_dg, "layer0_s_gamma_max_rel": err_sg,
+                  "ok": bool(err_dg < 1e-5 and err_sg < 1e-5)}
+
+    out = {
+        "metric": "fused LN bwd+per-example norms GB/s, % HBM peak, overhead vs plain ln_bwd",
+        "value": round(bytes_per_step / t_fused / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(t_fused * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if dtype == "f32" else "bf16 storage, f32 arithmetic",
+        "data": "synthetic",
+        "config": {
+            "workload": f"configs[{cfg - 1}]: {n_layers} LayerNorm layers back-to-back, B={B} T={T} D={D} "
+                        f"{dtype}, ln_bwd_pegn per layer + one gns_estimate; row stats {args.stats}",
+            "B": B, "T": T, "D": D, "layers": n_layers, "stats": args.stats,
+        },
+        "pct_hbm_peak": round(100.0 * bytes_per_step / t_fused / 1e9 / HBM_PEAK_GBS, 2),
+        "tokens_per_s": round(n_layers * N / t_fused, 1),
+        "plain_ln_bwd": {"ms_per_step": round(t_plain * 1e3, 4),
+                         "GBps": round(bytes_per_step / t_plain / 1e9, 2)},
+        "overhead_vs_plain_pct": round(100.0 * (t_fused / t_plain - 1.0), 2),
+        "gns": {"g_small_sq": gns[0], "g_big_sq": gns[1], "G2": gns[2], "S": gns[3], "B_simple": gns[4]},
+        "roofline": {
+            "kernel": "ln_bwd_rows_kernel (fused call)",
+            "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+            "avg_launch_us": round(k_fused_ms * 1e3, 2),
+            "plain_avg_launch_us": round(k_plain_ms * 1e3, 2),
+            "algorithmic_bytes_per_launch": bytes_per_layer,
+        },
+        "cpu_baseline": cpu_baseline,
+        "parity_spot_check": parity,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

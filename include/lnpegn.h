@@ -125,6 +125,26 @@ int gns_estimate(const float *pe_sq, const float *big_sq, int n_groups, int B, f
  */
 int lnpegn_set_tuning(int key, int value);
 
+/*
+ * Benchmarking aid, one-shot.  The next ln_bwd or ln_bwd_pegn call attaches the two hipEvent_t
+ * to the dispatch of its row-streaming kernel (start of execution, end of execution), so that
+ * hipEventElapsedTime(start, stop) is that kernel's own duration; then it forgets both.  The
+ * caller owns the events.  Passing two NULLs disarms.  Returns LNPEGN_EINVAL if exactly one of
+ * them is NULL.  Not thread-safe.
+ */
+int lnpegn_set_profile_events(void *start_event, void *stop_event);
+
+/*
+ * Benchmarking aid: a plain streaming kernel of known traffic, the yardstick for the row
+ * kernels (empirical bandwidth ceiling of the machine, and the scale of hardware byte
+ * counters).  mode 0: out = a (one read, one write); mode 1: out = a XOR b (two reads, one
+ * write -- the access mix of the LayerNorm backward).  `bytes` is the size of EACH array and
+ * must be a multiple of 16; a, b, out are 16-byte aligned device pointers (b is ignored in
+ * mode 0).  Honours lnpegn_set_profile_events like the backward calls.
+ */
+int lnpegn_stream_probe(const void *a, const void *b, void *out, size_t bytes, int mode,
+                        void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,8 @@ F32, BF16 = 0, 1
 STATUS = {0: "LNPEGN_OK", 1: "LNPEGN_EINVAL", 2: "LNPEGN_EUNSUPPORTED", 3: "LNPEGN_EWORKSPACE",
           4: "LNPEGN_EHIP"}
 EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "ln_fwd_stats", "ln_bwd",
-           "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning")
+           "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning", "lnpegn_set_profile_events",
+           "lnpegn_stream_probe")
 
 _lib = None
 
@@ -49,7 +50,10 @@ def load() -> ctypes.CDLL:
     lib.ln_bwd_pegn.argtypes = [vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, i, i, i, i, i, f, vp, sz, vp]
     lib.gns_estimate.argtypes = [fp, fp, i, i, f, fp, vp]
     lib.lnpegn_set_tuning.argtypes = [i, i]
-    for name in ("ln_fwd_stats", "ln_bwd", "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning"):
+    lib.lnpegn_set_profile_events.argtypes = [vp, vp]
+    lib.lnpegn_stream_probe.argtypes = [vp, vp, vp, sz, i, vp]
+    for name in ("ln_fwd_stats", "ln_bwd", "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning",
+                 "lnpegn_set_profile_events", "lnpegn_stream_probe"):
         getattr(lib, name).restype = i
     _lib = lib
     return lib
@@ -98,6 +102,22 @@ def set_tuning(key: int, value: int) -> None:
     rc = load().lnpegn_set_tuning(key, value)
     if rc:
         raise LnpegnError("lnpegn_set_tuning", rc)
+
+
+def set_profile_events(start_event, stop_event) -> None:
+    """Arm (or with two Nones disarm) the one-shot hipEvent pair around the next row kernel.
+    Events are raw hipEvent_t handles (integers or ctypes void pointers)."""
+    rc = load().lnpegn_set_profile_events(start_event, stop_event)
+    if rc:
+        raise LnpegnError("lnpegn_set_profile_events", rc)
+
+
+def stream_probe(a, b, out, mode: int, stream=None) -> None:
+    """Streaming yardstick kernel: out = a (mode 0) or a XOR b (mode 1) over equal-sized buffers."""
+    nbytes = out.numel() * out.element_size()
+    rc = load().lnpegn_stream_probe(_ptr(a), _ptr(b), _ptr(out), nbytes, mode, _stream(stream))
+    if rc:
+        raise LnpegnError("lnpegn_stream_probe", rc)
 
 
 def ln_fwd_stats(x, eps: float, mean=None, rstd=None, stream=None):

@@ -1,6 +1,7 @@
 // C ABI of the lnpegn library (declared in include/lnpegn.h): argument validation, launch
 // planning and kernel launches.  No allocation, no synchronisation, no state between calls
 // apart from the process-wide launch-shape overrides of lnpegn_set_tuning().
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -15,6 +16,9 @@ namespace {
 int g_chunks_pegn = 0;
 int g_chunks_plain = 0;
 int g_waves = 0;
+// one-shot profiling events around the row kernel (null = disarmed)
+hipEvent_t g_ev_start = nullptr;
+hipEvent_t g_ev_stop = nullptr;
 
 constexpr int kDefaultChunks = 1024;
 constexpr int kMaxChunks = 16384;
@@ -69,7 +73,7 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn)
             p.waves = ceil_div(p.nvec, 64 * vpt_max);
             p.vpt = ceil_div(p.nvec, 64 * p.waves);
             p.max_threads = p.waves <= 4 ? 256 : 512;
-            p.lds_bytes = 2 * 5 * 16 * sizeof(float);
+            p.lds_bytes = (2 * 4 * 16 + 16) * sizeof(float);
         }
     }
     int target = pegn ? g_chunks_pegn : g_chunks_plain;
@@ -112,33 +116,54 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // ------------------------------------------------------------------------------------------
 // row kernel dispatch
 // ------------------------------------------------------------------------------------------
-template <typename T, int kVpt, bool kSaved>
-hipError_t launch_rows_vpt(const Plan &p, const RowArgs &a, hipStream_t s)
+// One launch of a row kernel.  When profiling events are armed they are attached to this very
+// dispatch, so their elapsed time is the kernel's own execution time.
+struct RowLaunch {
+    hipStream_t stream;
+    hipEvent_t ev_start, ev_stop;
+};
+
+template <typename K>
+hipError_t launch_row_kernel(K kernel, dim3 grid, dim3 block, size_t lds, const RowLaunch &rl,
+                             const RowArgs &a)
 {
-    const dim3 grid((unsigned)p.n_slots), block(64 * p.waves);
-    if (!p.multi)
-        ln_bwd_rows_kernel<T, kVpt, kSaved, false, 256><<<grid, block, p.lds_bytes, s>>>(a);
-    else if (p.max_threads == 256)
-        ln_bwd_rows_kernel<T, kVpt, kSaved, true, 256><<<grid, block, p.lds_bytes, s>>>(a);
-    else
-        ln_bwd_rows_kernel<T, kVpt, kSaved, true, 512><<<grid, block, p.lds_bytes, s>>>(a);
+    if (rl.ev_start) {
+        RowArgs copy = a;
+        void *args[] = {&copy};
+        return hipExtLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, args, lds,
+                                  rl.stream, rl.ev_start, rl.ev_stop, 0);
+    }
+    kernel<<<grid, block, lds, rl.stream>>>(a);
     return hipGetLastError();
 }
 
-template <typename T, bool kSaved>
-hipError_t launch_rows(const Plan &p, bool fast, const RowArgs &a, hipStream_t s)
+template <typename T, int kVpt, bool kSaved>
+hipError_t launch_rows_vpt(const Plan &p, const RowArgs &a, const RowLaunch &rl)
 {
-    if (!fast) {
-        ln_bwd_rows_generic_kernel<T, kSaved><<<dim3((unsigned)p.n_slots), dim3(256), 0, s>>>(a);
-        return hipGetLastError();
-    }
+    const dim3 grid((unsigned)p.n_slots), block(64 * p.waves);
+    if (!p.multi)
+        return launch_row_kernel(ln_bwd_rows_kernel<T, kVpt, kSaved, false, 256>, grid, block,
+                                 p.lds_bytes, rl, a);
+    if (p.max_threads == 256)
+        return launch_row_kernel(ln_bwd_rows_kernel<T, kVpt, kSaved, true, 256>, grid, block,
+                                 p.lds_bytes, rl, a);
+    return launch_row_kernel(ln_bwd_rows_kernel<T, kVpt, kSaved, true, 512>, grid, block, p.lds_bytes,
+                             rl, a);
+}
+
+template <typename T, bool kSaved>
+hipError_t launch_rows(const Plan &p, bool fast, const RowArgs &a, const RowLaunch &rl)
+{
+    if (!fast)
+        return launch_row_kernel(ln_bwd_rows_generic_kernel<T, kSaved>, dim3((unsigned)p.n_slots),
+                                 dim3(256), 0, rl, a);
     // at most 16 elements per lane: 2 vectors of 8 bf16, 4 vectors of 4 fp32
     if constexpr (Vec<T>::kElems == 4) {
-        if (p.vpt == 3) return launch_rows_vpt<T, 3, kSaved>(p, a, s);
-        if (p.vpt == 4) return launch_rows_vpt<T, 4, kSaved>(p, a, s);
+        if (p.vpt == 3) return launch_rows_vpt<T, 3, kSaved>(p, a, rl);
+        if (p.vpt == 4) return launch_rows_vpt<T, 4, kSaved>(p, a, rl);
     }
-    if (p.vpt == 1) return launch_rows_vpt<T, 1, kSaved>(p, a, s);
-    if (p.vpt == 2) return launch_rows_vpt<T, 2, kSaved>(p, a, s);
+    if (p.vpt == 1) return launch_rows_vpt<T, 1, kSaved>(p, a, rl);
+    if (p.vpt == 2) return launch_rows_vpt<T, 2, kSaved>(p, a, rl);
     return hipErrorInvalidValue;
 }
 
@@ -175,18 +200,20 @@ int run_bwd(bool pegn, const void *x, const void *dy, const void *gamma, const f
     double *part_s = reinterpret_cast<double *>(ws + p.off_part_s);
     double *part_big = reinterpret_cast<double *>(ws + p.off_part_big);
 
-    const bool fast = p.fast && aligned16(x) && aligned16(dy) && aligned16(dx);
+    const bool fast = p.fast && aligned16(x) && aligned16(dy) && aligned16(dx) && aligned16(gamma);
     RowArgs a{};
     a.x = x; a.dy = dy; a.gamma = gamma; a.mean = mean; a.rstd = rstd; a.dx = dx;
-    a.part = part; a.Tp = p.Tp; a.C = p.C; a.D = D; a.nvec = p.nvec;
+    a.part = part; a.Tp = p.Tp; a.stagger = pegn ? (T / B > 0 ? T / B : 1) : 0; a.C = p.C; a.D = D; a.nvec = p.nvec;
     a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.eps = eps; a.inv_D = 1.0f / (float)D;
 
     hipError_t e;
     const bool saved = mean != nullptr;
+    const RowLaunch rl{s, g_ev_start, g_ev_stop};
+    g_ev_start = g_ev_stop = nullptr;
     if (dt == LNPEGN_BF16)
-        e = saved ? launch_rows<bf16_t, true>(p, fast, a, s) : launch_rows<bf16_t, false>(p, fast, a, s);
+        e = saved ? launch_rows<bf16_t, true>(p, fast, a, rl) : launch_rows<bf16_t, false>(p, fast, a, rl);
     else
-        e = saved ? launch_rows<float, true>(p, fast, a, s) : launch_rows<float, false>(p, fast, a, s);
+        e = saved ? launch_rows<float, true>(p, fast, a, rl) : launch_rows<float, false>(p, fast, a, rl);
     if (e != hipSuccess) return LNPEGN_EHIP;
 
     // ---- upper levels: fixed-order sums of the chunk vectors ----
@@ -219,6 +246,34 @@ int run_bwd(bool pegn, const void *x, const void *dy, const void *gamma, const f
         if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
     }
     return LNPEGN_OK;
+}
+
+// Streaming yardstick: every lane moves 4 x 16 bytes per array, one workgroup per 16 KiB.
+template <int kMode>
+__global__ __launch_bounds__(256) void stream_probe_kernel(const uint4 *a, const uint4 *b, uint4 *out,
+                                                           int64_t nvec)
+{
+    const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+    uint4 va[4], vb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t v = base + i * 256;
+        if (v < nvec) {
+            va[i] = a[v];
+            if (kMode == 1) vb[i] = b[v];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t v = base + i * 256;
+        if (v < nvec) {
+            uint4 o = va[i];
+            if (kMode == 1) {
+                o.x ^= vb[i].x; o.y ^= vb[i].y; o.z ^= vb[i].z; o.w ^= vb[i].w;
+            }
+            out[v] = o;
+        }
+    }
 }
 
 template <typename T>
@@ -345,6 +400,35 @@ int lnpegn_set_tuning(int key, int value)
             return LNPEGN_OK;
         default: return LNPEGN_EINVAL;
     }
+}
+
+int lnpegn_stream_probe(const void *a, const void *b, void *out, size_t bytes, int mode, void *stream)
+{
+    if (!a || !out || (mode == 1 && !b) || bytes == 0 || bytes % 16) return LNPEGN_EINVAL;
+    if (mode != 0 && mode != 1) return LNPEGN_EINVAL;
+    if (!aligned16(a) || !aligned16(out) || (mode == 1 && !aligned16(b))) return LNPEGN_EINVAL;
+    const int64_t nvec = (int64_t)(bytes / 16);
+    const int64_t blocks = (nvec + 1023) / 1024;
+    if (blocks > INT32_MAX) return LNPEGN_EINVAL;
+    hipEvent_t ev_start = g_ev_start, ev_stop = g_ev_stop;
+    g_ev_start = g_ev_stop = nullptr;
+    const uint4 *pa = static_cast<const uint4 *>(a), *pb = static_cast<const uint4 *>(b);
+    uint4 *po = static_cast<uint4 *>(out);
+    int64_t n = nvec;
+    void *args[] = {&pa, &pb, &po, &n};
+    const void *fn = mode == 0 ? reinterpret_cast<const void *>(stream_probe_kernel<0>)
+                               : reinterpret_cast<const void *>(stream_probe_kernel<1>);
+    const hipError_t e = hipExtLaunchKernel(fn, dim3((unsigned)blocks), dim3(256), args, 0,
+                                            static_cast<hipStream_t>(stream), ev_start, ev_stop, 0);
+    return e == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+}
+
+int lnpegn_set_profile_events(void *start_event, void *stop_event)
+{
+    if ((start_event == nullptr) != (stop_event == nullptr)) return LNPEGN_EINVAL;
+    g_ev_start = static_cast<hipEvent_t>(start_event);
+    g_ev_stop = static_cast<hipEvent_t>(stop_event);
+    return LNPEGN_OK;
 }
 
 }  // extern "C"

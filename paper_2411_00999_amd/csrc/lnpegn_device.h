@@ -50,6 +50,31 @@ __device__ __forceinline__ void wave_sum2(float &a, float &b)
     b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, b), 63));
 }
 
+__device__ __forceinline__ void wave_sum3(float &a, float &b, float &c)
+{
+    a += dpp_take<0xB1, 0xf>(a);
+    b += dpp_take<0xB1, 0xf>(b);
+    c += dpp_take<0xB1, 0xf>(c);
+    a += dpp_take<0x4E, 0xf>(a);
+    b += dpp_take<0x4E, 0xf>(b);
+    c += dpp_take<0x4E, 0xf>(c);
+    a += dpp_take<0x141, 0xf>(a);
+    b += dpp_take<0x141, 0xf>(b);
+    c += dpp_take<0x141, 0xf>(c);
+    a += dpp_take<0x140, 0xf>(a);
+    b += dpp_take<0x140, 0xf>(b);
+    c += dpp_take<0x140, 0xf>(c);
+    a += dpp_take<0x142, 0xa>(a);
+    b += dpp_take<0x142, 0xa>(b);
+    c += dpp_take<0x142, 0xa>(c);
+    a += dpp_take<0x143, 0xc>(a);
+    b += dpp_take<0x143, 0xc>(b);
+    c += dpp_take<0x143, 0xc>(c);
+    a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a), 63));
+    b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, b), 63));
+    c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, c), 63));
+}
+
 __device__ __forceinline__ double wave_sum_f64(double v)
 {
     // fp64 is only used in the small finalize kernels: plain shuffles are fine there

@@ -2,9 +2,11 @@
 // column sums  A_gamma[k] = sum_t dy*xhat,  A_beta[k] = sum_t dy  over one chunk of rows.
 //
 // Work partition.  The N = B*T rows are cut into `n_slots` chunks.  For the per-example path
-// chunks never straddle an example: example b owns chunks [b*C, (b+1)*C), so the per-example
-// sums of Appendix B steps 1 and 5 are sums of whole chunks.  The plain backward uses the same
-// kernels with the whole tensor declared as one "example" (Bp = 1, Tp = N).
+// chunks never straddle an example: example b owns chunks [b*C, (b+1)*C) and chunk j of it
+// takes rows j, j+C, j+2C, ... of that example, so the per-example sums of Appendix B steps 1
+// and 5 are sums of whole chunks and the workgroups of an example sweep one moving window of
+// memory together.  The plain backward uses the same kernels with the whole tensor declared
+// as one "example" (Bp = 1, Tp = N).
 //
 // Lane mapping.  A lane owns the same columns for every row it touches, so the sums over t
 // live in registers and never move between lanes; only the per-row scalars (mean, variance,
@@ -28,6 +30,7 @@ struct RowArgs {
     void *dx;
     float *part;        // [n_slots][2][D] fp32 column sums per chunk
     int64_t Tp;         // rows per partition example
+    int64_t stagger;    // example b starts its sweep at row (b*stagger) mod Tp of itself
     int C;              // chunks per partition example
     int D;
     int nvec;           // D / elements-per-vector
@@ -36,6 +39,49 @@ struct RowArgs {
     float inv_D;
 };
 
+// gamma for one 16-byte row vector, as fp32 (gamma may be stored in either type)
+template <typename T>
+__device__ __forceinline__ void load_gamma_vec(const void *gamma, int gamma_is_f32, int v,
+                                               float (&g)[Vec<T>::kElems])
+{
+    constexpr int E = Vec<T>::kElems;
+    if (gamma_is_f32) {
+        const float4 *p = static_cast<const float4 *>(gamma) + (int64_t)v * (E / 4);
+#pragma unroll
+        for (int q = 0; q < E / 4; ++q) {
+            const float4 t = p[q];
+            g[4 * q] = t.x; g[4 * q + 1] = t.y; g[4 * q + 2] = t.z; g[4 * q + 3] = t.w;
+        }
+    } else if constexpr (E == 8) {
+        Vec<bf16_t>::unpack(static_cast<const uint4 *>(gamma)[v], g);
+    } else {
+        const uint2 t = static_cast<const uint2 *>(gamma)[v];
+        g[0] = __builtin_bit_cast(float, t.x << 16);
+        g[1] = __builtin_bit_cast(float, t.x & 0xffff0000u);
+        g[2] = __builtin_bit_cast(float, t.y << 16);
+        g[3] = __builtin_bit_cast(float, t.y & 0xffff0000u);
+    }
+}
+
+// Valid elements owned by wave w (multi mode interleaves the waves inside 64*S-vector spans).
+template <int kVpt, int E>
+__device__ __forceinline__ int wave_valid_elems(int w, int nwaves, int nvec, bool multi)
+{
+    int n = 0;
+#pragma unroll
+    for (int k = 0; k < kVpt; ++k) {
+        const int left = nvec - (multi ? (k * nwaves + w) * kWave : k * kWave);
+        n += (left < 0 ? 0 : (left > kWave ? kWave : left)) * E;
+    }
+    return n;
+}
+
+// Row statistics with ONE cross-lane/cross-wave exchange per row.  Inside a wave the mean and
+// the centred second moment are taken in two passes over registers (exact, no E[x^2]-mu^2);
+// the waves of a row then merge (sum, M2) pairs with the pairwise-merge identity
+//   M2 = sum_w M2_w + n_w (mean_w - mean)^2,
+// and sum_d dyh*(x-mean) = sum_w [ sum dyh*(x-mean_w) + (mean_w-mean) sum dyh ]
+// so the wave mean is only a pivot and the result does not lose digits to a large |mean|.
 template <typename T, int kVpt, bool kSaved, bool kMulti, int kMaxThreads>
 __global__ __launch_bounds__(kMaxThreads) void ln_bwd_rows_kernel(RowArgs a)
 {
@@ -49,29 +95,58 @@ __global__ __launch_bounds__(kMaxThreads) void ln_bwd_rows_kernel(RowArgs a)
     const int nwaves = blockDim.x >> 6;
     const int64_t chunk = blockIdx.x;
     const int64_t b = chunk / a.C, j = chunk - b * a.C;
-    const int64_t r0 = b * a.Tp + (j * a.Tp) / a.C;
-    const int64_t r1 = b * a.Tp + ((j + 1) * a.Tp) / a.C;
+    // chunk j of example b owns rows  b*Tp + j + i*C : the chunks of an example sweep it together.
+    // Examples sit a power of two apart in memory; starting each sweep at a different row
+    // (wrapping around) keeps the concurrent sweeps on different HBM channels.
+    const int64_t row_base = b * a.Tp;
+    const int64_t t_end = a.Tp;
+    const int64_t t_rot = (b * a.stagger) % a.Tp;
 
-    // vector index of slot k: multi mode interleaves the waves inside each 64*S-vector span
     int vidx[kVpt];
     bool ok[kVpt];
-    int n_valid = 0;  // valid elements of this wave (uniform)
 #pragma unroll
     for (int k = 0; k < kVpt; ++k) {
-        const int first = kMulti ? (k * nwaves + wave) * kWave : k * kWave;
-        vidx[k] = first + lane;
+        vidx[k] = (kMulti ? (k * nwaves + wave) * kWave : k * kWave) + lane;
         ok[k] = vidx[k] < a.nvec;
-        const int left = a.nvec - first;
-        n_valid += (left < 0 ? 0 : (left > kWave ? kWave : left)) * E;
     }
-    const float inv_nw = 1.0f / (float)n_valid;
+    const float inv_nw = 1.0f / (float)wave_valid_elems<kVpt, E>(wave, nwaves, a.nvec, kMulti);
+
+    const Raw *xv = static_cast<const Raw *>(a.x);
+    const Raw *dyv = static_cast<const Raw *>(a.dy);
+    Raw *dxv = static_cast<Raw *>(a.dx);
+
+    // loads are unconditional (index clamped to a valid vector); padded lanes are zeroed on unpack
+    auto rotated = [&](int64_t tt) {
+        const int64_t u = tt + t_rot;
+        return row_base + (u >= t_end ? u - t_end : u);
+    };
+    auto load_row = [&](int64_t tt, Raw (&xr)[kVpt], Raw (&dr)[kVpt]) {
+        const int64_t rr = rotated(tt);
+        const Raw *xrow = xv + rr * a.nvec;
+        const Raw *drow = dyv + rr * a.nvec;
+#pragma unroll
+        for (int k = 0; k < kVpt; ++k) {
+            const int v = ok[k] ? vidx[k] : 0;
+            xr[k] = xrow[v];
+            dr[k] = drow[v];
+        }
+    };
+
+    // first row on its way before anything else is fetched
+    const int64_t step = (int64_t)a.C * (kMulti ? 1 : nwaves);
+    int64_t t = j + (kMulti ? 0 : (int64_t)wave * a.C);
+    Raw xa[kVpt], da[kVpt], xb[kVpt], db[kVpt];
+    if (t < t_end) load_row(t, xa, da);
 
     float gm[kVpt][E];
 #pragma unroll
-    for (int k = 0; k < kVpt; ++k)
+    for (int k = 0; k < kVpt; ++k) {
+        load_gamma_vec<T>(a.gamma, a.gamma_is_f32, ok[k] ? vidx[k] : 0, gm[k]);
+        if (!ok[k]) {
 #pragma unroll
-        for (int e = 0; e < E; ++e)
-            gm[k][e] = ok[k] ? load_gamma(a.gamma, a.gamma_is_f32, (int64_t)vidx[k] * E + e) : 0.f;
+            for (int e = 0; e < E; ++e) gm[k][e] = 0.f;
+        }
+    }
 
     float acc_g[kVpt][E], acc_b[kVpt][E];
 #pragma unroll
@@ -79,133 +154,109 @@ __global__ __launch_bounds__(kMaxThreads) void ln_bwd_rows_kernel(RowArgs a)
 #pragma unroll
         for (int e = 0; e < E; ++e) acc_g[k][e] = acc_b[k][e] = 0.f;
 
-    const Raw *xv = static_cast<const Raw *>(a.x);
-    const Raw *dyv = static_cast<const Raw *>(a.dy);
-    Raw *dxv = static_cast<Raw *>(a.dx);
-
-    auto load_row = [&](int64_t r, Raw (&xr)[kVpt], Raw (&dr)[kVpt]) {
-        const Raw *xrow = xv + r * a.nvec;
-        const Raw *drow = dyv + r * a.nvec;
-#pragma unroll
-        for (int k = 0; k < kVpt; ++k) {
-            xr[k] = V::zero();
-            dr[k] = V::zero();
-            if (ok[k]) {
-                xr[k] = xrow[vidx[k]];
-                dr[k] = drow[vidx[k]];
-            }
-        }
-    };
-
-    // Exchange buffer of multi mode: [parity][5][16] floats; one barrier per exchange, the
-    // parity flip between rows keeps a fast wave from overwriting values still being read.
+    // Exchange buffer of multi mode: [parity][4][16] floats, then 16 floats of 1/n_w.  One
+    // barrier per row; the parity flip keeps a fast wave from overwriting values still being read.
+    float *nw_inv = lds + 2 * 4 * 16;
+    if constexpr (kMulti) {
+        if (lane == 0) nw_inv[wave] = inv_nw;
+    }
     int parity = 0;
 
-    auto process = [&](int64_t r, const Raw (&xr)[kVpt], const Raw (&dr)[kVpt]) {
+    auto process = [&](int64_t tt, const Raw (&xr)[kVpt], const Raw (&dr)[kVpt]) {
+        const int64_t r = rotated(tt);
         float xf[kVpt][E], df[kVpt][E];
 #pragma unroll
         for (int k = 0; k < kVpt; ++k) {
             V::unpack(xr[k], xf[k]);
             V::unpack(dr[k], df[k]);
+            if (!ok[k]) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) xf[k][e] = df[k][e] = 0.f;
+            }
         }
-        float *xchg = lds + parity * 5 * 16;
-        float mean, rstd, s_dyh = 0.f;
-#pragma unroll
-        for (int k = 0; k < kVpt; ++k)
-#pragma unroll
-            for (int e = 0; e < E; ++e) s_dyh += df[k][e] * gm[k][e];
-
+        // pass 1: pivot = the wave's own mean (or the saved row mean)
+        float s_x = 0.f, pivot;
         if constexpr (kSaved) {
-            mean = a.mean[r];
-            rstd = a.rstd[r];
+            pivot = a.mean[r];
         } else {
-            // two-pass statistics inside the wave
-            float s_x = 0.f;
 #pragma unroll
             for (int k = 0; k < kVpt; ++k)
 #pragma unroll
                 for (int e = 0; e < E; ++e) s_x += xf[k][e];
-            wave_sum2(s_x, s_dyh);
-            const float m_w = s_x * (kMulti ? inv_nw : a.inv_D);
-            float m2 = 0.f;
-#pragma unroll
-            for (int k = 0; k < kVpt; ++k)
-#pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    const float c = ok[k] ? xf[k][e] - m_w : 0.f;
-                    m2 += c * c;
-                }
-            m2 = wave_sum(m2);
-            if constexpr (kMulti) {
-                // merge the waves' (sum, M2) pairs: M2 = sum_w M2_w + n_w*(mean_w - mean)^2
-                if (lane == 0) {
-                    xchg[wave] = s_x;
-                    xchg[16 + wave] = m2;
-                    xchg[32 + wave] = s_dyh;
-                }
-                __syncthreads();
-                float tot = 0.f, tdy = 0.f;
-                for (int w = 0; w < nwaves; ++w) {
-                    tot += xchg[w];
-                    tdy += xchg[32 + w];
-                }
-                mean = tot * a.inv_D;
-                s_dyh = tdy;
-                float M2 = 0.f;
-                for (int w = 0; w < nwaves; ++w) {
-                    int nw = 0;
-#pragma unroll
-                    for (int k = 0; k < kVpt; ++k) {
-                        const int left = a.nvec - (k * nwaves + w) * kWave;
-                        nw += (left < 0 ? 0 : (left > kWave ? kWave : left)) * E;
-                    }
-                    const float d = xchg[w] / (float)nw - mean;
-                    M2 += xchg[16 + w] + (float)nw * d * d;
-                }
-                rstd = rsqrtf(M2 * a.inv_D + a.eps);
-            } else {
-                mean = m_w;
-                rstd = rsqrtf(m2 * a.inv_D + a.eps);
-            }
+            s_x = wave_sum(s_x);
+            pivot = s_x * (kMulti ? inv_nw : a.inv_D);
         }
-        // xhat; padded lanes stay at zero so they do not enter any sum
-        float s_dx = 0.f;
+        // pass 2: centre about the pivot; M2, sum dyh, sum dyh*xc
+        float m2 = 0.f, s_dyh = 0.f, s_dyx = 0.f;
 #pragma unroll
         for (int k = 0; k < kVpt; ++k)
 #pragma unroll
             for (int e = 0; e < E; ++e) {
-                xf[k][e] = ok[k] ? (xf[k][e] - mean) * rstd : 0.f;
-                s_dx += df[k][e] * gm[k][e] * xf[k][e];
+                const float xc = ok[k] ? xf[k][e] - pivot : 0.f;
+                const float dyh = df[k][e] * gm[k][e];
+                xf[k][e] = xc;
+                s_dyh += dyh;
+                s_dyx += dyh * xc;
+                if constexpr (!kSaved) m2 += xc * xc;
             }
         if constexpr (kSaved) {
-            wave_sum2(s_dx, s_dyh);
+            wave_sum2(s_dyh, s_dyx);
         } else {
-            s_dx = wave_sum(s_dx);
+            wave_sum3(m2, s_dyh, s_dyx);
         }
+        float rstd, shift = 0.f;
         if constexpr (kMulti) {
+            float *xchg = lds + parity * 4 * 16;
             if (lane == 0) {
-                xchg[48 + wave] = s_dx;
-                if constexpr (kSaved) xchg[64 + wave] = s_dyh;
+                xchg[wave] = s_dyh;
+                xchg[16 + wave] = s_dyx;
+                if constexpr (!kSaved) {
+                    xchg[32 + wave] = s_x;
+                    xchg[48 + wave] = m2;
+                }
             }
             __syncthreads();
-            float t0 = 0.f, t1 = 0.f;
-            for (int w = 0; w < nwaves; ++w) {
-                t0 += xchg[48 + w];
-                if constexpr (kSaved) t1 += xchg[64 + w];
+            if constexpr (kSaved) {
+                float t0 = 0.f, t1 = 0.f;
+                for (int w = 0; w < nwaves; ++w) {
+                    t0 += xchg[w];
+                    t1 += xchg[16 + w];
+                }
+                s_dyh = t0;
+                s_dyx = t1;
+                rstd = a.rstd[r];
+            } else {
+                float tot = 0.f;
+                for (int w = 0; w < nwaves; ++w) tot += xchg[32 + w];
+                const float mean = tot * a.inv_D;
+                float M2 = 0.f, t0 = 0.f, t1 = 0.f;
+                for (int w = 0; w < nwaves; ++w) {
+                    const float inw = nw_inv[w];
+                    const float d = xchg[32 + w] * inw - mean;   // mean_w - mean
+                    M2 += xchg[48 + w] + d * d / inw;
+                    t0 += xchg[w];
+                    t1 += xchg[16 + w] + d * xchg[w];
+                }
+                s_dyh = t0;
+                s_dyx = t1;
+                shift = pivot - mean;
+                rstd = rsqrtf(M2 * a.inv_D + a.eps);
             }
-            s_dx = t0;
-            if constexpr (kSaved) s_dyh = t1;
+        } else {
+            if constexpr (kSaved) rstd = a.rstd[r];
+            else rstd = rsqrtf(m2 * a.inv_D + a.eps);
         }
-        // dx = rstd*(dyh - c2 - xhat*c1)
-        const float k1 = -rstd * s_dx * a.inv_D, k2 = -rstd * s_dyh * a.inv_D;
+        // pass 3: dx = rstd*(dyh - c2 - xhat*c1), c1 = rstd*mean_d(dyh*(x-mean)), c2 = mean_d(dyh)
+        const float k1 = -rstd * rstd * s_dyx * a.inv_D, k2 = -rstd * s_dyh * a.inv_D;
         Raw *orow = dxv + r * a.nvec;
 #pragma unroll
         for (int k = 0; k < kVpt; ++k) {
             float o[E];
 #pragma unroll
             for (int e = 0; e < E; ++e) {
-                o[e] = (df[k][e] * gm[k][e]) * rstd + (xf[k][e] * k1 + k2);
-                acc_g[k][e] += df[k][e] * xf[k][e];
+                const float xhat = kMulti && !kSaved ? (xf[k][e] + shift) * rstd : xf[k][e] * rstd;
+                o[e] = (df[k][e] * gm[k][e]) * rstd + (xhat * k1 + k2);
+                acc_g[k][e] += df[k][e] * xhat;
                 acc_b[k][e] += df[k][e];
             }
             if (ok[k]) orow[vidx[k]] = V::pack(o);
@@ -213,19 +264,15 @@ __global__ __launch_bounds__(kMaxThreads) void ln_bwd_rows_kernel(RowArgs a)
         parity ^= 1;
     };
 
-    // two register buffers, loads for the next row are in flight while the current one is reduced
-    const int64_t step = kMulti ? 1 : nwaves;
-    int64_t r = r0 + (kMulti ? 0 : wave);
-    Raw xa[kVpt], da[kVpt], xb[kVpt], db[kVpt];
-    if (r < r1) load_row(r, xa, da);
-    while (r < r1) {
-        if (r + step < r1) load_row(r + step, xb, db);
-        process(r, xa, da);
-        r += step;
-        if (r >= r1) break;
-        if (r + step < r1) load_row(r + step, xa, da);
-        process(r, xb, db);
-        r += step;
+    // two register buffers: the next row's loads are in flight while the current row is reduced
+    while (t < t_end) {
+        if (t + step < t_end) load_row(t + step, xb, db);
+        process(t, xa, da);
+        t += step;
+        if (t >= t_end) break;
+        if (t + step < t_end) load_row(t + step, xa, da);
+        process(t, xb, db);
+        t += step;
     }
 
     // ---- hand the chunk's column sums to the workspace ----

@@ -247,11 +247,12 @@ def test_full_size_workloads(cfg):
     got, want = _gns_both(res, ref, inp.B)
     _check_gns(got, want, inp.B)
     if cfg == 4:
-        # half of the examples are copies of example 0: their norms coincide exactly, and S
-        # equals the closed form  [ n/2 |a-ubar|^2 + sum_i |u_i-ubar|^2 ] / (2n-1)
+        # half of the examples are copies of example 0: their norms coincide (up to the order
+        # of the fp32 sums, which depends on where each example's sweep starts), and S equals
+        # the closed form  [ n/2 |a-ubar|^2 + sum_i |u_i-ubar|^2 ] / (2n-1)
         n = inp.B // 2
-        assert np.all(res["s_gamma"][:n] == res["s_gamma"][0])
-        assert np.all(res["s_beta"][:n] == res["s_beta"][0])
+        np.testing.assert_allclose(res["s_gamma"][:n], res["s_gamma"][0], rtol=2e-6)
+        np.testing.assert_allclose(res["s_beta"][:n], res["s_beta"][0], rtol=2e-6)
         o = oracle.ln_bwd_pegn(inp.x, inp.dy, inp.gamma, inp.eps, want_dx=False)
         g = inp.B * np.concatenate([o["pe_gamma"], o["pe_beta"]], axis=1)
         a, u = g[0], g[n:]
