@@ -120,8 +120,8 @@ int gns_estimate(const float *pe_sq, const float *big_sq, int n_groups, int B, f
  * Benchmarking aid.  Overrides launch-shape heuristics process-wide; it never changes results
  * beyond floating-point summation order.  key 0: target number of row chunks of ln_bwd_pegn
  * (0 = automatic); key 1: the same for ln_bwd; key 2: waves per workgroup of the row kernel
- * when one wave owns a row (0 = automatic, else 1..16).  Returns LNPEGN_EINVAL for an unknown key or a
- * value out of range.  Not thread-safe against concurrent launches.
+ * (0 = automatic, else 1..16); key 3: rows between the sweep starts of consecutive examples,
+ * plus one (0 = automatic).  Returns LNPEGN_EINVAL for an unknown key or a value out of range.  Not thread-safe against concurrent launches.
  */
 int lnpegn_set_tuning(int key, int value);
 

@@ -16,13 +16,16 @@ namespace {
 int g_chunks_pegn = 0;
 int g_chunks_plain = 0;
 int g_waves = 0;
+int g_stagger = -1;   // rows between the sweep starts of consecutive examples (-1 = automatic)
 // one-shot profiling events around the row kernel (null = disarmed)
 hipEvent_t g_ev_start = nullptr;
 hipEvent_t g_ev_stop = nullptr;
 
-constexpr int kDefaultChunks = 1024;
 constexpr int kMaxChunks = 16384;
-constexpr int kFanIn = 32;          // vectors summed per workgroup in the upper reduction levels
+constexpr int kCUs = 256;           // MI355X
+constexpr int kGroups = 16;         // groups of chunks in the reduction when groups are not examples
+constexpr int64_t kSmallFinal = 131072;  // G1*D up to which one workgroup finishes the reduction
+constexpr int kMaxPeGroups = 256;   // above this many examples a chunk is a whole example
 constexpr size_t kAlign = 256;
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -31,79 +34,104 @@ inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 struct Plan {
     // row kernel
     bool fast;        // vectorised kernels usable (shape-wise; pointer alignment checked apart)
-    bool multi;       // several waves per row
+    bool sync;        // several waves per row
     int vpt;          // 16-byte vectors per lane
-    int waves;        // waves per workgroup
+    int S, R;         // waves per row, row groups per workgroup
     int max_threads;  // launch bound of the instantiation
     int nvec;
     int64_t Tp;       // rows per partition example
     int C;            // chunks per partition example
-    int64_t n_slots;  // Bp * C
+    int64_t n_slots;  // chunks in all
     size_t lds_bytes;
-    // reduction levels
+    // reduction
     int ntile;
-    int64_t MA, MB;   // vectors in the two ping-pong buffers
+    int gs, G1;       // chunks per group, groups
+    bool emit_pe;         // row kernel writes the per-example norms (a chunk is a whole example)
+    bool pe_from_groups;  // reduction kernel writes them (groups are examples)
     // workspace layout (byte offsets)
-    size_t off_part, off_bufA, off_bufB, off_part_s, off_part_big, total;
+    size_t off_part, off_grp, off_part_s, off_part_big, total;
 };
 
-Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn)
+// `vector_ok`: the 16-byte aligned fast kernels will run (else the generic kernel does).
+Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
 {
     Plan p{};
     const int E = dt == LNPEGN_BF16 ? 8 : 4;
     const int64_t N = (int64_t)B * T;
     const int vpt_max = 16 / E;                      // at most 16 elements per lane
-    p.fast = (D % E == 0) && (D / E <= 64 * vpt_max * 8);
+    p.fast = vector_ok && (D % E == 0) && (D / E <= 64 * vpt_max * 8);
     p.nvec = p.fast ? D / E : 0;
-    p.multi = false;
+    p.sync = false;
     p.vpt = 1;
-    p.waves = 4;
+    p.S = 1;
+    p.R = 4;
     p.max_threads = 256;
-    p.lds_bytes = 0;
+    int waves_per_simd = 4;                          // resident waves per SIMD to aim for
     if (p.fast) {
-        if (p.nvec <= 64 * vpt_max) {
-            p.vpt = ceil_div(p.nvec, 64);
-            const int lds_per_wave = 2 * p.vpt * E * kWave * (int)sizeof(float);
-            int w = g_waves > 0 ? g_waves : 4;
-            if (w > 4) w = 4;
-            p.waves = w;
-            p.lds_bytes = (size_t)w * lds_per_wave;
-        } else {
-            p.multi = true;
-            p.waves = ceil_div(p.nvec, 64 * vpt_max);
-            p.vpt = ceil_div(p.nvec, 64 * p.waves);
-            p.max_threads = p.waves <= 4 ? 256 : 512;
-            p.lds_bytes = (2 * 4 * 16 + 16) * sizeof(float);
-        }
+        p.S = ceil_div(p.nvec, 64 * vpt_max);
+        p.vpt = ceil_div(p.nvec, 64 * p.S);
+        p.sync = p.S > 1;
+        const int elems = p.vpt * E;                 // per lane
+        waves_per_simd = elems > 8 ? 2 : 4;          // measured: more waves of 16-element lanes only add contention
+        int R = g_waves > 0 ? g_waves / p.S : (p.S >= 4 ? 1 : 4 / p.S);
+        if (R < 1) R = 1;
+        while (R * p.S > 8) --R;
+        p.R = R;
+        p.max_threads = R * p.S <= 4 ? 256 : 512;
     }
+    const int nwaves = p.fast ? p.R * p.S : 4;
+    {
+        const size_t xchg = (size_t)((8 * nwaves + 2 * p.S + 3) & ~3) * sizeof(float);
+        const size_t merge = p.fast && p.R > 1 ? (size_t)nwaves * 2 * p.vpt * E * kWave * sizeof(float) : 0;
+        p.lds_bytes = xchg + (merge > 512 ? merge : 512);
+    }
+    // one full round of resident workgroups unless told otherwise
     int target = pegn ? g_chunks_pegn : g_chunks_plain;
-    if (target <= 0) target = kDefaultChunks;
-    const int rows_min = p.fast && !p.multi ? 2 * p.waves : 1;   // keep every wave busy
+    if (target <= 0) {
+        const int per_cu = (waves_per_simd * 4) / nwaves > 0 ? (waves_per_simd * 4) / nwaves : 1;
+        target = kCUs * per_cu;
+    }
+    const int rows_min = p.fast ? 2 * p.R : 1;       // keep every row group busy
+    const int R = p.fast ? p.R : 1;
+    // Prefer a chunk count that gives every chunk the same number of rows, a multiple of R: no
+    // partial last iteration.  Searched downwards, never below 3/4 of the first choice.
+    auto even_chunks = [&](int64_t c, int64_t rows) {
+        for (int64_t t = c; t >= 1 && 4 * t >= 3 * c; --t)
+            if (rows % (t * R) == 0) return t;
+        return c;
+    };
     if (pegn) {
         p.Tp = T;
-        int64_t c = target / B;
+        int64_t c = B > kMaxPeGroups ? 1 : target / B;
         const int64_t cmax = T / rows_min > 1 ? T / rows_min : 1;
         if (c > cmax) c = cmax;
         if (c < 1) c = 1;
-        p.C = (int)c;
+        p.C = (int)even_chunks(c, T);
         p.n_slots = (int64_t)B * p.C;
     } else {
         p.Tp = N;
         int64_t c = target;
         const int64_t cmax = N / rows_min > 1 ? N / rows_min : 1;
         if (c > cmax) c = cmax;
-        p.C = (int)c;
+        p.C = (int)even_chunks(c, N);
         p.n_slots = p.C;
     }
+    p.emit_pe = pegn && p.fast && p.C == 1;
+    p.pe_from_groups = pegn && !p.emit_pe;
+    if (p.pe_from_groups) {
+        p.gs = p.C;
+        p.G1 = B;
+    } else {
+        p.gs = ceil_div(p.n_slots, kGroups);
+        p.G1 = ceil_div(p.n_slots, p.gs);
+    }
     p.ntile = ceil_div(D, kTile);
-    p.MA = pegn ? B : ceil_div(p.n_slots, kFanIn);
-    p.MB = ceil_div(p.MA, kFanIn);
     const size_t vec_bytes = (size_t)2 * D * sizeof(float);
+    const size_t g_max = (size_t)(B > kGroups ? B : kGroups);   // layout does not depend on the path taken
     size_t off = 0;
     p.off_part = off;      off += align_up((size_t)p.n_slots * vec_bytes);
-    p.off_bufA = off;      off += align_up((size_t)p.MA * vec_bytes);
-    p.off_bufB = off;      off += align_up((size_t)p.MB * vec_bytes);
-    p.off_part_s = off;    off += align_up((size_t)B * p.ntile * 2 * sizeof(double));
+    p.off_grp = off;       off += align_up(g_max * vec_bytes);
+    p.off_part_s = off;    off += align_up(g_max * p.ntile * 2 * sizeof(double));
     p.off_part_big = off;  off += align_up((size_t)p.ntile * 2 * sizeof(double));
     p.total = off;
     return p;
@@ -140,21 +168,23 @@ hipError_t launch_row_kernel(K kernel, dim3 grid, dim3 block, size_t lds, const 
 template <typename T, int kVpt, bool kSaved>
 hipError_t launch_rows_vpt(const Plan &p, const RowArgs &a, const RowLaunch &rl)
 {
-    const dim3 grid((unsigned)p.n_slots), block(64 * p.waves);
-    if (!p.multi)
-        return launch_row_kernel(ln_bwd_rows_kernel<T, kVpt, kSaved, false, 256>, grid, block,
-                                 p.lds_bytes, rl, a);
+    const dim3 grid((unsigned)p.n_slots), block(64 * p.R * p.S);
+    const bool full = p.nvec == 64 * p.S * kVpt;
+    auto go = [&](auto kernel) { return launch_row_kernel(kernel, grid, block, p.lds_bytes, rl, a); };
+    if (!p.sync)
+        return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, false, true, 256>)
+                    : go(ln_bwd_rows_kernel<T, kVpt, kSaved, false, false, 256>);
     if (p.max_threads == 256)
-        return launch_row_kernel(ln_bwd_rows_kernel<T, kVpt, kSaved, true, 256>, grid, block,
-                                 p.lds_bytes, rl, a);
-    return launch_row_kernel(ln_bwd_rows_kernel<T, kVpt, kSaved, true, 512>, grid, block, p.lds_bytes,
-                             rl, a);
+        return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, true, true, 256>)
+                    : go(ln_bwd_rows_kernel<T, kVpt, kSaved, true, false, 256>);
+    return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, true, true, 512>)
+                : go(ln_bwd_rows_kernel<T, kVpt, kSaved, true, false, 512>);
 }
 
 template <typename T, bool kSaved>
-hipError_t launch_rows(const Plan &p, bool fast, const RowArgs &a, const RowLaunch &rl)
+hipError_t launch_rows(const Plan &p, const RowArgs &a, const RowLaunch &rl)
 {
-    if (!fast)
+    if (!p.fast)
         return launch_row_kernel(ln_bwd_rows_generic_kernel<T, kSaved>, dim3((unsigned)p.n_slots),
                                  dim3(256), 0, rl, a);
     // at most 16 elements per lane: 2 vectors of 8 bf16, 4 vectors of 4 fp32
@@ -165,15 +195,6 @@ hipError_t launch_rows(const Plan &p, bool fast, const RowArgs &a, const RowLaun
     if (p.vpt == 1) return launch_rows_vpt<T, 1, kSaved>(p, a, rl);
     if (p.vpt == 2) return launch_rows_vpt<T, 2, kSaved>(p, a, rl);
     return hipErrorInvalidValue;
-}
-
-hipError_t launch_col_sum(const float *src, int M, int gs, int D, float *dst0, float *dst1,
-                          int64_t dst_stride, double *part_sq, hipStream_t s)
-{
-    ColSumArgs c{src, dst0, dst1, part_sq, dst_stride, M, gs, D};
-    const dim3 grid((unsigned)ceil_div(M, gs), (unsigned)ceil_div(D, kTile));
-    col_sum_kernel<<<grid, dim3(kTile), 0, s>>>(c);
-    return hipGetLastError();
 }
 
 int run_bwd(bool pegn, const void *x, const void *dy, const void *gamma, const float *mean,
@@ -187,7 +208,9 @@ int run_bwd(bool pegn, const void *x, const void *dy, const void *gamma, const f
     if (pegn && (!pe_gamma_sq || !pe_beta_sq)) return LNPEGN_EINVAL;
     if ((mean == nullptr) != (rstd == nullptr)) return LNPEGN_EINVAL;
     if (dx == x) return LNPEGN_EINVAL;
-    const Plan p = make_plan(B, T, D, (lnpegn_dtype)dt, pegn);
+    if ((int64_t)B * T > INT32_MAX) return LNPEGN_EINVAL;   // row indices are 32-bit
+    const bool vector_ok = aligned16(x) && aligned16(dy) && aligned16(dx) && aligned16(gamma);
+    const Plan p = make_plan(B, T, D, (lnpegn_dtype)dt, pegn, vector_ok);
     if (!workspace || workspace_bytes < p.total) return LNPEGN_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return LNPEGN_EINVAL;
     if (p.n_slots > INT32_MAX) return LNPEGN_EINVAL;
@@ -195,55 +218,50 @@ int run_bwd(bool pegn, const void *x, const void *dy, const void *gamma, const f
     hipStream_t s = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
     float *part = reinterpret_cast<float *>(ws + p.off_part);
-    float *bufA = reinterpret_cast<float *>(ws + p.off_bufA);
-    float *bufB = reinterpret_cast<float *>(ws + p.off_bufB);
-    double *part_s = reinterpret_cast<double *>(ws + p.off_part_s);
-    double *part_big = reinterpret_cast<double *>(ws + p.off_part_big);
 
-    const bool fast = p.fast && aligned16(x) && aligned16(dy) && aligned16(dx) && aligned16(gamma);
     RowArgs a{};
     a.x = x; a.dy = dy; a.gamma = gamma; a.mean = mean; a.rstd = rstd; a.dx = dx;
-    a.part = part; a.Tp = p.Tp; a.stagger = pegn ? (T / B > 0 ? T / B : 1) : 0; a.C = p.C; a.D = D; a.nvec = p.nvec;
-    a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.eps = eps; a.inv_D = 1.0f / (float)D;
+    a.part = part; a.pe_gamma_sq = pe_gamma_sq; a.pe_beta_sq = pe_beta_sq;
+    a.Tp = p.Tp; a.stagger = !pegn ? 0 : g_stagger >= 0 ? g_stagger : (T / B > 0 ? T / B : 1); a.C = p.C; a.D = D; a.nvec = p.nvec;
+    a.S = p.S; a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.emit_pe = p.emit_pe;
+    a.eps = eps; a.inv_D = 1.0f / (float)D;
 
     hipError_t e;
     const bool saved = mean != nullptr;
     const RowLaunch rl{s, g_ev_start, g_ev_stop};
     g_ev_start = g_ev_stop = nullptr;
     if (dt == LNPEGN_BF16)
-        e = saved ? launch_rows<bf16_t, true>(p, fast, a, rl) : launch_rows<bf16_t, false>(p, fast, a, rl);
+        e = saved ? launch_rows<bf16_t, true>(p, a, rl) : launch_rows<bf16_t, false>(p, a, rl);
     else
-        e = saved ? launch_rows<float, true>(p, fast, a, rl) : launch_rows<float, false>(p, fast, a, rl);
+        e = saved ? launch_rows<float, true>(p, a, rl) : launch_rows<float, false>(p, a, rl);
     if (e != hipSuccess) return LNPEGN_EHIP;
 
-    // ---- upper levels: fixed-order sums of the chunk vectors ----
-    const int64_t vec = 2 * (int64_t)D;
-    const float *src = part;
-    int64_t M = p.n_slots;
-    float *ping = bufA, *pong = bufB;
-    if (pegn) {
-        // per-example sums (Appendix B steps 1, 5) and their squared norms per tile (steps 2, 6)
-        e = launch_col_sum(src, (int)M, p.C, D, ping, ping + D, vec, part_s, s);
-        if (e != hipSuccess) return LNPEGN_EHIP;
-        src = ping;
-        M = B;
-        float *t = ping; ping = pong; pong = t;
-    }
-    while (M > kFanIn) {
-        e = launch_col_sum(src, (int)M, kFanIn, D, ping, ping + D, vec, nullptr, s);
-        if (e != hipSuccess) return LNPEGN_EHIP;
-        src = ping;
-        M = ceil_div(M, kFanIn);
-        float *t = ping; ping = pong; pong = t;
-    }
-    // batch gradients (steps 3, 7) and, if asked for, their squared norms per tile
-    const bool want_big = pegn && big_sq != nullptr;
-    e = launch_col_sum(src, (int)M, (int)M, D, dgamma, dbeta, 0, want_big ? part_big : nullptr, s);
-    if (e != hipSuccess) return LNPEGN_EHIP;
-    if (pegn) {
-        ScalarsArgs sa{part_s, want_big ? part_big : nullptr, pe_gamma_sq, pe_beta_sq, big_sq, B, p.ntile};
-        scalars_kernel<<<dim3((unsigned)ceil_div(B > 2 ? B : 2, 256)), dim3(256), 0, s>>>(sa);
+    // ---- the levels above the chunks (fixed-order sums) ----
+    ReduceArgs ra{};
+    ra.part = part;
+    ra.grp = reinterpret_cast<float *>(ws + p.off_grp);
+    ra.part_s = reinterpret_cast<double *>(ws + p.off_part_s);
+    ra.part_big = reinterpret_cast<double *>(ws + p.off_part_big);
+    ra.dgamma = dgamma; ra.dbeta = dbeta;
+    ra.pe_gamma_sq = pe_gamma_sq; ra.pe_beta_sq = pe_beta_sq;
+    ra.big_sq = pegn ? big_sq : nullptr;
+    ra.n_slots = (int)p.n_slots; ra.gs = p.gs; ra.G1 = p.G1; ra.D = D; ra.ntile = p.ntile;
+    ra.pe_from_groups = p.pe_from_groups;
+    reduce_groups_kernel<<<dim3((unsigned)p.G1, (unsigned)p.ntile), dim3(kTile), 0, s>>>(ra);
+    if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    const bool need_scalars = p.pe_from_groups || ra.big_sq != nullptr;
+    if (p.G1 == 1 || (int64_t)p.G1 * D <= kSmallFinal) {
+        if (p.G1 > 1 || need_scalars) {
+            reduce_final_small_kernel<<<dim3(1), dim3(1024), 0, s>>>(ra);
+            if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        }
+    } else {
+        reduce_final_tiles_kernel<<<dim3((unsigned)p.ntile), dim3(kTile), 0, s>>>(ra);
         if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        if (need_scalars) {
+            reduce_scalars_kernel<<<dim3(1), dim3(256), 0, s>>>(ra);
+            if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        }
     }
     return LNPEGN_OK;
 }
@@ -325,9 +343,13 @@ extern "C" {
 size_t lnpegn_workspace_bytes(int B, int T, int D, lnpegn_dtype dt)
 {
     if (!shape_ok(B, T, D) || !dtype_ok(dt)) return 0;
-    const size_t a = make_plan(B, T, D, dt, true).total;
-    const size_t b = make_plan(B, T, D, dt, false).total;
-    return a > b ? a : b;
+    size_t need = 0;
+    for (int pegn = 0; pegn < 2; ++pegn)
+        for (int vec = 0; vec < 2; ++vec) {
+            const size_t t = make_plan(B, T, D, dt, pegn != 0, vec != 0).total;
+            if (t > need) need = t;
+        }
+    return need;
 }
 
 const char *lnpegn_status_string(int status)
@@ -397,6 +419,9 @@ int lnpegn_set_tuning(int key, int value)
         case 2:
             if (value > 16) return LNPEGN_EINVAL;
             g_waves = value;
+            return LNPEGN_OK;
+        case 3:
+            g_stagger = value == 0 ? -1 : value - 1;
             return LNPEGN_OK;
         default: return LNPEGN_EINVAL;
     }

@@ -1,94 +1,228 @@
 // Second level of the two-level deterministic reduction: sums of the per-chunk column sums,
 // the per-example squared norms (Appendix B steps 2 and 6), the batch gradients (steps 3
 // and 7) and the gradient-noise-scale estimator (Section 2.1, Eq. 3-5).  Every sum runs in a
-// fixed order, in fp64, so results do not depend on scheduling.
+// fixed order, in fp64, so results do not depend on scheduling.  The levels are separate
+// launches on purpose: a device-scope fence inside a kernel writes back and invalidates the
+// whole L2 of an XCD on this part, which costs more than a launch.
 #pragma once
 #include "lnpegn_device.h"
 
 namespace lnpegn {
 
-constexpr int kTile = 256;  // columns per workgroup in the column-sum kernels
+constexpr int kTile = 256;  // columns per workgroup
 
-struct ColSumArgs {
-    const float *src;   // [M][2][D]
-    float *dst0;        // group g, array 0 -> dst0 + g*dst_stride ; array 1 -> dst1 + g*dst_stride
-    float *dst1;
-    double *part_sq;    // [n_groups][ntile][2] sums of squares of the outputs per tile, or null
-    int64_t dst_stride;
-    int M;              // number of source vectors
-    int gs;             // vectors per group (last group may be short)
+struct ReduceArgs {
+    const float *part;     // [n_slots][2][D] column sums per chunk
+    float *grp;            // [G1][2][D] sums per group of chunks (per example when pe_from_groups)
+    double *part_s;        // [G1][ntile][2] per-group squared norms per tile (pe_from_groups)
+    double *part_big;      // [ntile][2] squared norms of the batch gradients per tile
+    float *dgamma;         // [D]
+    float *dbeta;          // [D]
+    float *pe_gamma_sq;    // [G1] (pe_from_groups)
+    float *pe_beta_sq;
+    float *big_sq;         // [2] or null
+    int n_slots;
+    int gs;                // chunks per group (the last group may be short)
+    int G1;                // number of groups
     int D;
+    int ntile;
+    int pe_from_groups;    // groups are examples: emit their squared norms (Appendix B steps 2, 6)
 };
 
-// grid (n_groups, ntile), 256 threads: thread = one column, sequential sum over the group.
-__global__ __launch_bounds__(kTile) void col_sum_kernel(ColSumArgs a)
+// These kernels are a handful of dependent memory round trips long, so every level issues its
+// loads in batches of eight before it adds them (in index order: the sums are reproducible).
+
+// Level 1.  grid (G1, ntile), 256 threads.  The four waves split the group's chunks, add them
+// in chunk order, then the waves' partial sums are added in wave order.  With a single group the
+// group sums ARE the batch gradients and go straight to dgamma / dbeta.
+__global__ __launch_bounds__(kTile) void reduce_groups_kernel(ReduceArgs a)
 {
+    __shared__ double wsum[4][8][kWave];   // [wave][array*4 + component][lane]
     __shared__ double slots[2][4];
-    const int k = blockIdx.y * kTile + threadIdx.x;
-    const int g = blockIdx.x;
-    const int m0 = g * a.gs;
-    const int m1 = min(m0 + a.gs, a.M);
-    double s0 = 0.0, s1 = 0.0;
-    if (k < a.D) {
-        const float *p = a.src + (int64_t)m0 * 2 * a.D + k;
-        int m = m0;
-        for (; m + 4 <= m1; m += 4) {   // four loads in flight, added in order
-            const float u0 = p[0], v0 = p[a.D];
-            const float u1 = p[2 * (int64_t)a.D], v1 = p[3 * (int64_t)a.D];
-            const float u2 = p[4 * (int64_t)a.D], v2 = p[5 * (int64_t)a.D];
-            const float u3 = p[6 * (int64_t)a.D], v3 = p[7 * (int64_t)a.D];
-            s0 = (((s0 + u0) + u1) + u2) + u3;
-            s1 = (((s1 + v0) + v1) + v2) + v3;
-            p += 8 * (int64_t)a.D;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x, tile = blockIdx.y;
+    const int col0 = tile * kTile;
+
+    const int m0 = g * a.gs, m1 = min(m0 + a.gs, a.n_slots);
+    const int per = (m1 - m0 + 3) / 4;
+    const int w0 = min(m0 + wave * per, m1), w1 = min(w0 + per, m1);
+    const int c4 = col0 + lane * 4;            // this lane's four columns
+    double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (c4 < a.D) {
+        const int64_t stride = 2 * (int64_t)a.D;
+        if ((a.D & 3) == 0) {                  // rows of the workspace are 16-byte aligned
+            for (int m = w0; m < w1; m += 8) {
+                float4 u[8], v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int mm = min(m + i, w1 - 1);
+                    const float *p = a.part + mm * stride + c4;
+                    u[i] = *reinterpret_cast<const float4 *>(p);
+                    v[i] = *reinterpret_cast<const float4 *>(p + a.D);
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    if (m + i < w1) {
+                        acc[0] += u[i].x; acc[1] += u[i].y; acc[2] += u[i].z; acc[3] += u[i].w;
+                        acc[4] += v[i].x; acc[5] += v[i].y; acc[6] += v[i].z; acc[7] += v[i].w;
+                    }
+                }
+            }
+        } else {                               // any D: element by element
+            const int nc = min(4, a.D - c4);
+            for (int m = w0; m < w1; ++m) {
+                const float *p = a.part + m * stride + c4;
+                for (int i = 0; i < nc; ++i) {
+                    acc[i] += p[i];
+                    acc[4 + i] += p[a.D + i];
+                }
+            }
         }
-        for (; m < m1; ++m) {
-            s0 += p[0];
-            s1 += p[a.D];
-            p += 2 * (int64_t)a.D;
-        }
-        a.dst0[(int64_t)g * a.dst_stride + k] = (float)s0;
-        a.dst1[(int64_t)g * a.dst_stride + k] = (float)s1;
     }
-    if (a.part_sq) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) wsum[wave][i][lane] = acc[i];
+    __syncthreads();
+    // thread -> one column of the tile
+    const int col = col0 + tid;
+    const int src_lane = tid >> 2, comp = tid & 3;
+    double v0 = 0.0, v1 = 0.0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        v0 += wsum[w][comp][src_lane];
+        v1 += wsum[w][4 + comp][src_lane];
+    }
+    const float f0 = (float)v0, f1 = (float)v1;
+    const bool single = a.G1 == 1;
+    if (col < a.D) {
+        if (single) {
+            a.dgamma[col] = f0;
+            a.dbeta[col] = f1;
+        } else {
+            a.grp[((int64_t)g * 2) * a.D + col] = f0;
+            a.grp[((int64_t)g * 2 + 1) * a.D + col] = f1;
+        }
+    }
+    if (a.pe_from_groups || single) {
         // squares of the values as stored (fp32), summed in fp64
-        const double f0 = (double)(float)s0, f1 = (double)(float)s1;
-        const double q0 = block_sum_f64(f0 * f0, slots[0]);
-        const double q1 = block_sum_f64(f1 * f1, slots[1]);
-        if (threadIdx.x == 0) {
-            double *o = a.part_sq + ((int64_t)g * gridDim.y + blockIdx.y) * 2;
-            o[0] = q0;
-            o[1] = q1;
+        const double q0 = block_sum_f64(col < a.D ? (double)f0 * f0 : 0.0, slots[0]);
+        const double q1 = block_sum_f64(col < a.D ? (double)f1 * f1 : 0.0, slots[1]);
+        if (tid == 0) {
+            if (a.pe_from_groups) {
+                a.part_s[((int64_t)g * a.ntile + tile) * 2] = q0;
+                a.part_s[((int64_t)g * a.ntile + tile) * 2 + 1] = q1;
+            }
+            if (single) {
+                a.part_big[tile * 2] = q0;
+                a.part_big[tile * 2 + 1] = q1;
+            }
         }
     }
 }
 
-struct ScalarsArgs {
-    const double *part_s;    // [B][ntile][2] or null
-    const double *part_big;  // [ntile][2] or null
-    float *pe_gamma_sq;      // [B]
-    float *pe_beta_sq;       // [B]
-    float *big_sq;           // [2] or null
-    int B;
-    int ntile;
-};
-
-// tiny: per-example tile partials -> s_gamma[b], s_beta[b]; tile partials -> ||dgamma||^2, ||dbeta||^2
-__global__ __launch_bounds__(256) void scalars_kernel(ScalarsArgs a)
+// Sum over the groups for one column (Appendix B steps 3, 7), groups added in order.
+__device__ __forceinline__ void sum_groups(const float *grp, int G1, int D, int col, double &s0,
+                                           double &s1)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (a.part_s && i < a.B) {
-        double g = 0.0, b = 0.0;
-        for (int t = 0; t < a.ntile; ++t) {
-            g += a.part_s[((int64_t)i * a.ntile + t) * 2];
-            b += a.part_s[((int64_t)i * a.ntile + t) * 2 + 1];
+    const int64_t stride = 2 * (int64_t)D;
+    s0 = s1 = 0.0;
+    for (int g = 0; g < G1; g += 8) {
+        float u[8], v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float *p = grp + min(g + i, G1 - 1) * stride + col;
+            u[i] = p[0];
+            v[i] = p[D];
         }
-        a.pe_gamma_sq[i] = (float)g;
-        a.pe_beta_sq[i] = (float)b;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (g + i < G1) {
+                s0 += u[i];
+                s1 += v[i];
+            }
+        }
     }
-    if (a.big_sq && a.part_big && i < 2) {
-        double s = 0.0;
-        for (int t = 0; t < a.ntile; ++t) s += a.part_big[t * 2 + i];
-        a.big_sq[i] = (float)s;
+}
+
+// Per-example and batch squared norms from their per-tile parts, tiles added in order.
+__device__ __forceinline__ void finish_scalars(const ReduceArgs &a, int tid, int nthreads)
+{
+    if (a.pe_from_groups) {
+        for (int b = tid; b < a.G1; b += nthreads) {
+            double sg = 0.0, sb = 0.0;
+            for (int t = 0; t < a.ntile; ++t) {
+                sg += a.part_s[((int64_t)b * a.ntile + t) * 2];
+                sb += a.part_s[((int64_t)b * a.ntile + t) * 2 + 1];
+            }
+            a.pe_gamma_sq[b] = (float)sg;
+            a.pe_beta_sq[b] = (float)sb;
+        }
+    }
+}
+
+// Levels 2 and 3 in ONE workgroup of 1024 threads, for shapes where the group sums are small
+// (G1*D <= 128K): dgamma, dbeta, their squared norms, and the per-example squared norms.
+__global__ __launch_bounds__(1024) void reduce_final_small_kernel(ReduceArgs a)
+{
+    __shared__ double slots[2][16];
+    const int tid = threadIdx.x;
+    double q0 = 0.0, q1 = 0.0;
+    if (a.G1 > 1) {
+        for (int col = tid; col < a.D; col += 1024) {
+            double s0, s1;
+            sum_groups(a.grp, a.G1, a.D, col, s0, s1);
+            const float f0 = (float)s0, f1 = (float)s1;
+            a.dgamma[col] = f0;
+            a.dbeta[col] = f1;
+            q0 += (double)f0 * f0;
+            q1 += (double)f1 * f1;
+        }
+    }
+    finish_scalars(a, tid, 1024);
+    if (a.big_sq) {
+        if (a.G1 > 1) {
+            q0 = block_sum_f64(q0, slots[0]);
+            q1 = block_sum_f64(q1, slots[1]);
+        } else if (tid < 2) {   // level 1 already left the per-tile parts
+            double t2 = 0.0;
+            for (int t = 0; t < a.ntile; ++t) t2 += a.part_big[t * 2 + tid];
+            if (tid == 0) q0 = t2;
+            else q1 = t2;
+        }
+        if (tid == 0) a.big_sq[0] = (float)q0;
+        if (tid == (a.G1 > 1 ? 0 : 1)) a.big_sq[1] = (float)q1;
+    }
+}
+
+// Level 2 for large shapes: grid ntile, 256 threads, one column per thread.
+__global__ __launch_bounds__(kTile) void reduce_final_tiles_kernel(ReduceArgs a)
+{
+    __shared__ double slots[2][4];
+    const int tid = threadIdx.x, tile = blockIdx.x;
+    const int col = tile * kTile + tid;
+    double s0 = 0.0, s1 = 0.0;
+    if (col < a.D) {
+        sum_groups(a.grp, a.G1, a.D, col, s0, s1);
+        a.dgamma[col] = (float)s0;
+        a.dbeta[col] = (float)s1;
+    }
+    const double d0 = (double)(float)s0, d1 = (double)(float)s1;
+    const double q0 = block_sum_f64(d0 * d0, slots[0]);
+    const double q1 = block_sum_f64(d1 * d1, slots[1]);
+    if (tid == 0) {
+        a.part_big[tile * 2] = q0;
+        a.part_big[tile * 2 + 1] = q1;
+    }
+}
+
+// Level 3 for large shapes: one workgroup.
+__global__ __launch_bounds__(256) void reduce_scalars_kernel(ReduceArgs a)
+{
+    const int tid = threadIdx.x;
+    finish_scalars(a, tid, 256);
+    if (a.big_sq && tid < 2) {
+        double t2 = 0.0;
+        for (int t = 0; t < a.ntile; ++t) t2 += a.part_big[t * 2 + tid];
+        a.big_sq[tid] = (float)t2;
     }
 }
 

@@ -1,22 +1,21 @@
 // Row-streaming kernels: the single pass over x and dy that writes dx and accumulates the
 // column sums  A_gamma[k] = sum_t dy*xhat,  A_beta[k] = sum_t dy  over one chunk of rows.
 //
-// Work partition.  The N = B*T rows are cut into `n_slots` chunks.  For the per-example path
-// chunks never straddle an example: example b owns chunks [b*C, (b+1)*C) and chunk j of it
-// takes rows j, j+C, j+2C, ... of that example, so the per-example sums of Appendix B steps 1
-// and 5 are sums of whole chunks and the workgroups of an example sweep one moving window of
-// memory together.  The plain backward uses the same kernels with the whole tensor declared
-// as one "example" (Bp = 1, Tp = N).
+// Work partition.  The N = B*T rows are cut into `n_slots` chunks, one workgroup each.  For the
+// per-example path chunks never straddle an example: example b owns chunks [b*C, (b+1)*C) and
+// chunk j of it takes rows j, j+C, j+2C, ... of that example, so the per-example sums of
+// Appendix B steps 1 and 5 are sums of whole chunks and the workgroups of an example sweep one
+// moving window of memory together.  The plain backward uses the same kernels with the whole
+// tensor declared as one "example" (Tp = N).
 //
 // Lane mapping.  A lane owns the same columns for every row it touches, so the sums over t
-// live in registers and never move between lanes; only the per-row scalars (mean, variance,
-// mean_d(dyh), mean_d(dyh*xhat)) cross lanes, on the DPP network.
-//   wave mode  (kMulti = false): one wave owns a row; the R waves of a workgroup take rows
-//                                r0+w, r0+w+R, ... and merge their column sums through LDS in
-//                                wave order at the end of the chunk.
-//   multi mode (kMulti = true) : all S waves of a workgroup share one row (wide D); each wave
-//                                owns different columns, per-row scalars cross waves through LDS.
+// live in registers and never move between lanes; only the per-row scalars cross lanes, on the
+// DPP network.  A workgroup is R row groups of S waves: the S waves of a group share a row
+// (each owns different columns, at most 16 per lane), the R groups take different rows and
+// merge their column sums through LDS in group order when the chunk is done.
 #pragma once
+#include <type_traits>
+
 #include "lnpegn_device.h"
 
 namespace lnpegn {
@@ -25,16 +24,20 @@ struct RowArgs {
     const void *x;
     const void *dy;
     const void *gamma;
-    const float *mean;  // may be null (recompute)
+    const float *mean;   // may be null (recompute)
     const float *rstd;
     void *dx;
-    float *part;        // [n_slots][2][D] fp32 column sums per chunk
-    int64_t Tp;         // rows per partition example
-    int64_t stagger;    // example b starts its sweep at row (b*stagger) mod Tp of itself
-    int C;              // chunks per partition example
+    float *part;         // [n_slots][2][D] fp32 column sums per chunk
+    float *pe_gamma_sq;  // [B], written here only when emit_pe
+    float *pe_beta_sq;
+    int64_t Tp;          // rows per partition example
+    int64_t stagger;     // example b starts its sweep at row (b*stagger) mod Tp of itself
+    int C;               // chunks per partition example
     int D;
-    int nvec;           // D / elements-per-vector
+    int nvec;            // D / elements-per-vector
+    int S;               // waves per row
     int gamma_is_f32;
+    int emit_pe;         // C == 1: a chunk is a whole example, its squared norms are final here
     float eps;
     float inv_D;
 };
@@ -63,14 +66,14 @@ __device__ __forceinline__ void load_gamma_vec(const void *gamma, int gamma_is_f
     }
 }
 
-// Valid elements owned by wave w (multi mode interleaves the waves inside 64*S-vector spans).
+// Valid elements owned by wave ws of a row group (the S waves interleave inside 64*S-vector spans).
 template <int kVpt, int E>
-__device__ __forceinline__ int wave_valid_elems(int w, int nwaves, int nvec, bool multi)
+__device__ __forceinline__ int wave_valid_elems(int ws, int S, int nvec)
 {
     int n = 0;
 #pragma unroll
     for (int k = 0; k < kVpt; ++k) {
-        const int left = nvec - (multi ? (k * nwaves + w) * kWave : k * kWave);
+        const int left = nvec - (k * S + ws) * kWave;
         n += (left < 0 ? 0 : (left > kWave ? kWave : left)) * E;
     }
     return n;
@@ -82,67 +85,77 @@ __device__ __forceinline__ int wave_valid_elems(int w, int nwaves, int nvec, boo
 //   M2 = sum_w M2_w + n_w (mean_w - mean)^2,
 // and sum_d dyh*(x-mean) = sum_w [ sum dyh*(x-mean_w) + (mean_w-mean) sum dyh ]
 // so the wave mean is only a pivot and the result does not lose digits to a large |mean|.
-template <typename T, int kVpt, bool kSaved, bool kMulti, int kMaxThreads>
-__global__ __launch_bounds__(kMaxThreads) void ln_bwd_rows_kernel(RowArgs a)
+//
+// kSync: S > 1, the waves of a row exchange their scalars through LDS (one barrier per row;
+// every wave of the workgroup takes part in every barrier, also a group that has run out of rows).
+// kFull: every lane owns kVpt valid vectors (nvec == 64*S*kVpt), so no padding logic is compiled.
+template <typename T, int kVpt, bool kSaved, bool kSync, bool kFull, int kMaxThreads>
+__global__ __launch_bounds__(kMaxThreads, (kVpt * Vec<T>::kElems > 8 ? 3 : 4))
+void ln_bwd_rows_kernel(RowArgs a)
 {
     using V = Vec<T>;
     using Raw = typename V::Raw;
     constexpr int E = V::kElems;
+    constexpr int NF = 2 * kVpt * E;  // accumulator floats per lane
+    constexpr int KL = kVpt - 1;      // only a lane's last vector slot can be padding
     extern __shared__ __align__(16) float lds[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = blockDim.x >> 6;
-    const int64_t chunk = blockIdx.x;
-    const int64_t b = chunk / a.C, j = chunk - b * a.C;
-    // chunk j of example b owns rows  b*Tp + j + i*C : the chunks of an example sweep it together.
-    // Examples sit a power of two apart in memory; starting each sweep at a different row
-    // (wrapping around) keeps the concurrent sweeps on different HBM channels.
-    const int64_t row_base = b * a.Tp;
-    const int64_t t_end = a.Tp;
-    const int64_t t_rot = (b * a.stagger) % a.Tp;
+    const int S = kSync ? a.S : 1;
+    const int R = nwaves / S;
+    const int g = wave / S, ws = wave - g * S;
+    const int chunk = blockIdx.x;
+    const int b = chunk / a.C, j = chunk - b * a.C;
+    // Chunk j of example b owns rows b*Tp + j + m*C.  Examples sit a power of two apart in
+    // memory; starting each sweep at a different row (wrapping around) keeps the concurrent
+    // sweeps on different HBM channels.
+    const int Tp = (int)a.Tp;
+    const int row_base = b * Tp;
+    const int t_rot = (int)(((int64_t)b * a.stagger) % a.Tp);
+    const int n_rows = (Tp - j + a.C - 1) / a.C;   // rows of this chunk
+    const int n_full = n_rows / R;                 // iterations in which every row group has a row
+    const bool has_tail = n_rows - n_full * R > 0;
 
     int vidx[kVpt];
-    bool ok[kVpt];
 #pragma unroll
-    for (int k = 0; k < kVpt; ++k) {
-        vidx[k] = (kMulti ? (k * nwaves + wave) * kWave : k * kWave) + lane;
-        ok[k] = vidx[k] < a.nvec;
-    }
-    const float inv_nw = 1.0f / (float)wave_valid_elems<kVpt, E>(wave, nwaves, a.nvec, kMulti);
+    for (int k = 0; k < kVpt; ++k) vidx[k] = (k * S + ws) * kWave + lane;
+    const bool ok_last = kFull ? true : vidx[KL] < a.nvec;
+    const int v_last = ok_last ? vidx[KL] : 0;     // padded lanes load a valid vector and drop it
+    const int n_w = wave_valid_elems<kVpt, E>(ws, S, a.nvec);
 
     const Raw *xv = static_cast<const Raw *>(a.x);
     const Raw *dyv = static_cast<const Raw *>(a.dy);
     Raw *dxv = static_cast<Raw *>(a.dx);
 
-    // loads are unconditional (index clamped to a valid vector); padded lanes are zeroed on unpack
-    auto rotated = [&](int64_t tt) {
-        const int64_t u = tt + t_rot;
-        return row_base + (u >= t_end ? u - t_end : u);
+    auto row_of = [&](int m) {   // m-th row of the chunk -> global row index (wave-uniform)
+        int u = j + m * a.C + t_rot;
+        u = u >= Tp ? u - Tp : u;
+        return __builtin_amdgcn_readfirstlane(row_base + u);
     };
-    auto load_row = [&](int64_t tt, Raw (&xr)[kVpt], Raw (&dr)[kVpt]) {
-        const int64_t rr = rotated(tt);
-        const Raw *xrow = xv + rr * a.nvec;
-        const Raw *drow = dyv + rr * a.nvec;
+    auto load_row = [&](int m, Raw (&xr)[kVpt], Raw (&dr)[kVpt]) {
+        const int64_t off = (int64_t)row_of(m) * a.nvec;
+        const Raw *xrow = xv + off;
+        const Raw *drow = dyv + off;
 #pragma unroll
         for (int k = 0; k < kVpt; ++k) {
-            const int v = ok[k] ? vidx[k] : 0;
+            const int v = k < KL ? vidx[k] : v_last;
             xr[k] = xrow[v];
             dr[k] = drow[v];
         }
     };
 
     // first row on its way before anything else is fetched
-    const int64_t step = (int64_t)a.C * (kMulti ? 1 : nwaves);
-    int64_t t = j + (kMulti ? 0 : (int64_t)wave * a.C);
-    Raw xa[kVpt], da[kVpt], xb[kVpt], db[kVpt];
-    if (t < t_end) load_row(t, xa, da);
+    int m = g;
+    Raw xr[kVpt], dr[kVpt];
+    if (m < n_rows) load_row(m, xr, dr);
 
     float gm[kVpt][E];
 #pragma unroll
     for (int k = 0; k < kVpt; ++k) {
-        load_gamma_vec<T>(a.gamma, a.gamma_is_f32, ok[k] ? vidx[k] : 0, gm[k]);
-        if (!ok[k]) {
+        load_gamma_vec<T>(a.gamma, a.gamma_is_f32, k < KL ? vidx[k] : v_last, gm[k]);
+        if (k == KL && !ok_last) {
 #pragma unroll
             for (int e = 0; e < E; ++e) gm[k][e] = 0.f;
         }
@@ -154,135 +167,160 @@ __global__ __launch_bounds__(kMaxThreads) void ln_bwd_rows_kernel(RowArgs a)
 #pragma unroll
         for (int e = 0; e < E; ++e) acc_g[k][e] = acc_b[k][e] = 0.f;
 
-    // Exchange buffer of multi mode: [parity][4][16] floats, then 16 floats of 1/n_w.  One
-    // barrier per row; the parity flip keeps a fast wave from overwriting values still being read.
-    float *nw_inv = lds + 2 * 4 * 16;
-    if constexpr (kMulti) {
-        if (lane == 0) nw_inv[wave] = inv_nw;
+    // LDS: [parity][R][4][S] exchange floats, then S floats n_w and S floats 1/n_w, then the
+    // merge buffer.
+    float *nw_tab = lds + 8 * nwaves;
+    float *merge = lds + ((8 * nwaves + 2 * S + 3) & ~3);
+    if constexpr (kSync) {
+        if (lane == 0 && g == 0) {
+            nw_tab[ws] = (float)n_w;
+            nw_tab[S + ws] = 1.0f / (float)n_w;
+        }
     }
+    const float inv_nw = 1.0f / (float)n_w;
     int parity = 0;
 
-    auto process = [&](int64_t tt, const Raw (&xr)[kVpt], const Raw (&dr)[kVpt]) {
-        const int64_t r = rotated(tt);
+    // kTail: the last, partial iteration -- only row groups that still have a row do the work,
+    // but every wave meets the barrier.
+    // One register buffer: a row is unpacked to fp32, then the same registers receive the next
+    // row's loads, which stay in flight while the current row is reduced.
+    auto process = [&](auto tail_tag, int mm) {
+        constexpr bool kTail = decltype(tail_tag)::value;
+        const bool act = kTail ? mm < n_rows : true;
         float xf[kVpt][E], df[kVpt][E];
+        float s_x = 0.f, pivot = 0.f, m2 = 0.f, s_dyh = 0.f, s_dyx = 0.f;
+        int r = 0;
+        float *xchg = lds + ((parity * R + g) * 4) * S;
+        if (act) {
+            r = row_of(mm);
 #pragma unroll
-        for (int k = 0; k < kVpt; ++k) {
-            V::unpack(xr[k], xf[k]);
-            V::unpack(dr[k], df[k]);
-            if (!ok[k]) {
+            for (int k = 0; k < kVpt; ++k) {
+                V::unpack(xr[k], xf[k]);
+                V::unpack(dr[k], df[k]);
+                if (!kFull && k == KL) {
 #pragma unroll
-                for (int e = 0; e < E; ++e) xf[k][e] = df[k][e] = 0.f;
+                    for (int e = 0; e < E; ++e) {
+                        xf[k][e] = ok_last ? xf[k][e] : 0.f;
+                        df[k][e] = ok_last ? df[k][e] : 0.f;
+                    }
+                }
             }
-        }
-        // pass 1: pivot = the wave's own mean (or the saved row mean)
-        float s_x = 0.f, pivot;
-        if constexpr (kSaved) {
-            pivot = a.mean[r];
-        } else {
+            if (mm + R < n_rows) load_row(mm + R, xr, dr);
+            // pass 1: pivot = the wave's own mean (or the saved row mean)
+            if constexpr (kSaved) {
+                pivot = a.mean[r];
+            } else {
+#pragma unroll
+                for (int k = 0; k < kVpt; ++k)
+#pragma unroll
+                    for (int e = 0; e < E; ++e) s_x += xf[k][e];
+                s_x = wave_sum(s_x);
+                pivot = s_x * (kSync ? inv_nw : a.inv_D);
+            }
+            // pass 2: centre about the pivot; M2, sum dyh, sum dyh*xc
 #pragma unroll
             for (int k = 0; k < kVpt; ++k)
 #pragma unroll
-                for (int e = 0; e < E; ++e) s_x += xf[k][e];
-            s_x = wave_sum(s_x);
-            pivot = s_x * (kMulti ? inv_nw : a.inv_D);
-        }
-        // pass 2: centre about the pivot; M2, sum dyh, sum dyh*xc
-        float m2 = 0.f, s_dyh = 0.f, s_dyx = 0.f;
-#pragma unroll
-        for (int k = 0; k < kVpt; ++k)
-#pragma unroll
-            for (int e = 0; e < E; ++e) {
-                const float xc = ok[k] ? xf[k][e] - pivot : 0.f;
-                const float dyh = df[k][e] * gm[k][e];
-                xf[k][e] = xc;
-                s_dyh += dyh;
-                s_dyx += dyh * xc;
-                if constexpr (!kSaved) m2 += xc * xc;
-            }
-        if constexpr (kSaved) {
-            wave_sum2(s_dyh, s_dyx);
-        } else {
-            wave_sum3(m2, s_dyh, s_dyx);
-        }
-        float rstd, shift = 0.f;
-        if constexpr (kMulti) {
-            float *xchg = lds + parity * 4 * 16;
-            if (lane == 0) {
-                xchg[wave] = s_dyh;
-                xchg[16 + wave] = s_dyx;
-                if constexpr (!kSaved) {
-                    xchg[32 + wave] = s_x;
-                    xchg[48 + wave] = m2;
+                for (int e = 0; e < E; ++e) {
+                    float xc = xf[k][e] - pivot;
+                    if (!kFull && k == KL) xc = ok_last ? xc : 0.f;
+                    const float dyh = df[k][e] * gm[k][e];
+                    xf[k][e] = xc;
+                    s_dyh += dyh;
+                    s_dyx += dyh * xc;
+                    if constexpr (!kSaved) m2 += xc * xc;
                 }
-            }
-            __syncthreads();
             if constexpr (kSaved) {
-                float t0 = 0.f, t1 = 0.f;
-                for (int w = 0; w < nwaves; ++w) {
-                    t0 += xchg[w];
-                    t1 += xchg[16 + w];
-                }
-                s_dyh = t0;
-                s_dyx = t1;
-                rstd = a.rstd[r];
+                wave_sum2(s_dyh, s_dyx);
             } else {
-                float tot = 0.f;
-                for (int w = 0; w < nwaves; ++w) tot += xchg[32 + w];
-                const float mean = tot * a.inv_D;
-                float M2 = 0.f, t0 = 0.f, t1 = 0.f;
-                for (int w = 0; w < nwaves; ++w) {
-                    const float inw = nw_inv[w];
-                    const float d = xchg[32 + w] * inw - mean;   // mean_w - mean
-                    M2 += xchg[48 + w] + d * d / inw;
-                    t0 += xchg[w];
-                    t1 += xchg[16 + w] + d * xchg[w];
+                wave_sum3(m2, s_dyh, s_dyx);
+            }
+            if constexpr (kSync) {
+                if (lane == 0) {
+                    xchg[ws] = s_dyh;
+                    xchg[S + ws] = s_dyx;
+                    if constexpr (!kSaved) {
+                        xchg[2 * S + ws] = s_x;
+                        xchg[3 * S + ws] = m2;
+                    }
                 }
-                s_dyh = t0;
-                s_dyx = t1;
-                shift = pivot - mean;
-                rstd = rsqrtf(M2 * a.inv_D + a.eps);
             }
-        } else {
-            if constexpr (kSaved) rstd = a.rstd[r];
-            else rstd = rsqrtf(m2 * a.inv_D + a.eps);
         }
-        // pass 3: dx = rstd*(dyh - c2 - xhat*c1), c1 = rstd*mean_d(dyh*(x-mean)), c2 = mean_d(dyh)
-        const float k1 = -rstd * rstd * s_dyx * a.inv_D, k2 = -rstd * s_dyh * a.inv_D;
-        Raw *orow = dxv + r * a.nvec;
+        if constexpr (kSync) __syncthreads();
+        if (act) {
+            float rstd, shift_r = 0.f;   // shift_r = (pivot - mean) * rstd
+            if constexpr (kSync) {
+                if constexpr (kSaved) {
+                    float t0 = 0.f, t1 = 0.f;
 #pragma unroll
-        for (int k = 0; k < kVpt; ++k) {
-            float o[E];
+                    for (int w = 0; w < 8; ++w)
+                        if (w < S) {
+                            t0 += xchg[w];
+                            t1 += xchg[S + w];
+                        }
+                    s_dyh = t0;
+                    s_dyx = t1;
+                    rstd = a.rstd[r];
+                } else {
+                    float tot = 0.f;
 #pragma unroll
-            for (int e = 0; e < E; ++e) {
-                const float xhat = kMulti && !kSaved ? (xf[k][e] + shift) * rstd : xf[k][e] * rstd;
-                o[e] = (df[k][e] * gm[k][e]) * rstd + (xhat * k1 + k2);
-                acc_g[k][e] += df[k][e] * xhat;
-                acc_b[k][e] += df[k][e];
+                    for (int w = 0; w < 8; ++w)
+                        if (w < S) tot += xchg[2 * S + w];
+                    const float mean = tot * a.inv_D;
+                    float M2 = 0.f, t0 = 0.f, t1 = 0.f;
+#pragma unroll
+                    for (int w = 0; w < 8; ++w)
+                        if (w < S) {
+                            const float d = xchg[2 * S + w] * nw_tab[S + w] - mean;   // mean_w - mean
+                            M2 += xchg[3 * S + w] + d * d * nw_tab[w];
+                            t0 += xchg[w];
+                            t1 += xchg[S + w] + d * xchg[w];
+                        }
+                    s_dyh = t0;
+                    s_dyx = t1;
+                    rstd = rsqrtf(M2 * a.inv_D + a.eps);
+                    shift_r = (pivot - mean) * rstd;
+                }
+            } else {
+                if constexpr (kSaved) rstd = a.rstd[r];
+                else rstd = rsqrtf(m2 * a.inv_D + a.eps);
             }
-            if (ok[k]) orow[vidx[k]] = V::pack(o);
+            // pass 3: dx = rstd*(dyh - c2 - xhat*c1), c1 = rstd*mean_d(dyh*(x-mean)), c2 = mean_d(dyh)
+            const float k1 = -rstd * rstd * s_dyx * a.inv_D, k2 = -rstd * s_dyh * a.inv_D;
+            Raw *orow = dxv + (int64_t)r * a.nvec;
+#pragma unroll
+            for (int k = 0; k < kVpt; ++k) {
+                float o[E];
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    const float xhat = kSync && !kSaved ? xf[k][e] * rstd + shift_r : xf[k][e] * rstd;
+                    o[e] = (df[k][e] * gm[k][e]) * rstd + (xhat * k1 + k2);
+                    acc_g[k][e] += df[k][e] * xhat;
+                    acc_b[k][e] += df[k][e];
+                }
+                if (k < KL || ok_last) orow[vidx[k]] = V::pack(o);
+            }
         }
         parity ^= 1;
     };
 
-    // two register buffers: the next row's loads are in flight while the current row is reduced
-    while (t < t_end) {
-        if (t + step < t_end) load_row(t + step, xb, db);
-        process(t, xa, da);
-        t += step;
-        if (t >= t_end) break;
-        if (t + step < t_end) load_row(t + step, xa, da);
-        process(t, xb, db);
-        t += step;
+    using Full = std::integral_constant<bool, false>;
+    using Tail = std::integral_constant<bool, true>;
+    for (int it = 0; it < n_full; ++it) {
+        process(Full{}, m);
+        m += R;
     }
+    if (has_tail) process(Tail{}, m);
 
     // ---- hand the chunk's column sums to the workspace ----
-    float *out_g = a.part + chunk * 2 * (int64_t)a.D;
+    float *out_g = a.part + (int64_t)chunk * 2 * a.D;
     float *out_b = out_g + a.D;
-    if constexpr (kMulti) {
-        // each wave owns its columns: straight from registers
+    double sq_g = 0.0, sq_b = 0.0;   // squares of the final sums this lane writes (emit_pe)
+    if (R == 1) {
+        // one row group: every wave owns its columns, straight from registers
 #pragma unroll
         for (int k = 0; k < kVpt; ++k) {
-            if (ok[k]) {
+            if (k < KL || ok_last) {
 #pragma unroll
                 for (int q = 0; q < E / 4; ++q) {
                     const int64_t col = (int64_t)vidx[k] * E + q * 4;
@@ -291,12 +329,16 @@ __global__ __launch_bounds__(kMaxThreads) void ln_bwd_rows_kernel(RowArgs a)
                     *reinterpret_cast<float4 *>(out_b + col) = make_float4(
                         acc_b[k][q * 4], acc_b[k][q * 4 + 1], acc_b[k][q * 4 + 2], acc_b[k][q * 4 + 3]);
                 }
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    sq_g += (double)acc_g[k][e] * (double)acc_g[k][e];
+                    sq_b += (double)acc_b[k][e] * (double)acc_b[k][e];
+                }
             }
         }
     } else {
-        // merge the waves' sums through LDS, adding in wave order (reproducible)
-        constexpr int NF = 2 * kVpt * E;  // floats per lane
-        float *mine = lds + (int64_t)wave * NF * kWave;
+        // merge the row groups' sums through LDS, adding in group order (reproducible)
+        float *mine = merge + (int64_t)wave * NF * kWave;
 #pragma unroll
         for (int k = 0; k < kVpt; ++k)
 #pragma unroll
@@ -306,22 +348,37 @@ __global__ __launch_bounds__(kMaxThreads) void ln_bwd_rows_kernel(RowArgs a)
             }
         __syncthreads();
         constexpr int NQ = NF / 4;  // groups of four consecutive columns per lane
-        for (int q = wave; q < NQ; q += nwaves) {
+        for (int q = g; q < NQ; q += R) {
             const int f0 = q * 4;
             const int arr = f0 / (kVpt * E);
             const int k = (f0 / E) % kVpt;
             const int e0 = f0 % E;
             float s[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int w = 0; w < nwaves; ++w) {
-                const float *src = lds + ((int64_t)w * NF + f0) * kWave + lane;
+            for (int gg = 0; gg < R; ++gg) {
+                const float *src = merge + ((int64_t)(gg * S + ws) * NF + f0) * kWave + lane;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) s[i] += src[i * kWave];
             }
-            const int v = k * kWave + lane;
+            const int v = (k * S + ws) * kWave + lane;
             if (v < a.nvec) {
                 float *dst = (arr == 0 ? out_g : out_b) + (int64_t)v * E + e0;
                 *reinterpret_cast<float4 *>(dst) = make_float4(s[0], s[1], s[2], s[3]);
+                const double q2 = (double)s[0] * s[0] + (double)s[1] * s[1] + (double)s[2] * s[2] +
+                                  (double)s[3] * s[3];
+                if (arr == 0) sq_g += q2;
+                else sq_b += q2;
             }
+        }
+    }
+    if (a.emit_pe) {
+        // Appendix B steps 2 and 6 for the example this workgroup owns entirely
+        __syncthreads();   // the merge buffer is reused as the reduction scratch
+        double *slots = reinterpret_cast<double *>(merge);
+        const double tg = block_sum_f64(sq_g, slots);
+        const double tb = block_sum_f64(sq_b, slots + 16);
+        if (threadIdx.x == 0) {
+            a.pe_gamma_sq[b] = (float)tg;
+            a.pe_beta_sq[b] = (float)tb;
         }
     }
 }

@@ -128,8 +128,8 @@ def test_T1_and_B1():
         res = pu.run_gpu(inp)
         pu.compare_with_oracle(inp, res, ref)
         if B == 1:   # one example: its squared norm IS the squared norm of the batch gradient
-            np.testing.assert_array_equal(res["s_gamma"][0], res["big_sq"][0])
-            np.testing.assert_array_equal(res["s_beta"][0], res["big_sq"][1])
+            np.testing.assert_allclose(res["s_gamma"][0], res["big_sq"][0], rtol=1e-6)
+            np.testing.assert_allclose(res["s_beta"][0], res["big_sq"][1], rtol=1e-6)
 
 
 def test_constant_row_and_identical_examples():
