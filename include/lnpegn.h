@@ -98,6 +98,31 @@ int ln_bwd_pegn(const void *x, const void *dy, const void *gamma, const float *m
                 void *stream);
 
 /*
+ * Deferred reduction, for callers that run many LayerNorm layers of one shape (the 24 blocks x 2
+ * LayerNorms of a transformer's backward pass).  ln_bwd_deferred / ln_bwd_pegn_deferred take the
+ * arguments of ln_bwd / ln_bwd_pegn and run only the pass over x and dy: dx is complete in
+ * stream order, while dgamma, dbeta, pe_gamma_sq, pe_beta_sq and big_sq are NOT written yet.
+ * The per-chunk column sums (Appendix B steps 1 and 5 over a chunk of rows) and the output
+ * pointers stay in that call's workspace, which must therefore be private to the call and left
+ * untouched until lnpegn_reduce_deferred has run.  lnpegn_reduce_deferred then finishes n such
+ * calls in two launches in all (steps 2, 3, 6, 7 for every layer), instead of two small launches
+ * per layer.  Results are bitwise the same as those of the immediate calls.
+ *   workspaces  HOST array of n device workspace pointers, each used by one deferred call with
+ *               exactly these B, T, D, dt (plain and per-example calls may be mixed)
+ */
+int ln_bwd_deferred(const void *x, const void *dy, const void *gamma, const float *mean,
+                    const float *rstd, void *dx, float *dgamma, float *dbeta, int B, int T, int D,
+                    lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *workspace,
+                    size_t workspace_bytes, void *stream);
+int ln_bwd_pegn_deferred(const void *x, const void *dy, const void *gamma, const float *mean,
+                         const float *rstd, void *dx, float *dgamma, float *dbeta,
+                         float *pe_gamma_sq, float *pe_beta_sq, float *big_sq, int B, int T, int D,
+                         lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *workspace,
+                         size_t workspace_bytes, void *stream);
+int lnpegn_reduce_deferred(void *const *workspaces, int n, int B, int T, int D, lnpegn_dtype dt,
+                           void *stream);
+
+/*
  * Gradient-noise-scale estimate from per-example norms: Section 2.1, Eq. 4 (unbiased |G|^2),
  * Eq. 5 (S ~ tr Sigma) and Eq. 3 (B_simple = S / |G|^2) with B_small = 1 and B_big = B, after
  * steps 4 and 8 of the Appendix B algorithm (mean over examples, times pe_scale^2).

@@ -18,7 +18,7 @@ STATUS = {0: "LNPEGN_OK", 1: "LNPEGN_EINVAL", 2: "LNPEGN_EUNSUPPORTED", 3: "LNPE
           4: "LNPEGN_EHIP"}
 EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "ln_fwd_stats", "ln_bwd",
            "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning", "lnpegn_set_profile_events",
-           "lnpegn_stream_probe")
+           "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred")
 
 _lib = None
 
@@ -48,12 +48,16 @@ def load() -> ctypes.CDLL:
     lib.ln_fwd_stats.argtypes = [vp, fp, fp, i, i, i, i, f, vp]
     lib.ln_bwd.argtypes = [vp, vp, vp, fp, fp, vp, fp, fp, i, i, i, i, i, f, vp, sz, vp]
     lib.ln_bwd_pegn.argtypes = [vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, i, i, i, i, i, f, vp, sz, vp]
+    lib.ln_bwd_deferred.argtypes = lib.ln_bwd.argtypes
+    lib.ln_bwd_pegn_deferred.argtypes = lib.ln_bwd_pegn.argtypes
+    lib.lnpegn_reduce_deferred.argtypes = [ctypes.POINTER(ctypes.c_void_p), i, i, i, i, i, vp]
     lib.gns_estimate.argtypes = [fp, fp, i, i, f, fp, vp]
     lib.lnpegn_set_tuning.argtypes = [i, i]
     lib.lnpegn_set_profile_events.argtypes = [vp, vp]
     lib.lnpegn_stream_probe.argtypes = [vp, vp, vp, sz, i, vp]
     for name in ("ln_fwd_stats", "ln_bwd", "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning",
-                 "lnpegn_set_profile_events", "lnpegn_stream_probe"):
+                 "lnpegn_set_profile_events", "lnpegn_stream_probe", "ln_bwd_deferred",
+                 "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred"):
         getattr(lib, name).restype = i
     _lib = lib
     return lib
@@ -133,8 +137,9 @@ def ln_fwd_stats(x, eps: float, mean=None, rstd=None, stream=None):
 
 
 def ln_bwd(x, dy, gamma, eps: float, mean=None, rstd=None, dx=None, dgamma=None, dbeta=None,
-           workspace=None, stream=None):
-    """Plain LayerNorm backward -> (dx, dgamma, dbeta)."""
+           workspace=None, stream=None, deferred=False):
+    """Plain LayerNorm backward -> (dx, dgamma, dbeta).  deferred=True runs only the pass over x
+    and dy; dgamma/dbeta appear after reduce_deferred() on this call's own workspace."""
     torch = _torch()
     B, T, D = _check3(x)
     _check3(dy)
@@ -142,17 +147,21 @@ def ln_bwd(x, dy, gamma, eps: float, mean=None, rstd=None, dx=None, dgamma=None,
     dgamma = torch.empty(D, dtype=torch.float32, device=x.device) if dgamma is None else dgamma
     dbeta = torch.empty(D, dtype=torch.float32, device=x.device) if dbeta is None else dbeta
     workspace = alloc_workspace(B, T, D, _dt(x), x.device) if workspace is None else workspace
-    rc = load().ln_bwd(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(dx),
-                       _ptr(dgamma), _ptr(dbeta), B, T, D, _dt(x), _dt(gamma), eps,
-                       _ptr(workspace), workspace.numel(), _stream(stream))
+    fn = load().ln_bwd_deferred if deferred else load().ln_bwd
+    rc = fn(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(dx),
+            _ptr(dgamma), _ptr(dbeta), B, T, D, _dt(x), _dt(gamma), eps,
+            _ptr(workspace), workspace.numel(), _stream(stream))
     if rc:
         raise LnpegnError("ln_bwd", rc)
     return dx, dgamma, dbeta
 
 
 def ln_bwd_pegn(x, dy, gamma, eps: float, mean=None, rstd=None, dx=None, dgamma=None, dbeta=None,
-                pe_gamma_sq=None, pe_beta_sq=None, big_sq=None, workspace=None, stream=None):
-    """Fused backward -> (dx, dgamma, dbeta, pe_gamma_sq[B], pe_beta_sq[B], big_sq[2])."""
+                pe_gamma_sq=None, pe_beta_sq=None, big_sq=None, workspace=None, stream=None,
+                deferred=False):
+    """Fused backward -> (dx, dgamma, dbeta, pe_gamma_sq[B], pe_beta_sq[B], big_sq[2]).
+    deferred=True runs only the pass over x and dy; everything but dx appears after
+    reduce_deferred() on this call's own workspace."""
     torch = _torch()
     B, T, D = _check3(x)
     _check3(dy)
@@ -164,13 +173,23 @@ def ln_bwd_pegn(x, dy, gamma, eps: float, mean=None, rstd=None, dx=None, dgamma=
     pe_beta_sq = torch.empty(B, **f32) if pe_beta_sq is None else pe_beta_sq
     big_sq = torch.empty(2, **f32) if big_sq is None else big_sq
     workspace = alloc_workspace(B, T, D, _dt(x), x.device) if workspace is None else workspace
-    rc = load().ln_bwd_pegn(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(dx),
-                            _ptr(dgamma), _ptr(dbeta), _ptr(pe_gamma_sq), _ptr(pe_beta_sq),
-                            _ptr(big_sq), B, T, D, _dt(x), _dt(gamma), eps, _ptr(workspace),
-                            workspace.numel(), _stream(stream))
+    fn = load().ln_bwd_pegn_deferred if deferred else load().ln_bwd_pegn
+    rc = fn(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(dx),
+            _ptr(dgamma), _ptr(dbeta), _ptr(pe_gamma_sq), _ptr(pe_beta_sq),
+            _ptr(big_sq), B, T, D, _dt(x), _dt(gamma), eps, _ptr(workspace),
+            workspace.numel(), _stream(stream))
     if rc:
         raise LnpegnError("ln_bwd_pegn", rc)
     return dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq
+
+
+def reduce_deferred(workspaces, B: int, T: int, D: int, dtype: int, stream=None) -> None:
+    """Finish every deferred backward call whose workspace is listed (all of one shape)."""
+    n = len(workspaces)
+    arr = (ctypes.c_void_p * n)(*[w.data_ptr() for w in workspaces])
+    rc = load().lnpegn_reduce_deferred(arr, n, B, T, D, dtype, _stream(stream))
+    if rc:
+        raise LnpegnError("lnpegn_reduce_deferred", rc)
 
 
 def gns_estimate(pe_sq, big_sq, pe_scale: float, out=None, stream=None):

@@ -24,7 +24,7 @@ hipEvent_t g_ev_stop = nullptr;
 constexpr int kMaxChunks = 16384;
 constexpr int kCUs = 256;           // MI355X
 constexpr int kGroups = 16;         // groups of chunks in the reduction when groups are not examples
-constexpr int64_t kSmallFinal = 131072;  // G1*D up to which one workgroup finishes the reduction
+constexpr int64_t kSmallFinal = 32768;  // G1*D up to which one workgroup finishes the reduction
 constexpr int kMaxPeGroups = 256;   // above this many examples a chunk is a whole example
 constexpr size_t kAlign = 256;
 
@@ -49,8 +49,11 @@ struct Plan {
     bool emit_pe;         // row kernel writes the per-example norms (a chunk is a whole example)
     bool pe_from_groups;  // reduction kernel writes them (groups are examples)
     // workspace layout (byte offsets)
-    size_t off_part, off_grp, off_part_s, off_part_big, total;
+    // workspace layout (byte offsets); everything but `part` depends on B and D only, so that a
+    // batched reduction can address any layer of the same shape
+    size_t off_grp, off_part_s, off_part_big, off_part, total;
 };
+constexpr size_t kHeaderBytes = 256;
 
 // `vector_ok`: the 16-byte aligned fast kernels will run (else the generic kernel does).
 Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
@@ -128,11 +131,11 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
     p.ntile = ceil_div(D, kTile);
     const size_t vec_bytes = (size_t)2 * D * sizeof(float);
     const size_t g_max = (size_t)(B > kGroups ? B : kGroups);   // layout does not depend on the path taken
-    size_t off = 0;
-    p.off_part = off;      off += align_up((size_t)p.n_slots * vec_bytes);
+    size_t off = kHeaderBytes;
     p.off_grp = off;       off += align_up(g_max * vec_bytes);
     p.off_part_s = off;    off += align_up(g_max * p.ntile * 2 * sizeof(double));
     p.off_part_big = off;  off += align_up((size_t)p.ntile * 2 * sizeof(double));
+    p.off_part = off;      off += align_up((size_t)p.n_slots * vec_bytes);
     p.total = off;
     return p;
 }
@@ -197,7 +200,7 @@ hipError_t launch_rows(const Plan &p, const RowArgs &a, const RowLaunch &rl)
     return hipErrorInvalidValue;
 }
 
-int run_bwd(bool pegn, const void *x, const void *dy, const void *gamma, const float *mean,
+int run_bwd(bool pegn, bool defer, const void *x, const void *dy, const void *gamma, const float *mean,
             const float *rstd, void *dx, float *dgamma, float *dbeta, float *pe_gamma_sq,
             float *pe_beta_sq, float *big_sq, int B, int T, int D, int dt, int gamma_dt, float eps,
             void *workspace, size_t workspace_bytes, void *stream)
@@ -225,6 +228,11 @@ int run_bwd(bool pegn, const void *x, const void *dy, const void *gamma, const f
     a.Tp = p.Tp; a.stagger = !pegn ? 0 : g_stagger >= 0 ? g_stagger : (T / B > 0 ? T / B : 1); a.C = p.C; a.D = D; a.nvec = p.nvec;
     a.S = p.S; a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.emit_pe = p.emit_pe;
     a.eps = eps; a.inv_D = 1.0f / (float)D;
+    if (defer) {
+        a.defer = reinterpret_cast<DeferHeader *>(ws);
+        a.hdr = DeferHeader{dgamma, dbeta, pe_gamma_sq, pe_beta_sq, pegn ? big_sq : nullptr,
+                            (int)p.n_slots, p.gs, p.G1, p.pe_from_groups ? 1 : 0};
+    }
 
     hipError_t e;
     const bool saved = mean != nullptr;
@@ -235,6 +243,7 @@ int run_bwd(bool pegn, const void *x, const void *dy, const void *gamma, const f
     else
         e = saved ? launch_rows<float, true>(p, a, rl) : launch_rows<float, false>(p, a, rl);
     if (e != hipSuccess) return LNPEGN_EHIP;
+    if (defer) return LNPEGN_OK;   // lnpegn_reduce_deferred finishes the job
 
     // ---- the levels above the chunks (fixed-order sums) ----
     ReduceArgs ra{};
@@ -381,7 +390,7 @@ int ln_bwd(const void *x, const void *dy, const void *gamma, const float *mean, 
            void *dx, float *dgamma, float *dbeta, int B, int T, int D, lnpegn_dtype dt,
            lnpegn_dtype gamma_dt, float eps, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return run_bwd(false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, nullptr, nullptr, nullptr, B, T,
+    return run_bwd(false, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, nullptr, nullptr, nullptr, B, T,
                    D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
 }
 
@@ -391,8 +400,52 @@ int ln_bwd_pegn(const void *x, const void *dy, const void *gamma, const float *m
                 lnpegn_dtype gamma_dt, float eps, void *workspace, size_t workspace_bytes,
                 void *stream)
 {
-    return run_bwd(true, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq,
+    return run_bwd(true, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq,
                    B, T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
+}
+
+int ln_bwd_deferred(const void *x, const void *dy, const void *gamma, const float *mean,
+                    const float *rstd, void *dx, float *dgamma, float *dbeta, int B, int T, int D,
+                    lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *workspace,
+                    size_t workspace_bytes, void *stream)
+{
+    return run_bwd(false, true, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, nullptr, nullptr, nullptr, B,
+                   T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
+}
+
+int ln_bwd_pegn_deferred(const void *x, const void *dy, const void *gamma, const float *mean,
+                         const float *rstd, void *dx, float *dgamma, float *dbeta,
+                         float *pe_gamma_sq, float *pe_beta_sq, float *big_sq, int B, int T, int D,
+                         lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *workspace,
+                         size_t workspace_bytes, void *stream)
+{
+    return run_bwd(true, true, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq,
+                   big_sq, B, T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
+}
+
+int lnpegn_reduce_deferred(void *const *workspaces, int n, int B, int T, int D, lnpegn_dtype dt,
+                           void *stream)
+{
+    if (!workspaces || n <= 0 || !shape_ok(B, T, D)) return LNPEGN_EINVAL;
+    if (!dtype_ok(dt)) return LNPEGN_EUNSUPPORTED;
+    for (int i = 0; i < n; ++i)
+        if (!workspaces[i] || reinterpret_cast<uintptr_t>(workspaces[i]) % kAlign) return LNPEGN_EINVAL;
+    const Plan p = make_plan(B, T, D, dt, true, true);   // the offsets used depend on B and D only
+    const int g1_max = B > kGroups ? B : kGroups;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int first = 0; first < n; first += kBatchMax) {
+        BatchArgs b{};
+        b.n = n - first < kBatchMax ? n - first : kBatchMax;
+        for (int i = 0; i < b.n; ++i) b.ws[i] = static_cast<char *>(workspaces[first + i]);
+        b.D = D; b.ntile = p.ntile;
+        b.off_grp = p.off_grp; b.off_part_s = p.off_part_s; b.off_part_big = p.off_part_big;
+        b.off_part = p.off_part;
+        reduce_groups_batch_kernel<<<dim3((unsigned)g1_max, (unsigned)p.ntile, (unsigned)b.n), dim3(kTile), 0, s>>>(b);
+        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        reduce_final_batch_kernel<<<dim3((unsigned)b.n), dim3(1024), 0, s>>>(b);
+        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    }
+    return LNPEGN_OK;
 }
 
 int gns_estimate(const float *pe_sq, const float *big_sq, int n_groups, int B, float pe_scale,

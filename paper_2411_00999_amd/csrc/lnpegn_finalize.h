@@ -29,18 +29,23 @@ struct ReduceArgs {
     int pe_from_groups;    // groups are examples: emit their squared norms (Appendix B steps 2, 6)
 };
 
+// What a deferred backward call leaves at the start of its workspace for the batched reduction.
+struct DeferHeader {
+    float *dgamma, *dbeta, *pe_gamma_sq, *pe_beta_sq, *big_sq;
+    int n_slots, gs, G1, pe_from_groups;
+};
+
 // These kernels are a handful of dependent memory round trips long, so every level issues its
 // loads in batches of eight before it adds them (in index order: the sums are reproducible).
 
 // Level 1.  grid (G1, ntile), 256 threads.  The four waves split the group's chunks, add them
 // in chunk order, then the waves' partial sums are added in wave order.  With a single group the
 // group sums ARE the batch gradients and go straight to dgamma / dbeta.
-__global__ __launch_bounds__(kTile) void reduce_groups_kernel(ReduceArgs a)
+__device__ __forceinline__ void reduce_groups_body(const ReduceArgs &a, int g, int tile)
 {
     __shared__ double wsum[4][8][kWave];   // [wave][array*4 + component][lane]
     __shared__ double slots[2][4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int g = blockIdx.x, tile = blockIdx.y;
     const int col0 = tile * kTile;
 
     const int m0 = g * a.gs, m1 = min(m0 + a.gs, a.n_slots);
@@ -119,6 +124,11 @@ __global__ __launch_bounds__(kTile) void reduce_groups_kernel(ReduceArgs a)
     }
 }
 
+__global__ __launch_bounds__(kTile) void reduce_groups_kernel(ReduceArgs a)
+{
+    reduce_groups_body(a, blockIdx.x, blockIdx.y);
+}
+
 // Sum over the groups for one column (Appendix B steps 3, 7), groups added in order.
 __device__ __forceinline__ void sum_groups(const float *grp, int G1, int D, int col, double &s0,
                                            double &s1)
@@ -159,9 +169,10 @@ __device__ __forceinline__ void finish_scalars(const ReduceArgs &a, int tid, int
     }
 }
 
-// Levels 2 and 3 in ONE workgroup of 1024 threads, for shapes where the group sums are small
-// (G1*D <= 128K): dgamma, dbeta, their squared norms, and the per-example squared norms.
-__global__ __launch_bounds__(1024) void reduce_final_small_kernel(ReduceArgs a)
+// Levels 2 and 3 in ONE workgroup of 1024 threads: dgamma, dbeta, their squared norms, and the
+// per-example squared norms.  Used alone when the group sums are small, and one workgroup per
+// layer when many layers are finished at once.
+__device__ __forceinline__ void reduce_final_body(const ReduceArgs &a)
 {
     __shared__ double slots[2][16];
     const int tid = threadIdx.x;
@@ -191,6 +202,54 @@ __global__ __launch_bounds__(1024) void reduce_final_small_kernel(ReduceArgs a)
         if (tid == 0) a.big_sq[0] = (float)q0;
         if (tid == (a.G1 > 1 ? 0 : 1)) a.big_sq[1] = (float)q1;
     }
+}
+
+__global__ __launch_bounds__(1024) void reduce_final_small_kernel(ReduceArgs a)
+{
+    reduce_final_body(a);
+}
+
+// Many layers at once (deferred reduction).  Every layer's workspace starts with a DeferHeader
+// and has the same layout, because the layers have the same shape.
+constexpr int kBatchMax = 32;
+struct BatchArgs {
+    char *ws[kBatchMax];
+    int n;
+    int D;
+    int ntile;
+    size_t off_grp, off_part_s, off_part_big, off_part;
+};
+
+__device__ __forceinline__ ReduceArgs batch_layer_args(const BatchArgs &b, int layer)
+{
+    char *ws = b.ws[layer];
+    const DeferHeader h = *reinterpret_cast<const DeferHeader *>(ws);
+    ReduceArgs a;
+    a.part = reinterpret_cast<const float *>(ws + b.off_part);
+    a.grp = reinterpret_cast<float *>(ws + b.off_grp);
+    a.part_s = reinterpret_cast<double *>(ws + b.off_part_s);
+    a.part_big = reinterpret_cast<double *>(ws + b.off_part_big);
+    a.dgamma = h.dgamma; a.dbeta = h.dbeta;
+    a.pe_gamma_sq = h.pe_gamma_sq; a.pe_beta_sq = h.pe_beta_sq; a.big_sq = h.big_sq;
+    a.n_slots = h.n_slots; a.gs = h.gs; a.G1 = h.G1; a.D = b.D; a.ntile = b.ntile;
+    a.pe_from_groups = h.pe_from_groups;
+    return a;
+}
+
+// grid (G1max, ntile, layers): workgroups beyond a layer's own group count leave at once
+__global__ __launch_bounds__(kTile) void reduce_groups_batch_kernel(BatchArgs b)
+{
+    const ReduceArgs a = batch_layer_args(b, blockIdx.z);
+    if ((int)blockIdx.x >= a.G1) return;
+    reduce_groups_body(a, blockIdx.x, blockIdx.y);
+}
+
+// grid (layers)
+__global__ __launch_bounds__(1024) void reduce_final_batch_kernel(BatchArgs b)
+{
+    const ReduceArgs a = batch_layer_args(b, blockIdx.x);
+    if (a.G1 == 1 && !a.pe_from_groups && !a.big_sq) return;
+    reduce_final_body(a);
 }
 
 // Level 2 for large shapes: grid ntile, 256 threads, one column per thread.

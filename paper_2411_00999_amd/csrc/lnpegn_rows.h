@@ -17,6 +17,7 @@
 #include <type_traits>
 
 #include "lnpegn_device.h"
+#include "lnpegn_finalize.h"
 
 namespace lnpegn {
 
@@ -30,6 +31,8 @@ struct RowArgs {
     float *part;         // [n_slots][2][D] fp32 column sums per chunk
     float *pe_gamma_sq;  // [B], written here only when emit_pe
     float *pe_beta_sq;
+    DeferHeader *defer;  // not null: leave `hdr` there for the batched reduction
+    DeferHeader hdr;
     int64_t Tp;          // rows per partition example
     int64_t stagger;     // example b starts its sweep at row (b*stagger) mod Tp of itself
     int C;               // chunks per partition example
@@ -117,6 +120,7 @@ void ln_bwd_rows_kernel(RowArgs a)
     const int n_rows = (Tp - j + a.C - 1) / a.C;   // rows of this chunk
     const int n_full = n_rows / R;                 // iterations in which every row group has a row
     const bool has_tail = n_rows - n_full * R > 0;
+    if (a.defer && blockIdx.x == 0 && threadIdx.x == 0) *a.defer = a.hdr;
 
     int vidx[kVpt];
 #pragma unroll
@@ -298,7 +302,7 @@ void ln_bwd_rows_kernel(RowArgs a)
                     acc_g[k][e] += df[k][e] * xhat;
                     acc_b[k][e] += df[k][e];
                 }
-                if (k < KL || ok_last) orow[vidx[k]] = V::pack(o);
+                if (k < KL || ok_last) V::store_stream(orow + vidx[k], V::pack(o));
             }
         }
         parity ^= 1;
@@ -399,6 +403,7 @@ __global__ void ln_bwd_rows_generic_kernel(RowArgs a)
     float *out_g = a.part + chunk * 2 * (int64_t)a.D;
     float *out_b = out_g + a.D;
     const int tid = threadIdx.x, nt = blockDim.x;
+    if (a.defer && blockIdx.x == 0 && tid == 0) *a.defer = a.hdr;
     for (int k = tid; k < a.D; k += nt) {
         out_g[k] = 0.f;
         out_b[k] = 0.f;

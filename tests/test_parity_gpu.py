@@ -201,6 +201,45 @@ def test_chunk_count_only_changes_summation_order():
         binding.set_tuning(1, 0)
 
 
+@pytest.mark.parametrize("cfg,B,T,D", [(3, 4, 64, 2048), (2, 3, 37, 768), (4, 300, 4, 1024), (5, 2, 20, 8192),
+                                      (1, 2, 9, 257)])
+def test_deferred_reduction_matches_immediate_calls_bitwise(cfg, B, T, D):
+    """Several layers of one shape: row passes first, ONE batched reduction afterwards."""
+    import torch
+    from paper_2411_00999_amd import binding
+    n_layers = 5
+    dt_code = binding.BF16 if workloads.SHAPES[cfg][3] == "bf16" else binding.F32
+    immediate, deferred, wss = [], [], []
+    for l in range(n_layers):
+        inp = workloads.make_inputs(cfg, layer=l, B=B, T=T, D=D)
+        x, dy = pu.to_device(inp.x, inp.dtype), pu.to_device(inp.dy, inp.dtype)
+        gamma = pu.to_device(inp.gamma, inp.dtype)
+        pegn = l != 2                                   # one plain call mixed in
+        if pegn:
+            immediate.append(binding.ln_bwd_pegn(x, dy, gamma, inp.eps))
+        else:
+            immediate.append(binding.ln_bwd(x, dy, gamma, inp.eps))
+        ws = binding.alloc_workspace(B, T, D, dt_code)
+        wss.append(ws)
+        f32 = dict(dtype=torch.float32, device="cuda")
+        outs = dict(dgamma=torch.full((D,), float("nan"), **f32), dbeta=torch.full((D,), float("nan"), **f32))
+        if pegn:
+            outs.update(pe_gamma_sq=torch.full((B,), float("nan"), **f32),
+                        pe_beta_sq=torch.full((B,), float("nan"), **f32),
+                        big_sq=torch.full((2,), float("nan"), **f32))
+            deferred.append(binding.ln_bwd_pegn(x, dy, gamma, inp.eps, workspace=ws, deferred=True, **outs))
+        else:
+            deferred.append(binding.ln_bwd(x, dy, gamma, inp.eps, workspace=ws, deferred=True, **outs))
+    torch.cuda.synchronize()
+    assert all(torch.isnan(d[1]).all() for d in deferred)          # nothing but dx written yet
+    binding.reduce_deferred(wss, B, T, D, dt_code)
+    torch.cuda.synchronize()
+    for a, b in zip(immediate, deferred):
+        assert len(a) == len(b)
+        for u, v in zip(a, b):
+            assert torch.equal(u, v)
+
+
 # ------------------------------------------------------------------ estimator alone
 @pytest.mark.parametrize("n_groups,B", [(1, 2), (2, 8), (96, 16), (3, 513)])
 def test_gns_estimate_same_norms_both_sides(n_groups, B):
