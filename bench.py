@@ -2,11 +2,14 @@
 """Benchmark of the fused LayerNorm-backward + per-example-gradient-norm path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 3] [--stats saved|recompute]
+                    [--reduce deferred|immediate]
 
 One "step" is one pass of the whole hot path over one batch of synthetic input: for every
 LayerNorm layer of the workload, ln_bwd_pegn (dx, dgamma, dbeta, per-example squared norms),
-then one gns_estimate over all layers' norms.  Inputs are resident in HBM before the timed
-region starts.  Prints ONE JSON line (see the design doc for the fields).
+then one gns_estimate over all layers' norms.  With --reduce deferred (default) the layers'
+small reduction kernels are batched into one lnpegn_reduce_deferred per step, as a backward
+pass over many layers would do; --reduce immediate makes every call self-contained.  Inputs are
+resident in HBM before the timed region starts.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -23,6 +26,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+# HBM bytes per row-kernel launch counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the
+# stream probe of known size); see profiles/ln_bwd_rows_workload3_rocprofv3.md.  Re-measure after any
+# change to the row kernel or its launch shape.  Workloads without a measurement report null.
+MEASURED_TRAFFIC_BYTES = {3: 411_300_000}
 
 
 # ----------------------------------------------------------------------------- HIP events
@@ -73,7 +80,7 @@ def build_layers(cfg, n_layers, stats_mode, log):
 
     B, T, D, dtype, _ = workloads.SHAPES[cfg]
     workers = max(1, min(16, os.cpu_count() or 1, n_layers))
-    layers, host0 = [], None
+    layers, host_inputs = [], []
     t0 = time.time()
     with cf.ThreadPoolExecutor(max_workers=workers) as ex:
         futs = [ex.submit(workloads.make_inputs, cfg, l) for l in range(n_layers)]
@@ -89,15 +96,17 @@ def build_layers(cfg, n_layers, stats_mode, log):
             if stats_mode == "saved":
                 L["mean"], L["rstd"] = binding.ln_fwd_stats(L["x"], inp.eps)
             layers.append(L)
-            if l == 0:
-                host0 = inp
+            if l < 4:                      # bounded sample kept on the host for the CPU baseline
+                host_inputs.append(inp)
             futs[l] = None
             if (l + 1) % 8 == 0 or l + 1 == n_layers:
                 log(f"inputs: {l + 1}/{n_layers} layers resident ({time.time() - t0:.1f}s)")
     torch.cuda.synchronize()
     dt_code = binding.BF16 if dtype == "bf16" else binding.F32
+    for L in layers:                   # deferred reduction needs a private workspace per layer
+        L["ws"] = binding.alloc_workspace(B, T, D, dt_code)
     shared = dict(
-        ws=binding.alloc_workspace(B, T, D, dt_code),
+        ws=binding.alloc_workspace(B, T, D, dt_code), dt_code=dt_code,
         pe_all=torch.zeros((2 * n_layers, B), dtype=torch.float32, device="cuda"),
         big_all=torch.zeros(2 * n_layers, dtype=torch.float32, device="cuda"),
         gns=torch.zeros(5, dtype=torch.float32, device="cuda"),
@@ -105,7 +114,7 @@ def build_layers(cfg, n_layers, stats_mode, log):
     for l, L in enumerate(layers):     # views into the shared norm tables, made once
         L["pe_g"], L["pe_b"] = shared["pe_all"][2 * l], shared["pe_all"][2 * l + 1]
         L["big"] = shared["big_all"][2 * l:2 * l + 2]
-    return layers, shared, host0
+    return layers, shared, host_inputs
 
 
 def main():
@@ -117,6 +126,11 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the workload's layer count")
     ap.add_argument("--stats", default="recompute", choices=["saved", "recompute"],
                     help="row mean/rstd: recomputed inside the backward, or saved by ln_fwd_stats")
+    ap.add_argument("--reduce", default="deferred", choices=["deferred", "immediate"],
+                    help="finish each layer's small reductions per call, or all layers in one batch")
+    ap.add_argument("--only-fused", action="store_true",
+                    help="profiling aid: skip the plain ln_bwd, the other reduction mode and the probe, so "
+                         "that a kernel trace of this run holds fused dispatches only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
@@ -151,21 +165,33 @@ def main():
     log(f"workload {cfg}: B={B} T={T} D={D} {dtype} x {n_layers} layers, "
         f"{bytes_per_step / 1e9:.2f} GB algorithmic per step, stats={args.stats}")
 
-    layers, sh, host0 = build_layers(cfg, n_layers, args.stats, log)
+    layers, sh, host_inputs = build_layers(cfg, n_layers, args.stats, log)
     eps = workloads.EPS
 
-    def fused_step():
-        for L in layers:
-            binding.ln_bwd_pegn(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"],
-                                dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"],
-                                pe_gamma_sq=L["pe_g"], pe_beta_sq=L["pe_b"], big_sq=L["big"],
-                                workspace=sh["ws"])
-        binding.gns_estimate(sh["pe_all"], sh["big_all"], float(B), out=sh["gns"])
+    all_ws = [L["ws"] for L in layers]
 
-    def plain_step():
-        for L in layers:
-            binding.ln_bwd(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"],
-                           dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"], workspace=sh["ws"])
+    def make_steps(deferred):
+        def fused_step():
+            for L in layers:
+                binding.ln_bwd_pegn(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"],
+                                    dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"],
+                                    pe_gamma_sq=L["pe_g"], pe_beta_sq=L["pe_b"], big_sq=L["big"],
+                                    workspace=L["ws"] if deferred else sh["ws"], deferred=deferred)
+            if deferred:
+                binding.reduce_deferred(all_ws, B, T, D, sh["dt_code"])
+            binding.gns_estimate(sh["pe_all"], sh["big_all"], float(B), out=sh["gns"])
+
+        def plain_step():
+            for L in layers:
+                binding.ln_bwd(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"],
+                               dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"],
+                               workspace=L["ws"] if deferred else sh["ws"], deferred=deferred)
+            if deferred:
+                binding.reduce_deferred(all_ws, B, T, D, sh["dt_code"])
+        return fused_step, plain_step
+
+    fused_step, plain_step = make_steps(args.reduce == "deferred")
+    other_fused, other_plain = make_steps(args.reduce != "deferred")
 
     def timed(step, warmup, steps):
         for _ in range(warmup):
@@ -179,12 +205,22 @@ def main():
 
     t_fused = timed(fused_step, args.warmup, args.steps)
     log(f"fused : {t_fused * 1e3:.3f} ms/step  {bytes_per_step / t_fused / 1e9:.1f} GB/s")
-    t_plain = timed(plain_step, args.warmup, args.steps)
-    log(f"plain : {t_plain * 1e3:.3f} ms/step  {bytes_per_step / t_plain / 1e9:.1f} GB/s")
+    other = "immediate" if args.reduce == "deferred" else "deferred"
+    t_plain = t_fused_o = t_plain_o = float("nan")
+    if not args.only_fused:
+        t_plain = timed(plain_step, args.warmup, args.steps)
+        log(f"plain : {t_plain * 1e3:.3f} ms/step  {bytes_per_step / t_plain / 1e9:.1f} GB/s")
+        t_fused_o = timed(other_fused, 1, max(2, args.steps // 2))
+        t_plain_o = timed(other_plain, 1, max(2, args.steps // 2))
+        log(f"({other} reduction: fused {t_fused_o * 1e3:.3f} ms/step, plain {t_plain_o * 1e3:.3f} ms/step)")
+        fused_step()     # leave the outputs of the mode being reported in place
+        torch.cuda.synchronize()
 
     # ---- dominant kernel: HIP events around the row-streaming kernel, on its own stream ----
     hip = HipEvents()
     pairs = [(hip.create(), hip.create()) for _ in layers]
+
+    deferred = args.reduce == "deferred"
 
     def kernel_avg_ms(plain):
         tot, cnt = 0.0, 0
@@ -193,12 +229,15 @@ def main():
                 binding.set_profile_events(pairs[l][0], pairs[l][1])
                 if plain:
                     binding.ln_bwd(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"],
-                                   dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"], workspace=sh["ws"])
+                                   dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"], workspace=L["ws"],
+                                   deferred=deferred)
                 else:
                     binding.ln_bwd_pegn(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"],
                                         dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"],
                                         pe_gamma_sq=L["pe_g"], pe_beta_sq=L["pe_b"], big_sq=L["big"],
-                                        workspace=sh["ws"])
+                                        workspace=L["ws"], deferred=deferred)
+            if deferred:
+                binding.reduce_deferred(all_ws, B, T, D, sh["dt_code"])
             torch.cuda.synchronize()
             for a, b in pairs:
                 tot += hip.elapsed_ms(a, b)
@@ -206,12 +245,31 @@ def main():
         return tot / cnt
 
     k_fused_ms = kernel_avg_ms(False)
-    k_plain_ms = kernel_avg_ms(True)
+    k_plain_ms = float("nan") if args.only_fused else kernel_avg_ms(True)
+    achieved = bytes_per_layer / (k_fused_ms * 1e-3) / 1e9
+    log(f"row kernel: fused {k_fused_ms * 1e3:.1f} us ({achieved:.0f} GB/s), plain {k_plain_ms * 1e3:.1f} us")
+
+    # ---- streaming yardstick on the same buffers: out = a XOR b (2 reads + 1 write) and a copy ----
+    def probe_us(mode):
+        ts = []
+        for i in range(max(6, args.steps)):
+            L = layers[i % len(layers)]
+            binding.set_profile_events(pairs[0][0], pairs[0][1])
+            binding.stream_probe(L["x"], L["dy"], L["dx"], mode)
+            ts.append(hip.elapsed_ms(pairs[0][0], pairs[0][1]) * 1e3)
+        ts.sort()
+        return ts[len(ts) // 2]
+
+    probe_rrw_us = float("nan") if args.only_fused else probe_us(1)
+    probe_copy_us = float("nan") if args.only_fused else probe_us(0)
+    probe_rrw = bytes_per_layer / probe_rrw_us / 1e3
+    probe_copy = (2 * bytes_per_layer / 3) / probe_copy_us / 1e3
+    log(f"stream probe: 2 reads + 1 write {probe_rrw:.0f} GB/s, copy {probe_copy:.0f} GB/s")
+    fused_step()     # the probe overwrote dx of some layers; restore the reported outputs
+    torch.cuda.synchronize()
     for a, b in pairs:
         hip.destroy(a)
         hip.destroy(b)
-    achieved = bytes_per_layer / (k_fused_ms * 1e-3) / 1e9
-    log(f"row kernel: fused {k_fused_ms * 1e3:.1f} us ({achieved:.0f} GB/s), plain {k_plain_ms * 1e3:.1f} us")
 
     gns = sh["gns"].cpu().numpy().astype(float)
 
@@ -220,29 +278,36 @@ def main():
     parity = None
     if not args.no_cpu_baseline:
         import oracle
-        x64 = host0.x.astype(np.float64)
-        dy64 = host0.dy.astype(np.float64)
-        g64 = host0.gamma.astype(np.float64)
         threads = min(B, oracle.max_threads())
-        oracle.ln_bwd_pegn(x64[:1], dy64[:1], g64, eps)           # load + warm the library
-        t0 = time.perf_counter()
-        ref = oracle.ln_bwd_pegn(x64, dy64, g64, eps, want_dx=True, want_pe=False, nthreads=threads)
-        t_cpu = time.perf_counter() - t0
+        g64 = host_inputs[0].gamma.astype(np.float64)
+        oracle.ln_bwd_pegn(host_inputs[0].x[:1].astype(np.float64), host_inputs[0].dy[:1].astype(np.float64),
+                           g64, eps)           # load + warm the library
+        t_cpu, ref0 = 0.0, None
+        for inp in host_inputs:
+            x64, dy64 = inp.x.astype(np.float64), inp.dy.astype(np.float64)     # exact, not timed
+            t0 = time.perf_counter()
+            ref = oracle.ln_bwd_pegn(x64, dy64, inp.gamma.astype(np.float64), eps, want_dx=True,
+                                     want_pe=False, nthreads=threads)
+            t_cpu += time.perf_counter() - t0
+            ref0 = ref0 or ref
+            del x64, dy64
+        n_s = len(host_inputs)
         cpu_baseline = {
-            "value": round(bytes_per_layer / t_cpu / 1e9, 4), "unit": "GB/s", "cores": threads,
+            "value": round(n_s * bytes_per_layer / t_cpu / 1e9, 4), "unit": "GB/s", "cores": threads,
             "kind": "oracle",
-            "sample": f"layer 0 of {n_layers} (B={B} T={T} D={D}, dx + per-example norms), "
-                      f"{t_cpu:.2f} s wall on {threads} threads of {os.cpu_count()} host cpus; "
-                      f"bytes counted as for the GPU ({esz} B/element)",
+            "sample": f"layers 0..{n_s - 1} of {n_layers} (each B={B} T={T} D={D}: dx, dgamma, dbeta and "
+                      f"per-example norms by one separate fp64 backward per example), {t_cpu:.2f} s wall on "
+                      f"{threads} threads of {os.cpu_count()} host cpus; bytes counted as for the GPU "
+                      f"({esz} B/element)",
             "seconds": round(t_cpu, 3),
         }
-        log(f"oracle: {t_cpu:.2f} s for one layer on {threads} threads")
+        log(f"oracle: {t_cpu:.2f} s for {n_s} layers on {threads} threads")
         # spot parity of layer 0 against the oracle output just computed
         L0 = layers[0]
         dg = L0["dgamma"].cpu().numpy().astype(np.float64)
         sg = sh["pe_all"][0].cpu().numpy().astype(np.float64)
-        err_dg = float(np.linalg.norm(dg - ref["dgamma"]) / np.linalg.norm(ref["dgamma"]))
-        err_sg = float(np.max(np.abs(sg / ref["s_gamma"] - 1.0)))
+        err_dg = float(np.linalg.norm(dg - ref0["dgamma"]) / np.linalg.norm(ref0["dgamma"]))
+        err_sg = float(np.max(np.abs(sg / ref0["s_gamma"] - 1.0)))
         parity = {"layer0_dgamma_l2_rel": err_dg, "layer0_s_gamma_max_rel": err_sg,
                   "ok": bool(err_dg < 1e-5 and err_sg < 1e-5)}
 
@@ -257,27 +322,41 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"configs[{cfg - 1}]: {n_layers} LayerNorm layers back-to-back, B={B} T={T} D={D} "
-                        f"{dtype}, ln_bwd_pegn per layer + one gns_estimate; row stats {args.stats}",
-            "B": B, "T": T, "D": D, "layers": n_layers, "stats": args.stats,
+                        f"{dtype}, ln_bwd_pegn per layer + one gns_estimate; row stats {args.stats}; "
+                        f"{args.reduce} reduction",
+            "B": B, "T": T, "D": D, "layers": n_layers, "stats": args.stats, "reduce": args.reduce,
         },
         "pct_hbm_peak": round(100.0 * bytes_per_step / t_fused / 1e9 / HBM_PEAK_GBS, 2),
         "tokens_per_s": round(n_layers * N / t_fused, 1),
         "plain_ln_bwd": {"ms_per_step": round(t_plain * 1e3, 4),
                          "GBps": round(bytes_per_step / t_plain / 1e9, 2)},
         "overhead_vs_plain_pct": round(100.0 * (t_fused / t_plain - 1.0), 2),
+        f"{other}_reduction": {"fused_ms_per_step": round(t_fused_o * 1e3, 4),
+                               "plain_ms_per_step": round(t_plain_o * 1e3, 4),
+                               "fused_GBps": round(bytes_per_step / t_fused_o / 1e9, 2)},
         "gns": {"g_small_sq": gns[0], "g_big_sq": gns[1], "G2": gns[2], "S": gns[3], "B_simple": gns[4]},
         "roofline": {
             "kernel": "ln_bwd_rows_kernel (fused call)",
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg) if n_layers == workloads.SHAPES[cfg][4] else None,
             "avg_launch_us": round(k_fused_ms * 1e3, 2),
             "plain_avg_launch_us": round(k_plain_ms * 1e3, 2),
             "algorithmic_bytes_per_launch": bytes_per_layer,
+            "stream_probe_GBps": {"two_reads_one_write": round(probe_rrw, 1), "copy": round(probe_copy, 1)},
+            "frac_of_stream_probe": round(achieved / probe_rrw, 4),
         },
         "cpu_baseline": cpu_baseline,
         "parity_spot_check": parity,
     }
-    print(json.dumps(out), flush=True)
+    def clean(o):      # NaN (skipped legs) -> null, so the line stays valid JSON
+        if isinstance(o, dict):
+            return {k: clean(v) for k, v in o.items()}
+        if isinstance(o, float) and o != o:
+            return None
+        return o
+
+    print(json.dumps(clean(out)), flush=True)
 
 
 if __name__ == "__main__":
