@@ -76,11 +76,13 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         p.sync = p.S > 1;
         const int elems = p.vpt * E;                 // per lane
         waves_per_simd = elems > 8 ? 2 : 4;          // measured: more waves of 16-element lanes only add contention
+        // launch bound of the instantiation that will run: 256 threads for S = 1, 2, 4; 512 else
+        const int max_waves = (p.S == 1 || p.S == 2 || p.S == 4) ? 4 : 8;
         int R = g_waves > 0 ? g_waves / p.S : (p.S >= 4 ? 1 : 4 / p.S);
         if (R < 1) R = 1;
-        while (R * p.S > 8) --R;
+        while (R > 1 && R * p.S > max_waves) --R;
         p.R = R;
-        p.max_threads = R * p.S <= 4 ? 256 : 512;
+        p.max_threads = 64 * max_waves;
     }
     const int nwaves = p.fast ? p.R * p.S : 4;
     {
@@ -174,14 +176,18 @@ hipError_t launch_rows_vpt(const Plan &p, const RowArgs &a, const RowLaunch &rl)
     const dim3 grid((unsigned)p.n_slots), block(64 * p.R * p.S);
     const bool full = p.nvec == 64 * p.S * kVpt;
     auto go = [&](auto kernel) { return launch_row_kernel(kernel, grid, block, p.lds_bytes, rl, a); };
-    if (!p.sync)
-        return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, false, true, 256>)
-                    : go(ln_bwd_rows_kernel<T, kVpt, kSaved, false, false, 256>);
-    if (p.max_threads == 256)
-        return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, true, true, 256>)
-                    : go(ln_bwd_rows_kernel<T, kVpt, kSaved, true, false, 256>);
-    return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, true, true, 512>)
-                : go(ln_bwd_rows_kernel<T, kVpt, kSaved, true, false, 512>);
+    switch (p.S) {
+        case 1: return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, 1, true>)
+                            : go(ln_bwd_rows_kernel<T, kVpt, kSaved, 1, false>);
+        case 2: return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, 2, true>)
+                            : go(ln_bwd_rows_kernel<T, kVpt, kSaved, 2, false>);
+        case 4: return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, 4, true>)
+                            : go(ln_bwd_rows_kernel<T, kVpt, kSaved, 4, false>);
+        case 8: return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, 8, true>)
+                            : go(ln_bwd_rows_kernel<T, kVpt, kSaved, 8, false>);
+        default: return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, 0, true>)
+                             : go(ln_bwd_rows_kernel<T, kVpt, kSaved, 0, false>);
+    }
 }
 
 template <typename T, bool kSaved>

@@ -85,7 +85,7 @@ __device__ __forceinline__ double wave_sum_f64(double v)
 // ---------------------------------------------------------------------------------------
 // Row vectors: 16 bytes per lane per access.  dx is written once and never read back here, so
 // it is stored with the non-temporal (streaming) hint; measured on MI355X the same hint on the
-// loads of x and dy helps narrow rows and hurts wide ones, so loads stay plain.
+// loads of x and dy helps narrow rows (one or two waves per row) and hurts wide ones.
 // ---------------------------------------------------------------------------------------
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));

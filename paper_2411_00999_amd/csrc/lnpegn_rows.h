@@ -89,16 +89,23 @@ __device__ __forceinline__ int wave_valid_elems(int ws, int S, int nvec)
 // and sum_d dyh*(x-mean) = sum_w [ sum dyh*(x-mean_w) + (mean_w-mean) sum dyh ]
 // so the wave mean is only a pivot and the result does not lose digits to a large |mean|.
 //
-// kSync: S > 1, the waves of a row exchange their scalars through LDS (one barrier per row;
-// every wave of the workgroup takes part in every barrier, also a group that has run out of rows).
+// kS: waves per row.  1: a wave owns a row, nothing crosses waves.  2, 4, 8: that many waves share
+// a row and exchange their scalars through LDS (one barrier per row; every wave of the
+// workgroup takes part in every barrier, also a group that has run out of rows).  0: the same
+// with S read at run time (3, 5, 6, 7 waves).
 // kFull: every lane owns kVpt valid vectors (nvec == 64*S*kVpt), so no padding logic is compiled.
-template <typename T, int kVpt, bool kSaved, bool kSync, bool kFull, int kMaxThreads>
-__global__ __launch_bounds__(kMaxThreads, (kVpt * Vec<T>::kElems > 8 ? 3 : 4))
+constexpr int rows_kernel_max_threads(int kS) { return (kS == 0 || kS == 8) ? 512 : 256; }
+
+template <typename T, int kVpt, bool kSaved, int kS, bool kFull>
+__global__ __launch_bounds__(rows_kernel_max_threads(kS), (kVpt * Vec<T>::kElems > 8 ? 3 : 4))
 void ln_bwd_rows_kernel(RowArgs a)
 {
     using V = Vec<T>;
     using Raw = typename V::Raw;
     constexpr int E = V::kElems;
+    constexpr bool kSync = kS != 1;
+    // x and dy are read once: the streaming hint pays for narrow rows and costs on wide ones (measured)
+    constexpr bool kStreamLoads = kS == 1 || kS == 2;
     constexpr int NF = 2 * kVpt * E;  // accumulator floats per lane
     constexpr int KL = kVpt - 1;      // only a lane's last vector slot can be padding
     extern __shared__ __align__(16) float lds[];
@@ -106,7 +113,7 @@ void ln_bwd_rows_kernel(RowArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = blockDim.x >> 6;
-    const int S = kSync ? a.S : 1;
+    const int S = kS > 0 ? kS : a.S;
     const int R = nwaves / S;
     const int g = wave / S, ws = wave - g * S;
     const int chunk = blockIdx.x;
@@ -138,15 +145,27 @@ void ln_bwd_rows_kernel(RowArgs a)
         u = u >= Tp ? u - Tp : u;
         return __builtin_amdgcn_readfirstlane(row_base + u);
     };
+    // saved statistics of the row in flight: fetched with the row, a whole iteration before use
+    float st_mean = 0.f, st_rstd = 0.f;
     auto load_row = [&](int m, Raw (&xr)[kVpt], Raw (&dr)[kVpt]) {
-        const int64_t off = (int64_t)row_of(m) * a.nvec;
+        const int rr = row_of(m);
+        if constexpr (kSaved) {
+            st_mean = a.mean[rr];
+            st_rstd = a.rstd[rr];
+        }
+        const int64_t off = (int64_t)rr * a.nvec;
         const Raw *xrow = xv + off;
         const Raw *drow = dyv + off;
 #pragma unroll
         for (int k = 0; k < kVpt; ++k) {
             const int v = k < KL ? vidx[k] : v_last;
-            xr[k] = xrow[v];
-            dr[k] = drow[v];
+            if constexpr (kStreamLoads) {
+                xr[k] = V::load_stream(xrow + v);
+                dr[k] = V::load_stream(drow + v);
+            } else {
+                xr[k] = xrow[v];
+                dr[k] = drow[v];
+            }
         }
     };
 
@@ -171,11 +190,12 @@ void ln_bwd_rows_kernel(RowArgs a)
 #pragma unroll
         for (int e = 0; e < E; ++e) acc_g[k][e] = acc_b[k][e] = 0.f;
 
-    // LDS: [parity][R][4][S] exchange floats, then S floats n_w and S floats 1/n_w, then the
-    // merge buffer.
+    // LDS: [parity][R][S] exchange float4 {sum dyh, sum dyh*xc, sum x, M2}, then S floats n_w and
+    // S floats 1/n_w (rows with padding only), then the merge buffer.
+    float4 *xchg_base = reinterpret_cast<float4 *>(lds);
     float *nw_tab = lds + 8 * nwaves;
     float *merge = lds + ((8 * nwaves + 2 * S + 3) & ~3);
-    if constexpr (kSync) {
+    if constexpr (kSync && !kFull) {
         if (lane == 0 && g == 0) {
             nw_tab[ws] = (float)n_w;
             nw_tab[S + ws] = 1.0f / (float)n_w;
@@ -192,9 +212,9 @@ void ln_bwd_rows_kernel(RowArgs a)
         constexpr bool kTail = decltype(tail_tag)::value;
         const bool act = kTail ? mm < n_rows : true;
         float xf[kVpt][E], df[kVpt][E];
-        float s_x = 0.f, pivot = 0.f, m2 = 0.f, s_dyh = 0.f, s_dyx = 0.f;
+        float s_x = 0.f, pivot = 0.f, m2 = 0.f, s_dyh = 0.f, s_dyx = 0.f, rstd_saved = 0.f;
         int r = 0;
-        float *xchg = lds + ((parity * R + g) * 4) * S;
+        float4 *xchg = xchg_base + (parity * R + g) * S;
         if (act) {
             r = row_of(mm);
 #pragma unroll
@@ -209,10 +229,12 @@ void ln_bwd_rows_kernel(RowArgs a)
                     }
                 }
             }
+            const float saved_mean = st_mean, saved_rstd = st_rstd;   // this row's, before the prefetch
             if (mm + R < n_rows) load_row(mm + R, xr, dr);
             // pass 1: pivot = the wave's own mean (or the saved row mean)
             if constexpr (kSaved) {
-                pivot = a.mean[r];
+                pivot = saved_mean;
+                rstd_saved = saved_rstd;
             } else {
 #pragma unroll
                 for (int k = 0; k < kVpt; ++k)
@@ -240,53 +262,52 @@ void ln_bwd_rows_kernel(RowArgs a)
                 wave_sum3(m2, s_dyh, s_dyx);
             }
             if constexpr (kSync) {
-                if (lane == 0) {
-                    xchg[ws] = s_dyh;
-                    xchg[S + ws] = s_dyx;
-                    if constexpr (!kSaved) {
-                        xchg[2 * S + ws] = s_x;
-                        xchg[3 * S + ws] = m2;
-                    }
-                }
+                if (lane == 0) xchg[ws] = make_float4(s_dyh, s_dyx, s_x, m2);
             }
         }
         if constexpr (kSync) __syncthreads();
         if (act) {
             float rstd, shift_r = 0.f;   // shift_r = (pivot - mean) * rstd
             if constexpr (kSync) {
+                const int nS = kS > 0 ? kS : S;    // compile-time trip count when kS > 0
+                float4 part[kS > 0 ? kS : 8];
+#pragma unroll
+                for (int w = 0; w < (kS > 0 ? kS : 8); ++w)
+                    part[w] = w < nS ? xchg[w] : make_float4(0.f, 0.f, 0.f, 0.f);
                 if constexpr (kSaved) {
                     float t0 = 0.f, t1 = 0.f;
 #pragma unroll
-                    for (int w = 0; w < 8; ++w)
-                        if (w < S) {
-                            t0 += xchg[w];
-                            t1 += xchg[S + w];
-                        }
+                    for (int w = 0; w < (kS > 0 ? kS : 8); ++w) {
+                        t0 += part[w].x;
+                        t1 += part[w].y;
+                    }
                     s_dyh = t0;
                     s_dyx = t1;
-                    rstd = a.rstd[r];
+                    rstd = rstd_saved;
                 } else {
                     float tot = 0.f;
 #pragma unroll
-                    for (int w = 0; w < 8; ++w)
-                        if (w < S) tot += xchg[2 * S + w];
+                    for (int w = 0; w < (kS > 0 ? kS : 8); ++w) tot += part[w].z;
                     const float mean = tot * a.inv_D;
                     float M2 = 0.f, t0 = 0.f, t1 = 0.f;
 #pragma unroll
-                    for (int w = 0; w < 8; ++w)
-                        if (w < S) {
-                            const float d = xchg[2 * S + w] * nw_tab[S + w] - mean;   // mean_w - mean
-                            M2 += xchg[3 * S + w] + d * d * nw_tab[w];
-                            t0 += xchg[w];
-                            t1 += xchg[S + w] + d * xchg[w];
+                    for (int w = 0; w < (kS > 0 ? kS : 8); ++w) {
+                        if (kS > 0 || w < nS) {
+                            const float nw = kFull ? (float)(kVpt * E * kWave) : nw_tab[w];
+                            const float inw = kFull ? 1.0f / (float)(kVpt * E * kWave) : nw_tab[S + w];
+                            const float d = part[w].z * inw - mean;   // mean_w - mean
+                            M2 += part[w].w + d * d * nw;
+                            t0 += part[w].x;
+                            t1 += part[w].y + d * part[w].x;
                         }
+                    }
                     s_dyh = t0;
                     s_dyx = t1;
                     rstd = rsqrtf(M2 * a.inv_D + a.eps);
                     shift_r = (pivot - mean) * rstd;
                 }
             } else {
-                if constexpr (kSaved) rstd = a.rstd[r];
+                if constexpr (kSaved) rstd = rstd_saved;
                 else rstd = rsqrtf(m2 * a.inv_D + a.eps);
             }
             // pass 3: dx = rstd*(dyh - c2 - xhat*c1), c1 = rstd*mean_d(dyh*(x-mean)), c2 = mean_d(dyh)
