@@ -146,7 +146,8 @@ int gns_estimate(const float *pe_sq, const float *big_sq, int n_groups, int B, f
  * beyond floating-point summation order.  key 0: target number of row chunks of ln_bwd_pegn
  * (0 = automatic); key 1: the same for ln_bwd; key 2: waves per workgroup of the row kernel
  * (0 = automatic, else 1..16); key 3: rows between the sweep starts of consecutive examples,
- * plus one (0 = automatic).  Returns LNPEGN_EINVAL for an unknown key or a value out of range.  Not thread-safe against concurrent launches.
+ * plus one (0 = automatic); key 4: neighbouring chunks on one XCD (0 automatic, 1 never, 2 always).
+ * Returns LNPEGN_EINVAL for an unknown key or a value out of range.  Not thread-safe against concurrent launches.
  */
 int lnpegn_set_tuning(int key, int value);
 

@@ -16,6 +16,7 @@ namespace {
 int g_chunks_pegn = 0;
 int g_chunks_plain = 0;
 int g_waves = 0;
+int g_xcd = -1;        // hand neighbouring chunks to the same XCD: 0 never, 1 always, -1 automatic
 int g_stagger = -1;   // rows between the sweep starts of consecutive examples (-1 = automatic)
 // one-shot profiling events around the row kernel (null = disarmed)
 hipEvent_t g_ev_start = nullptr;
@@ -231,7 +232,10 @@ int run_bwd(bool pegn, bool defer, const void *x, const void *dy, const void *ga
     RowArgs a{};
     a.x = x; a.dy = dy; a.gamma = gamma; a.mean = mean; a.rstd = rstd; a.dx = dx;
     a.part = part; a.pe_gamma_sq = pe_gamma_sq; a.pe_beta_sq = pe_beta_sq;
-    a.Tp = p.Tp; a.stagger = !pegn ? 0 : g_stagger >= 0 ? g_stagger : (T / B > 0 ? T / B : 1); a.C = p.C; a.D = D; a.nvec = p.nvec;
+    a.Tp = p.Tp; a.stagger = !pegn ? 0 : g_stagger >= 0 ? g_stagger : (5 * (int64_t)T / (4 * (int64_t)B) > 0 ? 5 * (int64_t)T / (4 * (int64_t)B) : 1); a.C = p.C; a.D = D; a.nvec = p.nvec;
+    // measured: grouping an example's chunks on one XCD helps wide rows (S >= 4) and is neutral otherwise
+    const bool xcd = g_xcd >= 0 ? g_xcd != 0 : p.S >= 4;
+    a.xcd_chunks = (xcd && p.fast && p.n_slots % 8 == 0) ? (int)(p.n_slots / 8) : 0;
     a.S = p.S; a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.emit_pe = p.emit_pe;
     a.eps = eps; a.inv_D = 1.0f / (float)D;
     if (defer) {
@@ -481,6 +485,10 @@ int lnpegn_set_tuning(int key, int value)
             return LNPEGN_OK;
         case 3:
             g_stagger = value == 0 ? -1 : value - 1;
+            return LNPEGN_OK;
+        case 4:
+            if (value > 2) return LNPEGN_EINVAL;
+            g_xcd = value - 1;          // 0 automatic, 1 never, 2 always
             return LNPEGN_OK;
         default: return LNPEGN_EINVAL;
     }

@@ -41,6 +41,8 @@ struct RowArgs {
     int S;               // waves per row
     int gamma_is_f32;
     int emit_pe;         // C == 1: a chunk is a whole example, its squared norms are final here
+    int xcd_chunks;      // > 0: chunks per XCD; workgroup i (dispatched to XCD i % 8) takes chunk
+                         //      (i % 8) * xcd_chunks + i / 8, so neighbouring chunks share an L2
     float eps;
     float inv_D;
 };
@@ -116,7 +118,7 @@ void ln_bwd_rows_kernel(RowArgs a)
     const int S = kS > 0 ? kS : a.S;
     const int R = nwaves / S;
     const int g = wave / S, ws = wave - g * S;
-    const int chunk = blockIdx.x;
+    const int chunk = a.xcd_chunks > 0 ? (blockIdx.x & 7) * a.xcd_chunks + (blockIdx.x >> 3) : blockIdx.x;
     const int b = chunk / a.C, j = chunk - b * a.C;
     // Chunk j of example b owns rows b*Tp + j + m*C.  Examples sit a power of two apart in
     // memory; starting each sweep at a different row (wrapping around) keeps the concurrent
