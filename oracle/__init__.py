@@ -38,24 +38,27 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def _bind(lib):
+    """Declare the argument types of every oracle entry point on a loaded library."""
+    L, D_, I = ctypes.c_long, ctypes.c_double, ctypes.c_int
+    lib.lnpegn_oracle_ln_stats.argtypes = [_dp, L, L, D_, _dp, _dp]
+    lib.lnpegn_oracle_ln_fwd.argtypes = [_dp, _dp, _dp, L, L, D_, _dp]
+    lib.lnpegn_oracle_ln_bwd_example.argtypes = [_dp, _dp, _dp, L, L, D_, _dp, _dp, _dp]
+    lib.lnpegn_oracle_ln_bwd_pegn.argtypes = [_dp, _dp, _dp, L, L, L, D_] + [_dp] * 8 + [I]
+    lib.lnpegn_oracle_gns_from_norms.argtypes = [D_, D_, D_, D_, _dp]
+    lib.lnpegn_oracle_gns_estimate.argtypes = [_dp, _dp, L, L, D_, _dp]
+    lib.lnpegn_oracle_max_threads.restype = I
+    for name in ("ln_stats", "ln_fwd", "ln_bwd_example", "ln_bwd_pegn", "gns_from_norms", "gns_estimate"):
+        getattr(lib, "lnpegn_oracle_" + name).restype = I
+    return lib
+
+
 def _load():
     global _lib
     with _lock:
         if _lib is None:
             build()
-            lib = ctypes.CDLL(_LIB)
-            L, D_, I = ctypes.c_long, ctypes.c_double, ctypes.c_int
-            lib.lnpegn_oracle_ln_stats.argtypes = [_dp, L, L, D_, _dp, _dp]
-            lib.lnpegn_oracle_ln_fwd.argtypes = [_dp, _dp, _dp, L, L, D_, _dp]
-            lib.lnpegn_oracle_ln_bwd_example.argtypes = [_dp, _dp, _dp, L, L, D_, _dp, _dp, _dp]
-            lib.lnpegn_oracle_ln_bwd_pegn.argtypes = [_dp, _dp, _dp, L, L, L, D_] + [_dp] * 8 + [I]
-            lib.lnpegn_oracle_gns_from_norms.argtypes = [D_, D_, D_, D_, _dp]
-            lib.lnpegn_oracle_gns_estimate.argtypes = [_dp, _dp, L, L, D_, _dp]
-            lib.lnpegn_oracle_max_threads.restype = I
-            for name in ("ln_stats", "ln_fwd", "ln_bwd_example", "ln_bwd_pegn", "gns_from_norms",
-                         "gns_estimate"):
-                getattr(lib, "lnpegn_oracle_" + name).restype = I
-            _lib = lib
+            _lib = _bind(ctypes.CDLL(_LIB))
     return _lib
 
 

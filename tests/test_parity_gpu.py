@@ -276,6 +276,46 @@ def _sampled_dx_check(inp, res, n_rows=64, seed=0):
     assert np.all(row_sum <= budget), float(np.max(row_sum / budget))
 
 
+def test_more_than_2_to_31_elements():
+    """Index arithmetic is 64-bit: B*T*D = 2^31 + 2*8192 elements per tensor (12 GiB for x, dy, dx).
+    Inputs are drawn on the device (seeded) and copied to the host, so both sides read the same
+    bf16 values; the oracle does the whole tensor for the sums and sampled rows for dx."""
+    import torch
+    from paper_2411_00999_amd import binding
+    B, T, D = 4, 65537, 8192
+    assert B * T * D > 2 ** 31
+    gen = torch.Generator(device="cuda").manual_seed(2411)
+    x = torch.empty((B, T, D), dtype=torch.bfloat16, device="cuda")
+    dy = torch.empty((B, T, D), dtype=torch.bfloat16, device="cuda")
+    for b in range(B):                                    # per example: bounds the fp32 temporaries
+        x[b] = (torch.randn((T, D), generator=gen, device="cuda") * 1.5 + 0.25).to(torch.bfloat16)
+        dy[b] = (torch.randn((T, D), generator=gen, device="cuda") * 1e-3).to(torch.bfloat16)
+    gamma = (1.0 + 0.05 * torch.randn(D, generator=gen, device="cuda")).to(torch.bfloat16)
+    eps = 1e-5
+    dx, dg, db, sg, sb, big = binding.ln_bwd_pegn(x, dy, gamma, eps)
+    torch.cuda.synchronize()
+    g64 = gamma.float().cpu().numpy().astype(np.float64)
+    dgamma, dbeta = np.zeros(D), np.zeros(D)
+    s_gamma, s_beta = np.zeros(B), np.zeros(B)
+    for b in range(B):                                    # the oracle, one example at a time
+        xb = x[b].float().cpu().numpy().astype(np.float64)
+        dyb = dy[b].float().cpu().numpy().astype(np.float64)
+        _, gg, gb = oracle.ln_bwd_example(xb, dyb, g64, eps, want_dx=False)
+        dgamma += gg
+        dbeta += gb
+        s_gamma[b], s_beta[b] = np.sum(gg * gg), np.sum(gb * gb)
+        rows = np.unique(np.concatenate([[0, T - 1], np.random.default_rng(b).integers(0, T, 12)]))
+        want = np.stack([oracle.ln_bwd_example(xb[r:r + 1], dyb[r:r + 1], g64, eps)[0][0] for r in rows])
+        got = dx[b][torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        pu.check_close(f"dx[{b}] sampled rows", got, want, pu.TOL_BF16, bf16_output=True)
+        del xb, dyb
+    pu.check_close("dgamma", pu.to_host64(dg), dgamma, pu.TOL_SUMS)
+    pu.check_close("dbeta", pu.to_host64(db), dbeta, pu.TOL_SUMS)
+    np.testing.assert_allclose(pu.to_host64(sg), s_gamma, rtol=pu.TOL_SUMS)
+    np.testing.assert_allclose(pu.to_host64(sb), s_beta, rtol=pu.TOL_SUMS)
+    np.testing.assert_allclose(pu.to_host64(big), [np.sum(dgamma ** 2), np.sum(dbeta ** 2)], rtol=pu.TOL_SUMS)
+
+
 @pytest.mark.parametrize("cfg", [2, 3, 4, 5])
 def test_full_size_workloads(cfg):
     inp = workloads.make_inputs(cfg)
