@@ -65,6 +65,16 @@ int ln_fwd_stats(const void *x, float *mean, float *rstd, int B, int T, int D, l
                  float eps, void *stream);
 
 /*
+ * LayerNorm forward: y = gamma*xhat + beta over the last dimension, and the row statistics the
+ * backward reuses (the forward half of the forward+backward workload measured in Section 5.1).
+ *   x, y      [B,T,D] in dt (y is rounded to dt with round-to-nearest-even; y may alias x)
+ *   gamma,beta [D], both in gamma_dt
+ *   mean,rstd [N] fp32; either may be NULL if not wanted
+ */
+int ln_fwd(const void *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd, int B,
+           int T, int D, lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *stream);
+
+/*
  * Plain LayerNorm backward (no per-example outputs): the comparison kernel for the paper's
  * "zero overhead" claim of Section 5.1.
  *   x, dy     [B,T,D] in dt
@@ -121,6 +131,26 @@ int ln_bwd_pegn_deferred(const void *x, const void *dy, const void *gamma, const
                          size_t workspace_bytes, void *stream);
 int lnpegn_reduce_deferred(void *const *workspaces, int n, int B, int T, int D, lnpegn_dtype dt,
                            void *stream);
+
+/*
+ * The general form of the backward calls above: flags select the per-example outputs
+ * (LNPEGN_PER_EXAMPLE: ln_bwd_pegn; without it pe_gamma_sq, pe_beta_sq, big_sq are ignored), the
+ * deferred reduction (LNPEGN_DEFER) and gradient accumulation (LNPEGN_ACCUMULATE).
+ *
+ * LNPEGN_ACCUMULATE is for training with several micro-batches per optimiser step (the setting
+ * of the paper's timing figure in Section 5.1 and of its batch-size schedule, Section 5.2):
+ * dgamma and dbeta are ADDED to (they must hold valid values, e.g. zeros before the first
+ * micro-batch); big_sq receives the squared norms of the accumulated dgamma and dbeta, so after
+ * the last micro-batch it is ||G_big||^2 of the whole batch; pe_gamma_sq / pe_beta_sq are those
+ * of this micro-batch's B examples, to be placed by the caller at its slice of an [A*B] table.
+ * With A micro-batches of B examples and a loss averaged over all of them, gns_estimate is then
+ * called with B_big = A*B columns per group and pe_scale = A*B.
+ */
+typedef enum { LNPEGN_PER_EXAMPLE = 1, LNPEGN_DEFER = 2, LNPEGN_ACCUMULATE = 4 } lnpegn_flags;
+int ln_bwd_ex(const void *x, const void *dy, const void *gamma, const float *mean, const float *rstd,
+              void *dx, float *dgamma, float *dbeta, float *pe_gamma_sq, float *pe_beta_sq, float *big_sq,
+              int B, int T, int D, lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *workspace,
+              size_t workspace_bytes, unsigned flags, void *stream);
 
 /*
  * Gradient-noise-scale estimate from per-example norms: Section 2.1, Eq. 4 (unbiased |G|^2),

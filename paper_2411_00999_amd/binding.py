@@ -18,7 +18,9 @@ STATUS = {0: "LNPEGN_OK", 1: "LNPEGN_EINVAL", 2: "LNPEGN_EUNSUPPORTED", 3: "LNPE
           4: "LNPEGN_EHIP"}
 EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "ln_fwd_stats", "ln_bwd",
            "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning", "lnpegn_set_profile_events",
-           "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred")
+           "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred",
+           "ln_fwd", "ln_bwd_ex")
+PER_EXAMPLE, DEFER, ACCUMULATE = 1, 2, 4
 
 _lib = None
 
@@ -51,13 +53,16 @@ def load() -> ctypes.CDLL:
     lib.ln_bwd_deferred.argtypes = lib.ln_bwd.argtypes
     lib.ln_bwd_pegn_deferred.argtypes = lib.ln_bwd_pegn.argtypes
     lib.lnpegn_reduce_deferred.argtypes = [ctypes.POINTER(ctypes.c_void_p), i, i, i, i, i, vp]
+    lib.ln_fwd.argtypes = [vp, vp, vp, vp, fp, fp, i, i, i, i, i, f, vp]
+    lib.ln_bwd_ex.argtypes = [vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, i, i, i, i, i, f, vp, sz,
+                              ctypes.c_uint, vp]
     lib.gns_estimate.argtypes = [fp, fp, i, i, f, fp, vp]
     lib.lnpegn_set_tuning.argtypes = [i, i]
     lib.lnpegn_set_profile_events.argtypes = [vp, vp]
     lib.lnpegn_stream_probe.argtypes = [vp, vp, vp, sz, i, vp]
     for name in ("ln_fwd_stats", "ln_bwd", "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning",
                  "lnpegn_set_profile_events", "lnpegn_stream_probe", "ln_bwd_deferred",
-                 "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred"):
+                 "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred", "ln_fwd", "ln_bwd_ex"):
         getattr(lib, name).restype = i
     _lib = lib
     return lib
@@ -134,6 +139,38 @@ def ln_fwd_stats(x, eps: float, mean=None, rstd=None, stream=None):
     if rc:
         raise LnpegnError("ln_fwd_stats", rc)
     return mean, rstd
+
+
+def ln_fwd(x, gamma, beta, eps: float, y=None, mean=None, rstd=None, want_stats=True, stream=None):
+    """LayerNorm forward -> (y, mean[B,T], rstd[B,T]); the statistics are None if not wanted."""
+    torch = _torch()
+    B, T, D = _check3(x)
+    y = torch.empty_like(x) if y is None else y
+    if want_stats:
+        mean = torch.empty((B, T), dtype=torch.float32, device=x.device) if mean is None else mean
+        rstd = torch.empty((B, T), dtype=torch.float32, device=x.device) if rstd is None else rstd
+    rc = load().ln_fwd(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(mean), _ptr(rstd), B, T, D,
+                       _dt(x), _dt(gamma), eps, _stream(stream))
+    if rc:
+        raise LnpegnError("ln_fwd", rc)
+    return y, mean, rstd
+
+
+def ln_bwd_ex(x, dy, gamma, eps: float, flags: int, dgamma, dbeta, mean=None, rstd=None, dx=None,
+              pe_gamma_sq=None, pe_beta_sq=None, big_sq=None, workspace=None, stream=None):
+    """General backward (flags: PER_EXAMPLE | DEFER | ACCUMULATE); the caller passes dgamma and
+    dbeta, which ACCUMULATE adds to.  Returns dx."""
+    torch = _torch()
+    B, T, D = _check3(x)
+    _check3(dy)
+    dx = torch.empty_like(x) if dx is None else dx
+    workspace = alloc_workspace(B, T, D, _dt(x), x.device) if workspace is None else workspace
+    rc = load().ln_bwd_ex(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(dx), _ptr(dgamma),
+                          _ptr(dbeta), _ptr(pe_gamma_sq), _ptr(pe_beta_sq), _ptr(big_sq), B, T, D, _dt(x),
+                          _dt(gamma), eps, _ptr(workspace), workspace.numel(), flags, _stream(stream))
+    if rc:
+        raise LnpegnError("ln_bwd_ex", rc)
+    return dx
 
 
 def ln_bwd(x, dy, gamma, eps: float, mean=None, rstd=None, dx=None, dgamma=None, dbeta=None,

@@ -207,7 +207,7 @@ hipError_t launch_rows(const Plan &p, const RowArgs &a, const RowLaunch &rl)
     return hipErrorInvalidValue;
 }
 
-int run_bwd(bool pegn, bool defer, const void *x, const void *dy, const void *gamma, const float *mean,
+int run_bwd(bool pegn, bool defer, bool accumulate, const void *x, const void *dy, const void *gamma, const float *mean,
             const float *rstd, void *dx, float *dgamma, float *dbeta, float *pe_gamma_sq,
             float *pe_beta_sq, float *big_sq, int B, int T, int D, int dt, int gamma_dt, float eps,
             void *workspace, size_t workspace_bytes, void *stream)
@@ -241,7 +241,7 @@ int run_bwd(bool pegn, bool defer, const void *x, const void *dy, const void *ga
     if (defer) {
         a.defer = reinterpret_cast<DeferHeader *>(ws);
         a.hdr = DeferHeader{dgamma, dbeta, pe_gamma_sq, pe_beta_sq, pegn ? big_sq : nullptr,
-                            (int)p.n_slots, p.gs, p.G1, p.pe_from_groups ? 1 : 0};
+                            (int)p.n_slots, p.gs, p.G1, p.pe_from_groups ? 1 : 0, accumulate ? 1 : 0};
     }
 
     hipError_t e;
@@ -266,6 +266,7 @@ int run_bwd(bool pegn, bool defer, const void *x, const void *dy, const void *ga
     ra.big_sq = pegn ? big_sq : nullptr;
     ra.n_slots = (int)p.n_slots; ra.gs = p.gs; ra.G1 = p.G1; ra.D = D; ra.ntile = p.ntile;
     ra.pe_from_groups = p.pe_from_groups;
+    ra.accumulate = accumulate;
     reduce_groups_kernel<<<dim3((unsigned)p.G1, (unsigned)p.ntile), dim3(kTile), 0, s>>>(ra);
     if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
     const bool need_scalars = p.pe_from_groups || ra.big_sq != nullptr;
@@ -313,16 +314,16 @@ __global__ __launch_bounds__(256) void stream_probe_kernel(const uint4 *a, const
     }
 }
 
-template <typename T>
-hipError_t launch_stats(const void *x, float *mean, float *rstd, int64_t N, int D, float eps,
-                        hipStream_t s)
+template <typename T, bool kWriteY>
+hipError_t launch_fwd(FwdArgs a, bool vector_ok, hipStream_t s)
 {
     constexpr int E = Vec<T>::kElems;
-    StatsArgs a{x, mean, rstd, N, D, 0, eps, 1.0f / (float)D};
-    const bool fast = (D % E == 0) && (D / E <= 64 * (16 / E) * 8) && aligned16(x);
+    const int D = a.D;
+    const int64_t N = a.N;
+    const bool fast = vector_ok && (D % E == 0) && (D / E <= 64 * (16 / E) * 8);
     if (!fast) {
         const unsigned grid = (unsigned)(N < 4096 ? N : 4096);
-        ln_stats_generic_kernel<T><<<dim3(grid), dim3(256), 0, s>>>(a);
+        ln_fwd_generic_kernel<T, kWriteY><<<dim3(grid), dim3(256), 0, s>>>(a);
         return hipGetLastError();
     }
     a.nvec = D / E;
@@ -331,10 +332,10 @@ hipError_t launch_stats(const void *x, float *mean, float *rstd, int64_t N, int 
         const int64_t want = (N + 3) / 4;
         const dim3 grid((unsigned)(want < 4096 ? want : 4096)), block(256);
         switch (vpt) {
-            case 1: ln_stats_kernel<T, 1, false><<<grid, block, 0, s>>>(a); break;
-            case 2: ln_stats_kernel<T, 2, false><<<grid, block, 0, s>>>(a); break;
-            case 3: ln_stats_kernel<T, 3, false><<<grid, block, 0, s>>>(a); break;
-            case 4: ln_stats_kernel<T, 4, false><<<grid, block, 0, s>>>(a); break;
+            case 1: ln_fwd_kernel<T, 1, false, kWriteY><<<grid, block, 0, s>>>(a); break;
+            case 2: ln_fwd_kernel<T, 2, false, kWriteY><<<grid, block, 0, s>>>(a); break;
+            case 3: ln_fwd_kernel<T, 3, false, kWriteY><<<grid, block, 0, s>>>(a); break;
+            case 4: ln_fwd_kernel<T, 4, false, kWriteY><<<grid, block, 0, s>>>(a); break;
             default: return hipErrorInvalidValue;
         }
     } else {
@@ -342,10 +343,10 @@ hipError_t launch_stats(const void *x, float *mean, float *rstd, int64_t N, int 
         const int vpt = ceil_div(a.nvec, 64 * waves);
         const dim3 grid((unsigned)(N < 4096 ? N : 4096)), block(64 * waves);
         switch (vpt) {
-            case 1: ln_stats_kernel<T, 1, true><<<grid, block, 0, s>>>(a); break;
-            case 2: ln_stats_kernel<T, 2, true><<<grid, block, 0, s>>>(a); break;
-            case 3: ln_stats_kernel<T, 3, true><<<grid, block, 0, s>>>(a); break;
-            case 4: ln_stats_kernel<T, 4, true><<<grid, block, 0, s>>>(a); break;
+            case 1: ln_fwd_kernel<T, 1, true, kWriteY><<<grid, block, 0, s>>>(a); break;
+            case 2: ln_fwd_kernel<T, 2, true, kWriteY><<<grid, block, 0, s>>>(a); break;
+            case 3: ln_fwd_kernel<T, 3, true, kWriteY><<<grid, block, 0, s>>>(a); break;
+            case 4: ln_fwd_kernel<T, 4, true, kWriteY><<<grid, block, 0, s>>>(a); break;
             default: return hipErrorInvalidValue;
         }
     }
@@ -390,9 +391,28 @@ int ln_fwd_stats(const void *x, float *mean, float *rstd, int B, int T, int D, l
     if (!dtype_ok(dt)) return LNPEGN_EUNSUPPORTED;
     if (!x || !mean || !rstd) return LNPEGN_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t N = (int64_t)B * T;
-    const hipError_t e = dt == LNPEGN_BF16 ? launch_stats<bf16_t>(x, mean, rstd, N, D, eps, s)
-                                           : launch_stats<float>(x, mean, rstd, N, D, eps, s);
+    FwdArgs a{};
+    a.x = x; a.mean = mean; a.rstd = rstd; a.N = (int64_t)B * T; a.D = D; a.eps = eps;
+    a.inv_D = 1.0f / (float)D;
+    const hipError_t e = dt == LNPEGN_BF16 ? launch_fwd<bf16_t, false>(a, aligned16(x), s)
+                                           : launch_fwd<float, false>(a, aligned16(x), s);
+    return e == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+}
+
+int ln_fwd(const void *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd, int B,
+           int T, int D, lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *stream)
+{
+    if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
+    if (!dtype_ok(dt) || !dtype_ok(gamma_dt)) return LNPEGN_EUNSUPPORTED;
+    if (!x || !gamma || !beta || !y) return LNPEGN_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    FwdArgs a{};
+    a.x = x; a.gamma = gamma; a.beta = beta; a.y = y; a.mean = mean; a.rstd = rstd;
+    a.N = (int64_t)B * T; a.D = D; a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.eps = eps;
+    a.inv_D = 1.0f / (float)D;
+    const bool vec = aligned16(x) && aligned16(y) && aligned16(gamma) && aligned16(beta);
+    const hipError_t e = dt == LNPEGN_BF16 ? launch_fwd<bf16_t, true>(a, vec, s)
+                                           : launch_fwd<float, true>(a, vec, s);
     return e == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
 }
 
@@ -400,7 +420,7 @@ int ln_bwd(const void *x, const void *dy, const void *gamma, const float *mean, 
            void *dx, float *dgamma, float *dbeta, int B, int T, int D, lnpegn_dtype dt,
            lnpegn_dtype gamma_dt, float eps, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return run_bwd(false, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, nullptr, nullptr, nullptr, B, T,
+    return run_bwd(false, false, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, nullptr, nullptr, nullptr, B, T,
                    D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
 }
 
@@ -410,7 +430,7 @@ int ln_bwd_pegn(const void *x, const void *dy, const void *gamma, const float *m
                 lnpegn_dtype gamma_dt, float eps, void *workspace, size_t workspace_bytes,
                 void *stream)
 {
-    return run_bwd(true, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq,
+    return run_bwd(true, false, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq,
                    B, T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
 }
 
@@ -419,7 +439,7 @@ int ln_bwd_deferred(const void *x, const void *dy, const void *gamma, const floa
                     lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *workspace,
                     size_t workspace_bytes, void *stream)
 {
-    return run_bwd(false, true, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, nullptr, nullptr, nullptr, B,
+    return run_bwd(false, true, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, nullptr, nullptr, nullptr, B,
                    T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
 }
 
@@ -429,8 +449,20 @@ int ln_bwd_pegn_deferred(const void *x, const void *dy, const void *gamma, const
                          lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *workspace,
                          size_t workspace_bytes, void *stream)
 {
-    return run_bwd(true, true, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq,
+    return run_bwd(true, true, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq,
                    big_sq, B, T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
+}
+
+int ln_bwd_ex(const void *x, const void *dy, const void *gamma, const float *mean, const float *rstd,
+              void *dx, float *dgamma, float *dbeta, float *pe_gamma_sq, float *pe_beta_sq, float *big_sq,
+              int B, int T, int D, lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *workspace,
+              size_t workspace_bytes, unsigned flags, void *stream)
+{
+    if (flags & ~(unsigned)(LNPEGN_PER_EXAMPLE | LNPEGN_DEFER | LNPEGN_ACCUMULATE)) return LNPEGN_EINVAL;
+    const bool pegn = (flags & LNPEGN_PER_EXAMPLE) != 0;
+    return run_bwd(pegn, (flags & LNPEGN_DEFER) != 0, (flags & LNPEGN_ACCUMULATE) != 0, x, dy, gamma, mean,
+                   rstd, dx, dgamma, dbeta, pegn ? pe_gamma_sq : nullptr, pegn ? pe_beta_sq : nullptr,
+                   pegn ? big_sq : nullptr, B, T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
 }
 
 int lnpegn_reduce_deferred(void *const *workspaces, int n, int B, int T, int D, lnpegn_dtype dt,

@@ -27,12 +27,13 @@ struct ReduceArgs {
     int D;
     int ntile;
     int pe_from_groups;    // groups are examples: emit their squared norms (Appendix B steps 2, 6)
+    int accumulate;        // dgamma, dbeta: add to what is there (gradient accumulation) instead of overwrite
 };
 
 // What a deferred backward call leaves at the start of its workspace for the batched reduction.
 struct DeferHeader {
     float *dgamma, *dbeta, *pe_gamma_sq, *pe_beta_sq, *big_sq;
-    int n_slots, gs, G1, pe_from_groups;
+    int n_slots, gs, G1, pe_from_groups, accumulate;
 };
 
 // These kernels are a handful of dependent memory round trips long, so every level issues its
@@ -96,8 +97,12 @@ __device__ __forceinline__ void reduce_groups_body(const ReduceArgs &a, int g, i
         v0 += wsum[w][comp][src_lane];
         v1 += wsum[w][4 + comp][src_lane];
     }
-    const float f0 = (float)v0, f1 = (float)v1;
     const bool single = a.G1 == 1;
+    if (single && a.accumulate && col < a.D) {
+        v0 += (double)a.dgamma[col];
+        v1 += (double)a.dbeta[col];
+    }
+    const float f0 = (float)v0, f1 = (float)v1;
     if (col < a.D) {
         if (single) {
             a.dgamma[col] = f0;
@@ -181,6 +186,10 @@ __device__ __forceinline__ void reduce_final_body(const ReduceArgs &a)
         for (int col = tid; col < a.D; col += 1024) {
             double s0, s1;
             sum_groups(a.grp, a.G1, a.D, col, s0, s1);
+            if (a.accumulate) {
+                s0 += (double)a.dgamma[col];
+                s1 += (double)a.dbeta[col];
+            }
             const float f0 = (float)s0, f1 = (float)s1;
             a.dgamma[col] = f0;
             a.dbeta[col] = f1;
@@ -233,6 +242,7 @@ __device__ __forceinline__ ReduceArgs batch_layer_args(const BatchArgs &b, int l
     a.pe_gamma_sq = h.pe_gamma_sq; a.pe_beta_sq = h.pe_beta_sq; a.big_sq = h.big_sq;
     a.n_slots = h.n_slots; a.gs = h.gs; a.G1 = h.G1; a.D = b.D; a.ntile = b.ntile;
     a.pe_from_groups = h.pe_from_groups;
+    a.accumulate = h.accumulate;
     return a;
 }
 
@@ -261,6 +271,10 @@ __global__ __launch_bounds__(kTile) void reduce_final_tiles_kernel(ReduceArgs a)
     double s0 = 0.0, s1 = 0.0;
     if (col < a.D) {
         sum_groups(a.grp, a.G1, a.D, col, s0, s1);
+        if (a.accumulate) {
+            s0 += (double)a.dgamma[col];
+            s1 += (double)a.dbeta[col];
+        }
         a.dgamma[col] = (float)s0;
         a.dbeta[col] = (float)s1;
     }

@@ -471,22 +471,27 @@ __global__ void ln_bwd_rows_generic_kernel(RowArgs a)
 }
 
 // ---------------------------------------------------------------------------------------
-// Row statistics (forward): mean and rstd of every row, two-pass variance in fp32.
-// Wave mode only needs a grid-stride loop over rows; wide rows use the whole workgroup.
+// Forward: mean and rstd of every row (two-pass variance in fp32) and, with kWriteY, the
+// LayerNorm output y = gamma*xhat + beta.  Rows are taken in a grid-stride sweep (one moving
+// window of memory); wide rows use the whole workgroup.
 // ---------------------------------------------------------------------------------------
-struct StatsArgs {
+struct FwdArgs {
     const void *x;
-    float *mean;
-    float *rstd;
+    const void *gamma;  // kWriteY only
+    const void *beta;   // kWriteY only
+    void *y;            // kWriteY only
+    float *mean;        // may be null
+    float *rstd;        // may be null
     int64_t N;
     int D;
     int nvec;
+    int gamma_is_f32;
     float eps;
     float inv_D;
 };
 
-template <typename T, int kVpt, bool kMulti>
-__global__ void ln_stats_kernel(StatsArgs a)
+template <typename T, int kVpt, bool kMulti, bool kWriteY>
+__global__ void ln_fwd_kernel(FwdArgs a)
 {
     using V = Vec<T>;
     using Raw = typename V::Raw;
@@ -502,7 +507,16 @@ __global__ void ln_stats_kernel(StatsArgs a)
         vidx[k] = kMulti ? (k * nwaves + wave) * kWave + lane : k * kWave + lane;
         ok[k] = vidx[k] < a.nvec;
     }
+    float gm[kWriteY ? kVpt : 1][E], bt[kWriteY ? kVpt : 1][E];
+    if constexpr (kWriteY) {
+#pragma unroll
+        for (int k = 0; k < kVpt; ++k) {
+            load_gamma_vec<T>(a.gamma, a.gamma_is_f32, ok[k] ? vidx[k] : 0, gm[k]);
+            load_gamma_vec<T>(a.beta, a.gamma_is_f32, ok[k] ? vidx[k] : 0, bt[k]);
+        }
+    }
     const Raw *xv = static_cast<const Raw *>(a.x);
+    Raw *yv = static_cast<Raw *>(a.y);
     const int64_t first = kMulti ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * nwaves + wave;
     const int64_t stride = kMulti ? (int64_t)gridDim.x : (int64_t)gridDim.x * nwaves;
     for (int64_t r = first; r < a.N; r += stride) {
@@ -530,6 +544,7 @@ __global__ void ln_stats_kernel(StatsArgs a)
 #pragma unroll
             for (int e = 0; e < E; ++e) {
                 const float c = ok[k] ? xf[k][e] - mean : 0.f;
+                xf[k][e] = c;
                 ss += c * c;
             }
         ss = wave_sum(ss);
@@ -540,15 +555,25 @@ __global__ void ln_stats_kernel(StatsArgs a)
             for (int w = 0; w < nwaves; ++w) ss += slots[1][w];
             __syncthreads();  // slots are rewritten by the next row
         }
-        if (threadIdx.x == (kMulti ? 0 : wave * kWave) ) {
-            a.mean[r] = mean;
-            a.rstd[r] = rsqrtf(ss * a.inv_D + a.eps);
+        const float rstd = rsqrtf(ss * a.inv_D + a.eps);
+        if (threadIdx.x == (kMulti ? 0 : wave * kWave)) {
+            if (a.mean) a.mean[r] = mean;
+            if (a.rstd) a.rstd[r] = rstd;
+        }
+        if constexpr (kWriteY) {
+#pragma unroll
+            for (int k = 0; k < kVpt; ++k) {
+                float o[E];
+#pragma unroll
+                for (int e = 0; e < E; ++e) o[e] = xf[k][e] * rstd * gm[k][e] + bt[k][e];
+                if (ok[k]) V::store_stream(yv + r * a.nvec + vidx[k], V::pack(o));
+            }
         }
     }
 }
 
-template <typename T>
-__global__ void ln_stats_generic_kernel(StatsArgs a)
+template <typename T, bool kWriteY>
+__global__ void ln_fwd_generic_kernel(FwdArgs a)
 {
     __shared__ float slots[8];
     const int tid = threadIdx.x, nt = blockDim.x;
@@ -563,9 +588,18 @@ __global__ void ln_stats_generic_kernel(StatsArgs a)
             ss += c * c;
         }
         ss = block_sum(ss, slots);
+        const float rstd = rsqrtf(ss * a.inv_D + a.eps);
         if (tid == 0) {
-            a.mean[r] = mean;
-            a.rstd[r] = rsqrtf(ss * a.inv_D + a.eps);
+            if (a.mean) a.mean[r] = mean;
+            if (a.rstd) a.rstd[r] = rstd;
+        }
+        if constexpr (kWriteY) {
+            for (int k = tid; k < a.D; k += nt) {
+                const float xhat = (load_elem<T>(a.x, base + k) - mean) * rstd;
+                store_elem<T>(a.y, base + k,
+                              xhat * load_gamma(a.gamma, a.gamma_is_f32, k) +
+                                  load_gamma(a.beta, a.gamma_is_f32, k));
+            }
         }
     }
 }

@@ -44,6 +44,49 @@ def test_hand_worked_example_exact():
         assert est[key] == pytest.approx(e[key], rel=1e-13), key
 
 
+def test_hand_worked_forward():
+    with open(os.path.join(GOLDEN, "ln_pegn_hand_example.json")) as f:
+        g = json.load(f)
+    y = oracle.ln_fwd(np.array(g["x"], float), np.array(g["gamma"], float), np.array(g["beta_fwd"], float),
+                      g["eps"])
+    np.testing.assert_allclose(y, np.array(g["expected"]["y_with_beta_fwd"], float), rtol=1e-14, atol=1e-14)
+
+
+def test_forward_matches_library():
+    import torch
+    import torch.nn.functional as F
+    x, _, gamma, beta = _rand_case(41, 3, 5, 37, offset=-2.0)
+    y = oracle.ln_fwd(x, gamma, beta, 1e-5)
+    want = F.layer_norm(torch.tensor(x), (37,), torch.tensor(gamma), torch.tensor(beta), 1e-5).numpy()
+    np.testing.assert_allclose(y, want, rtol=1e-12, atol=1e-13)
+
+
+def test_gradient_accumulation_is_the_big_batch():
+    """A micro-batches of B examples, loss averaged over all A*B examples: summing the micro-batch
+    gradients and concatenating the per-example norms is the same as one batch of A*B examples,
+    with B_big = A*B and pe_scale = A*B in the estimator."""
+    A, B, T, D = 3, 4, 5, 24
+    x, dy, gamma, _ = _rand_case(43, A * B, T, D)
+    whole = oracle.ln_bwd_pegn(x, dy, gamma, 1e-5)
+    dgamma, dbeta = np.zeros(D), np.zeros(D)
+    sg, sb = [], []
+    for a in range(A):
+        part = oracle.ln_bwd_pegn(x[a * B:(a + 1) * B], dy[a * B:(a + 1) * B], gamma, 1e-5)
+        dgamma += part["dgamma"]
+        dbeta += part["dbeta"]
+        sg.append(part["s_gamma"])
+        sb.append(part["s_beta"])
+    np.testing.assert_allclose(dgamma, whole["dgamma"], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(dbeta, whole["dbeta"], rtol=1e-12, atol=1e-14)
+    np.testing.assert_array_equal(np.concatenate(sg), whole["s_gamma"])
+    big = np.array([np.sum(dgamma ** 2), np.sum(dbeta ** 2)])
+    est_acc = oracle.gns_estimate(np.stack([np.concatenate(sg), np.concatenate(sb)]), big, pe_scale=A * B)
+    est_whole = oracle.gns_estimate(np.stack([whole["s_gamma"], whole["s_beta"]]), whole["big_sq"],
+                                    pe_scale=A * B)
+    for k in est_whole:
+        assert est_acc[k] == pytest.approx(est_whole[k], rel=1e-10)
+
+
 # ---------------------------------------------------------------- P1 finite differences
 def _loss(x, dy, gamma, beta, eps):
     return float(np.sum(dy * oracle.ln_fwd(x, gamma, beta, eps)))

@@ -240,6 +240,69 @@ def test_deferred_reduction_matches_immediate_calls_bitwise(cfg, B, T, D):
             assert torch.equal(u, v)
 
 
+# ------------------------------------------------------------------ forward, accumulation
+@pytest.mark.parametrize("cfg,B,T,D", [(1, 4, 128, 256), (2, 3, 37, 768), (3, 2, 50, 2048), (5, 2, 9, 8192),
+                                      (1, 2, 7, 257), (2, 2, 5, 1001)])
+def test_forward_against_oracle(cfg, B, T, D):
+    import torch
+    from paper_2411_00999_amd import binding
+    inp = workloads.make_inputs(cfg, B=B, T=T, D=D)
+    x, gamma, beta = (pu.to_device(a, inp.dtype) for a in (inp.x, inp.gamma, inp.beta))
+    y, mean, rstd = binding.ln_fwd(x, gamma, beta, inp.eps)
+    torch.cuda.synchronize()
+    want = oracle.ln_fwd(inp.x, inp.gamma, inp.beta, inp.eps)
+    bf = inp.dtype == "bf16"
+    pu.check_close("y", pu.to_host64(y), want, pu.TOL_BF16 if bf else pu.TOL_F32, bf16_output=bf)
+    m, r = oracle.ln_stats(inp.x, inp.eps)
+    pu.check_close("mean", pu.to_host64(mean), m, pu.TOL_F32, floor_rms=float(np.sqrt(np.mean(inp.x.astype(np.float64) ** 2))))
+    np.testing.assert_allclose(pu.to_host64(rstd), r, rtol=pu.TOL_F32)
+    y2, none_m, none_r = binding.ln_fwd(x, gamma, beta, inp.eps, want_stats=False)
+    torch.cuda.synchronize()
+    assert none_m is None and none_r is None and torch.equal(y, y2)
+    # the saved statistics feed the backward
+    dy = pu.to_device(inp.dy, inp.dtype)
+    a = binding.ln_bwd_pegn(x, dy, gamma, inp.eps, mean=mean, rstd=rstd)
+    m2, r2 = binding.ln_fwd_stats(x, inp.eps)
+    torch.cuda.synchronize()
+    assert torch.equal(m2, mean) and torch.equal(r2, rstd)
+
+
+@pytest.mark.parametrize("cfg,B,T,D,defer", [(3, 4, 40, 2048, False), (2, 3, 21, 768, False),
+                                            (4, 300, 2, 1024, False), (3, 4, 40, 2048, True), (1, 2, 9, 257, True)])
+def test_gradient_accumulation_over_micro_batches(cfg, B, T, D, defer):
+    """A micro-batches through LNPEGN_ACCUMULATE == the oracle on the concatenated batch."""
+    import torch
+    from paper_2411_00999_amd import binding
+    A = 3
+    inp = workloads.make_inputs(cfg, B=A * B, T=T, D=D)
+    ref = oracle.ln_bwd_pegn(inp.x, inp.dy, inp.gamma, inp.eps, want_pe=False)
+    dt_code = binding.BF16 if inp.dtype == "bf16" else binding.F32
+    f32 = dict(dtype=torch.float32, device="cuda")
+    dgamma, dbeta = torch.zeros(D, **f32), torch.zeros(D, **f32)
+    pe = torch.zeros((2, A * B), **f32)
+    big = torch.zeros(2, **f32)
+    gamma = pu.to_device(inp.gamma, inp.dtype)
+    flags = binding.PER_EXAMPLE | binding.ACCUMULATE | (binding.DEFER if defer else 0)
+    dxs = []
+    for a in range(A):
+        sl = slice(a * B, (a + 1) * B)
+        x, dy = pu.to_device(inp.x[sl], inp.dtype), pu.to_device(inp.dy[sl], inp.dtype)
+        ws = binding.alloc_workspace(B, T, D, dt_code)
+        dxs.append(binding.ln_bwd_ex(x, dy, gamma, inp.eps, flags, dgamma, dbeta,
+                                     pe_gamma_sq=pe[0, sl], pe_beta_sq=pe[1, sl], big_sq=big, workspace=ws))
+        if defer:
+            binding.reduce_deferred([ws], B, T, D, dt_code)
+    torch.cuda.synchronize()
+    res = dict(dx=np.concatenate([pu.to_host64(d) for d in dxs]), dgamma=pu.to_host64(dgamma),
+               dbeta=pu.to_host64(dbeta), s_gamma=pu.to_host64(pe[0]), s_beta=pu.to_host64(pe[1]),
+               big_sq=pu.to_host64(big))
+    pu.compare_with_oracle(inp, res, ref)
+    out = binding.gns_estimate(pe, big, float(A * B))
+    torch.cuda.synchronize()
+    want = oracle.gns_estimate(np.stack([ref["s_gamma"], ref["s_beta"]]), ref["big_sq"], float(A * B))
+    _check_gns(out.cpu().numpy().astype(np.float64), want, A * B)
+
+
 # ------------------------------------------------------------------ estimator alone
 @pytest.mark.parametrize("n_groups,B", [(1, 2), (2, 8), (96, 16), (3, 513)])
 def test_gns_estimate_same_norms_both_sides(n_groups, B):
