@@ -216,6 +216,37 @@ def main():
         fused_step()     # leave the outputs of the mode being reported in place
         torch.cuda.synchronize()
 
+    # ---- forward + backward with gradient accumulation (the workload of the paper's timing figure
+    #      in Section 5.1): ln_fwd saves the statistics, ln_bwd_ex(PER_EXAMPLE|ACCUMULATE|DEFER) reuses them
+    fwd_bwd = None
+    if not args.only_fused:
+        y_buf = torch.empty_like(layers[0]["x"])
+        beta = torch.zeros(D, dtype=layers[0]["gamma"].dtype, device="cuda")
+        st_mean = torch.empty((B, T), dtype=torch.float32, device="cuda")
+        st_rstd = torch.empty((B, T), dtype=torch.float32, device="cuda")
+        flags = binding.PER_EXAMPLE | binding.ACCUMULATE | binding.DEFER
+
+        def fwd_bwd_step():
+            for L in layers:
+                binding.ln_fwd(L["x"], L["gamma"], beta, eps, y=y_buf, mean=st_mean, rstd=st_rstd)
+                binding.ln_bwd_ex(L["x"], L["dy"], L["gamma"], eps, flags, L["dgamma"], L["dbeta"],
+                                  mean=st_mean, rstd=st_rstd, dx=L["dx"], pe_gamma_sq=L["pe_g"],
+                                  pe_beta_sq=L["pe_b"], big_sq=L["big"], workspace=L["ws"])
+            binding.reduce_deferred(all_ws, B, T, D, sh["dt_code"])
+            binding.gns_estimate(sh["pe_all"], sh["big_all"], float(B), out=sh["gns"])
+
+        t_fb = timed(fwd_bwd_step, 1, max(2, args.steps // 2))
+        fb_bytes = (5 * N * D * esz + 16 * N) * n_layers      # fwd: read x, write y, 8N stats; bwd: 3ND + 8N
+        fwd_bwd = {"ms_per_step": round(t_fb * 1e3, 4), "GBps": round(fb_bytes / t_fb / 1e9, 2),
+                   "algorithmic_bytes_per_step": fb_bytes,
+                   "what": "ln_fwd + ln_bwd_ex(per-example, accumulate, deferred) per layer, saved statistics"}
+        log(f"fwd+bwd with accumulation: {t_fb * 1e3:.3f} ms/step  {fb_bytes / t_fb / 1e9:.1f} GB/s")
+        for L in layers:                 # accumulation left sums of several steps behind: start clean
+            L["dgamma"].zero_()
+            L["dbeta"].zero_()
+        fused_step()
+        torch.cuda.synchronize()
+
     # ---- dominant kernel: HIP events around the row-streaming kernel, on its own stream ----
     hip = HipEvents()
     pairs = [(hip.create(), hip.create()) for _ in layers]
@@ -334,6 +365,7 @@ def main():
         f"{other}_reduction": {"fused_ms_per_step": round(t_fused_o * 1e3, 4),
                                "plain_ms_per_step": round(t_plain_o * 1e3, 4),
                                "fused_GBps": round(bytes_per_step / t_fused_o / 1e9, 2)},
+        "fwd_bwd_accumulate": fwd_bwd,
         "gns": {"g_small_sq": gns[0], "g_big_sq": gns[1], "G2": gns[2], "S": gns[3], "B_simple": gns[4]},
         "roofline": {
             "kernel": "ln_bwd_rows_kernel (fused call)",
