@@ -48,7 +48,11 @@ def _bind(lib):
     lib.lnpegn_oracle_gns_from_norms.argtypes = [D_, D_, D_, D_, _dp]
     lib.lnpegn_oracle_gns_estimate.argtypes = [_dp, _dp, L, L, D_, _dp]
     lib.lnpegn_oracle_max_threads.restype = I
-    for name in ("ln_stats", "ln_fwd", "ln_bwd_example", "ln_bwd_pegn", "gns_from_norms", "gns_estimate"):
+    lib.lnpegn_oracle_rms_fwd.argtypes = [_dp, _dp, L, L, D_, _dp, _dp]
+    lib.lnpegn_oracle_rms_bwd_example.argtypes = [_dp, _dp, _dp, L, L, D_, _dp, _dp]
+    lib.lnpegn_oracle_rms_bwd_pegn.argtypes = [_dp, _dp, _dp, L, L, L, D_] + [_dp] * 5 + [I]
+    for name in ("ln_stats", "ln_fwd", "ln_bwd_example", "ln_bwd_pegn", "gns_from_norms", "gns_estimate",
+                 "rms_fwd", "rms_bwd_example", "rms_bwd_pegn"):
         getattr(lib, "lnpegn_oracle_" + name).restype = I
     return lib
 
@@ -142,6 +146,51 @@ def ln_bwd_pegn(x, dy, gamma, eps, want_dx=True, want_pe=True, nthreads=0):
         _p(out["s_beta"]), _p(out["big_sq"]), int(nthreads))
     if rc:
         raise ValueError(f"oracle ln_bwd_pegn rc={rc}")
+    return out
+
+
+def rms_fwd(x, gamma, eps):
+    """RMSNorm forward -> (y, rstd): y = gamma * x * rstd, rstd = 1/sqrt(mean_d x^2 + eps)."""
+    x = _c(x)
+    D = x.shape[-1]
+    gamma = _c(gamma, (D,))
+    y = np.empty_like(x)
+    rstd = np.empty(x.size // D)
+    rc = _load().lnpegn_oracle_rms_fwd(_p(x), _p(gamma), x.size // D, D, float(eps), _p(y), _p(rstd))
+    if rc:
+        raise ValueError(f"oracle rms_fwd rc={rc}")
+    return y, rstd.reshape(x.shape[:-1])
+
+
+def rms_bwd_example(x, dy, gamma, eps, want_dx=True):
+    """RMSNorm backward of ONE example x[T,D] -> (dx or None, g_gamma[D])."""
+    x = _c(x)
+    if x.ndim != 2:
+        raise ValueError("x must be [T,D]")
+    T, D = x.shape
+    dy, gamma = _c(dy, (T, D)), _c(gamma, (D,))
+    dx = np.empty_like(x) if want_dx else None
+    gg = np.empty(D)
+    rc = _load().lnpegn_oracle_rms_bwd_example(_p(x), _p(dy), _p(gamma), T, D, float(eps), _p(dx), _p(gg))
+    if rc:
+        raise ValueError(f"oracle rms_bwd_example rc={rc}")
+    return dx, gg
+
+
+def rms_bwd_pegn(x, dy, gamma, eps, want_dx=True, want_pe=True, nthreads=0):
+    """RMSNorm brute force over [B,T,D] -> dict(dx, pe_gamma, dgamma, s_gamma, big_sq[1])."""
+    x = _c(x)
+    if x.ndim != 3:
+        raise ValueError("x must be [B,T,D]")
+    B, T, D = x.shape
+    dy, gamma = _c(dy, (B, T, D)), _c(gamma, (D,))
+    out = dict(dx=np.empty_like(x) if want_dx else None, pe_gamma=np.empty((B, D)) if want_pe else None,
+               dgamma=np.empty(D), s_gamma=np.empty(B), big_sq=np.empty(1))
+    rc = _load().lnpegn_oracle_rms_bwd_pegn(_p(x), _p(dy), _p(gamma), B, T, D, float(eps), _p(out["dx"]),
+                                            _p(out["pe_gamma"]), _p(out["dgamma"]), _p(out["s_gamma"]),
+                                            _p(out["big_sq"]), int(nthreads))
+    if rc:
+        raise ValueError(f"oracle rms_bwd_pegn rc={rc}")
     return out
 
 

@@ -198,6 +198,94 @@ int lnpegn_oracle_ln_bwd_pegn(const double *x, const double *dy, const double *g
     return bad ? -3 : 0;
 }
 
+/*
+ * RMSNorm variant (Appendix B: "practically identical", the gradient is with respect to the
+ * affine parameter):  rstd = 1/sqrt(mean_d x^2 + eps),  xhat = x*rstd,  y = gamma*xhat.
+ */
+static double rms_rstd(const double *x, long D, double eps)
+{
+    double ss = 0.0;
+    for (long d = 0; d < D; ++d) ss += x[d] * x[d];
+    return 1.0 / sqrt(ss / (double)D + eps);
+}
+
+int lnpegn_oracle_rms_fwd(const double *x, const double *gamma, long N, long D, double eps, double *y,
+                          double *rstd)
+{
+    if (!x || !gamma || !y || N <= 0 || D <= 0 || eps < 0.0) return -1;
+    for (long r = 0; r < N; ++r) {
+        const double rs = rms_rstd(x + r * D, D, eps);
+        if (rstd) rstd[r] = rs;
+        for (long d = 0; d < D; ++d) y[r * D + d] = gamma[d] * (x[r * D + d] * rs);
+    }
+    return 0;
+}
+
+/* Backward of ONE example: g_gamma[k] = sum_t dy*xhat (step 1 of the LayerNorm algorithm with the
+ * RMS-normalised activation), dx[t,:] = rstd*(dyh - xhat*mean_d(dyh*xhat)). */
+int lnpegn_oracle_rms_bwd_example(const double *x, const double *dy, const double *gamma, long T,
+                                  long D, double eps, double *dx, double *g_gamma)
+{
+    if (!x || !dy || !gamma || !g_gamma || T <= 0 || D <= 0 || eps < 0.0) return -1;
+    for (long k = 0; k < D; ++k) g_gamma[k] = 0.0;
+    for (long t = 0; t < T; ++t) {
+        const double *xr = x + t * D;
+        const double *gr = dy + t * D;
+        const double rs = rms_rstd(xr, D, eps);
+        double sum_dyh_xhat = 0.0;
+        for (long k = 0; k < D; ++k) {
+            const double xhat = xr[k] * rs;
+            sum_dyh_xhat += gr[k] * gamma[k] * xhat;
+            g_gamma[k] += gr[k] * xhat;
+        }
+        if (dx) {
+            const double c1 = sum_dyh_xhat / (double)D;
+            for (long k = 0; k < D; ++k) {
+                const double xhat = xr[k] * rs;
+                dx[t * D + k] = rs * (gr[k] * gamma[k] - xhat * c1);
+            }
+        }
+    }
+    return 0;
+}
+
+/* Whole batch by brute force, as lnpegn_oracle_ln_bwd_pegn; big_sq is one value, ||dgamma||^2. */
+int lnpegn_oracle_rms_bwd_pegn(const double *x, const double *dy, const double *gamma, long B, long T,
+                               long D, double eps, double *dx, double *pe_gamma, double *dgamma,
+                               double *s_gamma, double *big_sq, int nthreads)
+{
+    if (!x || !dy || !gamma || !dgamma || !s_gamma || !big_sq) return -1;
+    if (B <= 0 || T <= 0 || D <= 0 || eps < 0.0) return -1;
+    double *gg = pe_gamma ? pe_gamma : (double *)malloc(sizeof(double) * (size_t)B * (size_t)D);
+    if (!gg) return -2;
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#else
+    (void)nthreads;
+#endif
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(| : bad)
+    for (long b = 0; b < B; ++b) {
+        const size_t off = (size_t)b * (size_t)T * (size_t)D;
+        if (lnpegn_oracle_rms_bwd_example(x + off, dy + off, gamma, T, D, eps, dx ? dx + off : NULL,
+                                          gg + b * D))
+            bad |= 1;
+        double sg = 0.0;
+        for (long k = 0; k < D; ++k) sg += gg[b * D + k] * gg[b * D + k];
+        s_gamma[b] = sg;
+    }
+    double ng = 0.0;
+    for (long k = 0; k < D; ++k) {
+        double a = 0.0;
+        for (long b = 0; b < B; ++b) a += gg[b * D + k];
+        dgamma[k] = a;
+        ng += a * a;
+    }
+    big_sq[0] = ng;
+    if (!pe_gamma) free(gg);
+    return bad ? -3 : 0;
+}
+
 /* Number of OpenMP threads a parallel region would use (1 without OpenMP). */
 int lnpegn_oracle_max_threads(void)
 {

@@ -384,3 +384,72 @@ def test_threads_do_not_change_results():
     b = oracle.ln_bwd_pegn(x, dy, gamma, 1e-5, nthreads=4)
     for k in a:
         np.testing.assert_array_equal(a[k], b[k])
+
+
+# ---------------------------------------------------------------- RMSNorm variant
+def test_rms_hand_worked_example_exact():
+    with open(os.path.join(GOLDEN, "rms_pegn_hand_example.json")) as f:
+        g = json.load(f)
+    x, dy, gamma = np.array(g["x"], float), np.array(g["dy"], float), np.array(g["gamma"], float)
+    e = g["expected"]
+    y, rstd = oracle.rms_fwd(x, gamma, g["eps"])
+    np.testing.assert_allclose(rstd, e["rstd"], rtol=1e-15)
+    np.testing.assert_allclose(y, np.array(e["y"], float), rtol=1e-14, atol=1e-14)
+    o = oracle.rms_bwd_pegn(x, dy, gamma, g["eps"])
+    for key in ("dx", "pe_gamma", "s_gamma", "dgamma", "big_sq"):
+        np.testing.assert_allclose(o[key], np.array(e[key], float), rtol=1e-14, atol=1e-14, err_msg=key)
+    est = oracle.gns_estimate(o["s_gamma"], o["big_sq"], e["gns_pe_scale"])
+    for key in ("g_small_sq", "g_big_sq", "G2", "S", "B_simple"):
+        assert est[key] == pytest.approx(e[key], rel=1e-13), key
+
+
+def _torch_rms_grads(x, dy, gamma, eps):
+    import torch
+    import torch.nn.functional as F
+    xt = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    gt = torch.tensor(gamma, dtype=torch.float64, requires_grad=True)
+    y = F.rms_norm(xt, (x.shape[-1],), gt, eps)
+    (y * torch.tensor(dy)).sum().backward()
+    return y.detach().numpy(), xt.grad.numpy(), gt.grad.numpy()
+
+
+@pytest.mark.parametrize("shape", [(3, 6, 40), (4, 1, 8), (1, 5, 1)])
+def test_rms_library_autograd_each_example_and_whole_batch(shape):
+    B, T, D = shape
+    eps = 1e-6
+    x, dy, gamma, _ = _rand_case(61 + D, B, T, D, offset=0.7)
+    o = oracle.rms_bwd_pegn(x, dy, gamma, eps)
+    y, dx, dg = _torch_rms_grads(x, dy, gamma, eps)
+    np.testing.assert_allclose(oracle.rms_fwd(x, gamma, eps)[0], y, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(o["dx"], dx, rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(o["dgamma"], dg, rtol=1e-10, atol=1e-12)
+    assert o["big_sq"][0] == pytest.approx(np.sum(dg ** 2), rel=1e-10)
+    for b in range(B):
+        _, dxb, dgb = _torch_rms_grads(x[b], dy[b], gamma, eps)
+        np.testing.assert_allclose(o["pe_gamma"][b], dgb, rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(o["dx"][b], dxb, rtol=1e-9, atol=1e-11)
+        assert o["s_gamma"][b] == pytest.approx(np.sum(dgb ** 2), rel=1e-10)
+
+
+def test_rms_finite_differences_and_invariants():
+    B, T, D, eps, h = 2, 3, 6, 1e-6, 1e-6
+    x, dy, gamma, _ = _rand_case(67, B, T, D, offset=0.3)
+    o = oracle.rms_bwd_pegn(x, dy, gamma, eps)
+    loss = lambda xx, gg: float(np.sum(dy * oracle.rms_fwd(xx, gg, eps)[0]))
+    fd = np.zeros_like(x)
+    for idx in np.ndindex(*x.shape):
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        fd[idx] = (loss(xp, gamma) - loss(xm, gamma)) / (2 * h)
+    np.testing.assert_allclose(o["dx"], fd, rtol=1e-6, atol=1e-8)
+    # sum_d dx*xhat = D*c1*eps*rstd^3: the row gradient is orthogonal to xhat when eps = 0
+    o0 = oracle.rms_bwd_pegn(x, dy, gamma, 0.0)
+    xhat = x / np.sqrt(np.mean(x * x, -1, keepdims=True))
+    assert np.max(np.abs((o0["dx"] * xhat).sum(-1))) < 1e-12 * np.abs(o0["dx"]).sum(-1).max()
+    # a centred input makes RMSNorm and LayerNorm agree (mean = 0), gamma gradients included
+    xc = x - x.mean(-1, keepdims=True)
+    ln = oracle.ln_bwd_pegn(xc, dy, gamma, eps)
+    rm = oracle.rms_bwd_pegn(xc, dy, gamma, eps)
+    np.testing.assert_allclose(rm["dgamma"], ln["dgamma"], rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(rm["s_gamma"], ln["s_gamma"], rtol=1e-10)
