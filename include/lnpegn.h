@@ -153,6 +153,22 @@ int ln_bwd_ex(const void *x, const void *dy, const void *gamma, const float *mea
               size_t workspace_bytes, unsigned flags, void *stream);
 
 /*
+ * RMSNorm variant (Appendix B: the per-example algorithm is "practically identical", the gradient
+ * being with respect to the affine parameter):  rstd = 1/sqrt(mean_d x^2 + eps),  xhat = x*rstd,
+ * y = gamma*xhat; there is no beta.
+ *   rms_fwd     y [B,T,D] in dt; rstd [N] fp32 or NULL
+ *   rms_bwd_ex  dx = rstd*(dyh - xhat*mean_d(dyh*xhat));  dgamma [D] = sum dy*xhat;
+ *               pe_gamma_sq [B] and big_sq [1] = ||dgamma||^2 with LNPEGN_PER_EXAMPLE;
+ *               rstd [N] from rms_fwd, or NULL to recompute it from x with eps;
+ *               flags, workspace (lnpegn_workspace_bytes) and deferral exactly as for ln_bwd_ex.
+ */
+int rms_fwd(const void *x, const void *gamma, void *y, float *rstd, int B, int T, int D, lnpegn_dtype dt,
+            lnpegn_dtype gamma_dt, float eps, void *stream);
+int rms_bwd_ex(const void *x, const void *dy, const void *gamma, const float *rstd, void *dx, float *dgamma,
+               float *pe_gamma_sq, float *big_sq, int B, int T, int D, lnpegn_dtype dt, lnpegn_dtype gamma_dt,
+               float eps, void *workspace, size_t workspace_bytes, unsigned flags, void *stream);
+
+/*
  * Gradient-noise-scale estimate from per-example norms: Section 2.1, Eq. 4 (unbiased |G|^2),
  * Eq. 5 (S ~ tr Sigma) and Eq. 3 (B_simple = S / |G|^2) with B_small = 1 and B_big = B, after
  * steps 4 and 8 of the Appendix B algorithm (mean over examples, times pe_scale^2).

@@ -19,7 +19,7 @@ STATUS = {0: "LNPEGN_OK", 1: "LNPEGN_EINVAL", 2: "LNPEGN_EUNSUPPORTED", 3: "LNPE
 EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "ln_fwd_stats", "ln_bwd",
            "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning", "lnpegn_set_profile_events",
            "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred",
-           "ln_fwd", "ln_bwd_ex")
+           "ln_fwd", "ln_bwd_ex", "rms_fwd", "rms_bwd_ex")
 PER_EXAMPLE, DEFER, ACCUMULATE = 1, 2, 4
 
 _lib = None
@@ -56,13 +56,16 @@ def load() -> ctypes.CDLL:
     lib.ln_fwd.argtypes = [vp, vp, vp, vp, fp, fp, i, i, i, i, i, f, vp]
     lib.ln_bwd_ex.argtypes = [vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, i, i, i, i, i, f, vp, sz,
                               ctypes.c_uint, vp]
+    lib.rms_fwd.argtypes = [vp, vp, vp, fp, i, i, i, i, i, f, vp]
+    lib.rms_bwd_ex.argtypes = [vp, vp, vp, fp, vp, fp, fp, fp, i, i, i, i, i, f, vp, sz, ctypes.c_uint, vp]
     lib.gns_estimate.argtypes = [fp, fp, i, i, f, fp, vp]
     lib.lnpegn_set_tuning.argtypes = [i, i]
     lib.lnpegn_set_profile_events.argtypes = [vp, vp]
     lib.lnpegn_stream_probe.argtypes = [vp, vp, vp, sz, i, vp]
     for name in ("ln_fwd_stats", "ln_bwd", "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning",
                  "lnpegn_set_profile_events", "lnpegn_stream_probe", "ln_bwd_deferred",
-                 "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred", "ln_fwd", "ln_bwd_ex"):
+                 "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred", "ln_fwd", "ln_bwd_ex",
+                 "rms_fwd", "rms_bwd_ex"):
         getattr(lib, name).restype = i
     _lib = lib
     return lib
@@ -171,6 +174,41 @@ def ln_bwd_ex(x, dy, gamma, eps: float, flags: int, dgamma, dbeta, mean=None, rs
     if rc:
         raise LnpegnError("ln_bwd_ex", rc)
     return dx
+
+
+def rms_fwd(x, gamma, eps: float, y=None, rstd=None, want_rstd=True, stream=None):
+    """RMSNorm forward -> (y, rstd[B,T] or None)."""
+    torch = _torch()
+    B, T, D = _check3(x)
+    y = torch.empty_like(x) if y is None else y
+    if want_rstd and rstd is None:
+        rstd = torch.empty((B, T), dtype=torch.float32, device=x.device)
+    rc = load().rms_fwd(_ptr(x), _ptr(gamma), _ptr(y), _ptr(rstd), B, T, D, _dt(x), _dt(gamma), eps,
+                        _stream(stream))
+    if rc:
+        raise LnpegnError("rms_fwd", rc)
+    return y, rstd
+
+
+def rms_bwd_ex(x, dy, gamma, eps: float, flags: int, dgamma=None, rstd=None, dx=None, pe_gamma_sq=None,
+               big_sq=None, workspace=None, stream=None):
+    """RMSNorm backward (flags as ln_bwd_ex) -> (dx, dgamma, pe_gamma_sq[B] or None, big_sq[1] or None)."""
+    torch = _torch()
+    B, T, D = _check3(x)
+    _check3(dy)
+    f32 = dict(dtype=torch.float32, device=x.device)
+    dx = torch.empty_like(x) if dx is None else dx
+    dgamma = torch.zeros(D, **f32) if dgamma is None else dgamma
+    if flags & PER_EXAMPLE:
+        pe_gamma_sq = torch.empty(B, **f32) if pe_gamma_sq is None else pe_gamma_sq
+        big_sq = torch.empty(1, **f32) if big_sq is None else big_sq
+    workspace = alloc_workspace(B, T, D, _dt(x), x.device) if workspace is None else workspace
+    rc = load().rms_bwd_ex(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(rstd), _ptr(dx), _ptr(dgamma),
+                           _ptr(pe_gamma_sq), _ptr(big_sq), B, T, D, _dt(x), _dt(gamma), eps,
+                           _ptr(workspace), workspace.numel(), flags, _stream(stream))
+    if rc:
+        raise LnpegnError("rms_bwd_ex", rc)
+    return dx, dgamma, pe_gamma_sq, big_sq
 
 
 def ln_bwd(x, dy, gamma, eps: float, mean=None, rstd=None, dx=None, dgamma=None, dbeta=None,

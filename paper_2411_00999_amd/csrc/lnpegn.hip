@@ -207,16 +207,16 @@ hipError_t launch_rows(const Plan &p, const RowArgs &a, const RowLaunch &rl)
     return hipErrorInvalidValue;
 }
 
-int run_bwd(bool pegn, bool defer, bool accumulate, const void *x, const void *dy, const void *gamma, const float *mean,
+int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, const void *dy, const void *gamma, const float *mean,
             const float *rstd, void *dx, float *dgamma, float *dbeta, float *pe_gamma_sq,
             float *pe_beta_sq, float *big_sq, int B, int T, int D, int dt, int gamma_dt, float eps,
             void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
     if (!dtype_ok(dt) || !dtype_ok(gamma_dt)) return LNPEGN_EUNSUPPORTED;
-    if (!x || !dy || !gamma || !dx || !dgamma || !dbeta) return LNPEGN_EINVAL;
-    if (pegn && (!pe_gamma_sq || !pe_beta_sq)) return LNPEGN_EINVAL;
-    if ((mean == nullptr) != (rstd == nullptr)) return LNPEGN_EINVAL;
+    if (!x || !dy || !gamma || !dx || !dgamma || (!rms && !dbeta)) return LNPEGN_EINVAL;
+    if (pegn && (!pe_gamma_sq || (!rms && !pe_beta_sq))) return LNPEGN_EINVAL;
+    if (!rms && (mean == nullptr) != (rstd == nullptr)) return LNPEGN_EINVAL;
     if (dx == x) return LNPEGN_EINVAL;
     if ((int64_t)B * T > INT32_MAX) return LNPEGN_EINVAL;   // row indices are 32-bit
     const bool vector_ok = aligned16(x) && aligned16(dy) && aligned16(dx) && aligned16(gamma);
@@ -236,7 +236,7 @@ int run_bwd(bool pegn, bool defer, bool accumulate, const void *x, const void *d
     // measured: grouping an example's chunks on one XCD helps wide rows (S >= 4) and is neutral otherwise
     const bool xcd = g_xcd >= 0 ? g_xcd != 0 : p.S >= 4;
     a.xcd_chunks = (xcd && p.fast && p.n_slots % 8 == 0) ? (int)(p.n_slots / 8) : 0;
-    a.S = p.S; a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.emit_pe = p.emit_pe;
+    a.S = p.S; a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.emit_pe = p.emit_pe; a.rms = rms;
     a.eps = eps; a.inv_D = 1.0f / (float)D;
     if (defer) {
         a.defer = reinterpret_cast<DeferHeader *>(ws);
@@ -245,7 +245,7 @@ int run_bwd(bool pegn, bool defer, bool accumulate, const void *x, const void *d
     }
 
     hipError_t e;
-    const bool saved = mean != nullptr;
+    const bool saved = rstd != nullptr;
     const RowLaunch rl{s, g_ev_start, g_ev_stop};
     g_ev_start = g_ev_stop = nullptr;
     if (dt == LNPEGN_BF16)
@@ -420,7 +420,7 @@ int ln_bwd(const void *x, const void *dy, const void *gamma, const float *mean, 
            void *dx, float *dgamma, float *dbeta, int B, int T, int D, lnpegn_dtype dt,
            lnpegn_dtype gamma_dt, float eps, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return run_bwd(false, false, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, nullptr, nullptr, nullptr, B, T,
+    return run_bwd(false, false, false, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, nullptr, nullptr, nullptr, B, T,
                    D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
 }
 
@@ -430,7 +430,7 @@ int ln_bwd_pegn(const void *x, const void *dy, const void *gamma, const float *m
                 lnpegn_dtype gamma_dt, float eps, void *workspace, size_t workspace_bytes,
                 void *stream)
 {
-    return run_bwd(true, false, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq,
+    return run_bwd(true, false, false, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq,
                    B, T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
 }
 
@@ -439,7 +439,7 @@ int ln_bwd_deferred(const void *x, const void *dy, const void *gamma, const floa
                     lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *workspace,
                     size_t workspace_bytes, void *stream)
 {
-    return run_bwd(false, true, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, nullptr, nullptr, nullptr, B,
+    return run_bwd(false, true, false, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, nullptr, nullptr, nullptr, B,
                    T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
 }
 
@@ -449,7 +449,7 @@ int ln_bwd_pegn_deferred(const void *x, const void *dy, const void *gamma, const
                          lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *workspace,
                          size_t workspace_bytes, void *stream)
 {
-    return run_bwd(true, true, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq,
+    return run_bwd(true, true, false, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq,
                    big_sq, B, T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
 }
 
@@ -460,8 +460,36 @@ int ln_bwd_ex(const void *x, const void *dy, const void *gamma, const float *mea
 {
     if (flags & ~(unsigned)(LNPEGN_PER_EXAMPLE | LNPEGN_DEFER | LNPEGN_ACCUMULATE)) return LNPEGN_EINVAL;
     const bool pegn = (flags & LNPEGN_PER_EXAMPLE) != 0;
-    return run_bwd(pegn, (flags & LNPEGN_DEFER) != 0, (flags & LNPEGN_ACCUMULATE) != 0, x, dy, gamma, mean,
+    return run_bwd(pegn, (flags & LNPEGN_DEFER) != 0, (flags & LNPEGN_ACCUMULATE) != 0, false, x, dy, gamma, mean,
                    rstd, dx, dgamma, dbeta, pegn ? pe_gamma_sq : nullptr, pegn ? pe_beta_sq : nullptr,
+                   pegn ? big_sq : nullptr, B, T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
+}
+
+int rms_fwd(const void *x, const void *gamma, void *y, float *rstd, int B, int T, int D, lnpegn_dtype dt,
+            lnpegn_dtype gamma_dt, float eps, void *stream)
+{
+    if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
+    if (!dtype_ok(dt) || !dtype_ok(gamma_dt)) return LNPEGN_EUNSUPPORTED;
+    if (!x || !gamma || !y) return LNPEGN_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    FwdArgs a{};
+    a.x = x; a.gamma = gamma; a.beta = nullptr; a.y = y; a.mean = nullptr; a.rstd = rstd;
+    a.N = (int64_t)B * T; a.D = D; a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.rms = 1; a.eps = eps;
+    a.inv_D = 1.0f / (float)D;
+    const bool vec = aligned16(x) && aligned16(y) && aligned16(gamma);
+    const hipError_t e = dt == LNPEGN_BF16 ? launch_fwd<bf16_t, true>(a, vec, s)
+                                           : launch_fwd<float, true>(a, vec, s);
+    return e == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+}
+
+int rms_bwd_ex(const void *x, const void *dy, const void *gamma, const float *rstd, void *dx, float *dgamma,
+               float *pe_gamma_sq, float *big_sq, int B, int T, int D, lnpegn_dtype dt, lnpegn_dtype gamma_dt,
+               float eps, void *workspace, size_t workspace_bytes, unsigned flags, void *stream)
+{
+    if (flags & ~(unsigned)(LNPEGN_PER_EXAMPLE | LNPEGN_DEFER | LNPEGN_ACCUMULATE)) return LNPEGN_EINVAL;
+    const bool pegn = (flags & LNPEGN_PER_EXAMPLE) != 0;
+    return run_bwd(pegn, (flags & LNPEGN_DEFER) != 0, (flags & LNPEGN_ACCUMULATE) != 0, true, x, dy, gamma,
+                   nullptr, rstd, dx, dgamma, nullptr, pegn ? pe_gamma_sq : nullptr, nullptr,
                    pegn ? big_sq : nullptr, B, T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
 }
 

@@ -100,13 +100,13 @@ __device__ __forceinline__ void reduce_groups_body(const ReduceArgs &a, int g, i
     const bool single = a.G1 == 1;
     if (single && a.accumulate && col < a.D) {
         v0 += (double)a.dgamma[col];
-        v1 += (double)a.dbeta[col];
+        if (a.dbeta) v1 += (double)a.dbeta[col];
     }
     const float f0 = (float)v0, f1 = (float)v1;
     if (col < a.D) {
         if (single) {
             a.dgamma[col] = f0;
-            a.dbeta[col] = f1;
+            if (a.dbeta) a.dbeta[col] = f1;
         } else {
             a.grp[((int64_t)g * 2) * a.D + col] = f0;
             a.grp[((int64_t)g * 2 + 1) * a.D + col] = f1;
@@ -169,7 +169,7 @@ __device__ __forceinline__ void finish_scalars(const ReduceArgs &a, int tid, int
                 sb += a.part_s[((int64_t)b * a.ntile + t) * 2 + 1];
             }
             a.pe_gamma_sq[b] = (float)sg;
-            a.pe_beta_sq[b] = (float)sb;
+            if (a.pe_beta_sq) a.pe_beta_sq[b] = (float)sb;
         }
     }
 }
@@ -188,11 +188,11 @@ __device__ __forceinline__ void reduce_final_body(const ReduceArgs &a)
             sum_groups(a.grp, a.G1, a.D, col, s0, s1);
             if (a.accumulate) {
                 s0 += (double)a.dgamma[col];
-                s1 += (double)a.dbeta[col];
+                if (a.dbeta) s1 += (double)a.dbeta[col];
             }
             const float f0 = (float)s0, f1 = (float)s1;
             a.dgamma[col] = f0;
-            a.dbeta[col] = f1;
+            if (a.dbeta) a.dbeta[col] = f1;
             q0 += (double)f0 * f0;
             q1 += (double)f1 * f1;
         }
@@ -209,7 +209,7 @@ __device__ __forceinline__ void reduce_final_body(const ReduceArgs &a)
             else q1 = t2;
         }
         if (tid == 0) a.big_sq[0] = (float)q0;
-        if (tid == (a.G1 > 1 ? 0 : 1)) a.big_sq[1] = (float)q1;
+        if (tid == (a.G1 > 1 ? 0 : 1) && a.dbeta) a.big_sq[1] = (float)q1;   // one norm without beta
     }
 }
 
@@ -273,10 +273,10 @@ __global__ __launch_bounds__(kTile) void reduce_final_tiles_kernel(ReduceArgs a)
         sum_groups(a.grp, a.G1, a.D, col, s0, s1);
         if (a.accumulate) {
             s0 += (double)a.dgamma[col];
-            s1 += (double)a.dbeta[col];
+            if (a.dbeta) s1 += (double)a.dbeta[col];
         }
         a.dgamma[col] = (float)s0;
-        a.dbeta[col] = (float)s1;
+        if (a.dbeta) a.dbeta[col] = (float)s1;
     }
     const double d0 = (double)(float)s0, d1 = (double)(float)s1;
     const double q0 = block_sum_f64(d0 * d0, slots[0]);
@@ -292,7 +292,7 @@ __global__ __launch_bounds__(256) void reduce_scalars_kernel(ReduceArgs a)
 {
     const int tid = threadIdx.x;
     finish_scalars(a, tid, 256);
-    if (a.big_sq && tid < 2) {
+    if (a.big_sq && tid < (a.dbeta ? 2 : 1)) {
         double t2 = 0.0;
         for (int t = 0; t < a.ntile; ++t) t2 += a.part_big[t * 2 + tid];
         a.big_sq[tid] = (float)t2;

@@ -41,6 +41,7 @@ struct RowArgs {
     int S;               // waves per row
     int gamma_is_f32;
     int emit_pe;         // C == 1: a chunk is a whole example, its squared norms are final here
+    int rms;             // RMSNorm variant: no mean is subtracted, no beta (uniform run-time flag)
     int xcd_chunks;      // > 0: chunks per XCD; workgroup i (dispatched to XCD i % 8) takes chunk
                          //      (i % 8) * xcd_chunks + i / 8, so neighbouring chunks share an L2
     float eps;
@@ -152,7 +153,7 @@ void ln_bwd_rows_kernel(RowArgs a)
     auto load_row = [&](int m, Raw (&xr)[kVpt], Raw (&dr)[kVpt]) {
         const int rr = row_of(m);
         if constexpr (kSaved) {
-            st_mean = a.mean[rr];
+            st_mean = a.rms ? 0.f : a.mean[rr];
             st_rstd = a.rstd[rr];
         }
         const int64_t off = (int64_t)rr * a.nvec;
@@ -238,12 +239,14 @@ void ln_bwd_rows_kernel(RowArgs a)
                 pivot = saved_mean;
                 rstd_saved = saved_rstd;
             } else {
+                if (!a.rms) {   // RMSNorm: the pivot is zero, M2 is the plain sum of squares
 #pragma unroll
-                for (int k = 0; k < kVpt; ++k)
+                    for (int k = 0; k < kVpt; ++k)
 #pragma unroll
-                    for (int e = 0; e < E; ++e) s_x += xf[k][e];
-                s_x = wave_sum(s_x);
-                pivot = s_x * (kSync ? inv_nw : a.inv_D);
+                        for (int e = 0; e < E; ++e) s_x += xf[k][e];
+                    s_x = wave_sum(s_x);
+                    pivot = s_x * (kSync ? inv_nw : a.inv_D);
+                }
             }
             // pass 2: centre about the pivot; M2, sum dyh, sum dyh*xc
 #pragma unroll
@@ -313,7 +316,8 @@ void ln_bwd_rows_kernel(RowArgs a)
                 else rstd = rsqrtf(m2 * a.inv_D + a.eps);
             }
             // pass 3: dx = rstd*(dyh - c2 - xhat*c1), c1 = rstd*mean_d(dyh*(x-mean)), c2 = mean_d(dyh)
-            const float k1 = -rstd * rstd * s_dyx * a.inv_D, k2 = -rstd * s_dyh * a.inv_D;
+            const float k1 = -rstd * rstd * s_dyx * a.inv_D;
+            const float k2 = a.rms ? 0.f : -rstd * s_dyh * a.inv_D;   // RMSNorm has no mean(dyh) term
             Raw *orow = dxv + (int64_t)r * a.nvec;
 #pragma unroll
             for (int k = 0; k < kVpt; ++k) {
@@ -405,7 +409,7 @@ void ln_bwd_rows_kernel(RowArgs a)
         const double tb = block_sum_f64(sq_b, slots + 16);
         if (threadIdx.x == 0) {
             a.pe_gamma_sq[b] = (float)tg;
-            a.pe_beta_sq[b] = (float)tb;
+            if (a.pe_beta_sq) a.pe_beta_sq[b] = (float)tb;
         }
     }
 }
@@ -439,11 +443,12 @@ __global__ void ln_bwd_rows_generic_kernel(RowArgs a)
             s_dyh += load_elem<T>(a.dy, base + k) * load_gamma(a.gamma, a.gamma_is_f32, k);
         s_dyh = block_sum(s_dyh, slots);
         if constexpr (kSaved) {
-            mean = a.mean[r];
+            mean = a.rms ? 0.f : a.mean[r];
             rstd = a.rstd[r];
         } else {
             float s_x = 0.f;
-            for (int k = tid; k < a.D; k += nt) s_x += load_elem<T>(a.x, base + k);
+            if (!a.rms)
+                for (int k = tid; k < a.D; k += nt) s_x += load_elem<T>(a.x, base + k);
             mean = block_sum(s_x, slots) * a.inv_D;
             float ss = 0.f;
             for (int k = tid; k < a.D; k += nt) {
@@ -458,7 +463,7 @@ __global__ void ln_bwd_rows_generic_kernel(RowArgs a)
             s_dx += load_elem<T>(a.dy, base + k) * load_gamma(a.gamma, a.gamma_is_f32, k) * xhat;
         }
         s_dx = block_sum(s_dx, slots);
-        const float c1 = s_dx * a.inv_D, c2 = s_dyh * a.inv_D;
+        const float c1 = s_dx * a.inv_D, c2 = a.rms ? 0.f : s_dyh * a.inv_D;
         for (int k = tid; k < a.D; k += nt) {
             const float xhat = (load_elem<T>(a.x, base + k) - mean) * rstd;
             const float dyv = load_elem<T>(a.dy, base + k);
@@ -486,6 +491,7 @@ struct FwdArgs {
     int D;
     int nvec;
     int gamma_is_f32;
+    int rms;            // RMSNorm: mean taken as zero, beta absent
     float eps;
     float inv_D;
 };
@@ -512,7 +518,12 @@ __global__ void ln_fwd_kernel(FwdArgs a)
 #pragma unroll
         for (int k = 0; k < kVpt; ++k) {
             load_gamma_vec<T>(a.gamma, a.gamma_is_f32, ok[k] ? vidx[k] : 0, gm[k]);
-            load_gamma_vec<T>(a.beta, a.gamma_is_f32, ok[k] ? vidx[k] : 0, bt[k]);
+            if (a.beta) {
+                load_gamma_vec<T>(a.beta, a.gamma_is_f32, ok[k] ? vidx[k] : 0, bt[k]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < E; ++e) bt[k][e] = 0.f;
+            }
         }
     }
     const Raw *xv = static_cast<const Raw *>(a.x);
@@ -537,7 +548,7 @@ __global__ void ln_fwd_kernel(FwdArgs a)
             s = 0.f;
             for (int w = 0; w < nwaves; ++w) s += slots[0][w];
         }
-        const float mean = s * a.inv_D;
+        const float mean = a.rms ? 0.f : s * a.inv_D;
         float ss = 0.f;
 #pragma unroll
         for (int k = 0; k < kVpt; ++k)
@@ -581,7 +592,7 @@ __global__ void ln_fwd_generic_kernel(FwdArgs a)
         const int64_t base = r * (int64_t)a.D;
         float s = 0.f;
         for (int k = tid; k < a.D; k += nt) s += load_elem<T>(a.x, base + k);
-        const float mean = block_sum(s, slots) * a.inv_D;
+        const float mean = a.rms ? 0.f : block_sum(s, slots) * a.inv_D;
         float ss = 0.f;
         for (int k = tid; k < a.D; k += nt) {
             const float c = load_elem<T>(a.x, base + k) - mean;
@@ -598,7 +609,7 @@ __global__ void ln_fwd_generic_kernel(FwdArgs a)
                 const float xhat = (load_elem<T>(a.x, base + k) - mean) * rstd;
                 store_elem<T>(a.y, base + k,
                               xhat * load_gamma(a.gamma, a.gamma_is_f32, k) +
-                                  load_gamma(a.beta, a.gamma_is_f32, k));
+                                  (a.beta ? load_gamma(a.beta, a.gamma_is_f32, k) : 0.f));
             }
         }
     }

@@ -303,6 +303,47 @@ def test_gradient_accumulation_over_micro_batches(cfg, B, T, D, defer):
     _check_gns(out.cpu().numpy().astype(np.float64), want, A * B)
 
 
+# ------------------------------------------------------------------ RMSNorm variant
+@pytest.mark.parametrize("cfg,B,T,D", [(1, 4, 128, 256), (2, 3, 37, 768), (3, 3, 70, 2048), (4, 300, 3, 1024),
+                                      (5, 2, 17, 8192), (3, 2, 9, 3072), (1, 2, 7, 257), (2, 2, 5, 1001)])
+@pytest.mark.parametrize("saved", [False, True])
+def test_rmsnorm_against_oracle(cfg, B, T, D, saved):
+    import torch
+    from paper_2411_00999_amd import binding
+    inp = workloads.make_inputs(cfg, B=B, T=T, D=D)
+    inp.x += np.float32(0.5)                       # RMSNorm does not centre: give the rows a mean
+    if inp.dtype == "bf16":
+        inp.x = workloads.round_to_bf16(inp.x)
+    eps = 1e-6
+    ref = oracle.rms_bwd_pegn(inp.x, inp.dy, inp.gamma, eps, want_pe=False)
+    x, dy, gamma = (pu.to_device(a, inp.dtype) for a in (inp.x, inp.dy, inp.gamma))
+    y, rstd = binding.rms_fwd(x, gamma, eps)
+    dx, dg, sg, big = binding.rms_bwd_ex(x, dy, gamma, eps, binding.PER_EXAMPLE, rstd=rstd if saved else None)
+    torch.cuda.synchronize()
+    bf = inp.dtype == "bf16"
+    tol = pu.TOL_BF16 if bf else pu.TOL_F32
+    y_ref, rstd_ref = oracle.rms_fwd(inp.x, inp.gamma, eps)
+    pu.check_close("y", pu.to_host64(y), y_ref, tol, bf16_output=bf)
+    np.testing.assert_allclose(pu.to_host64(rstd), rstd_ref, rtol=pu.TOL_F32)
+    x64, dy64 = inp.x.reshape(-1, D).astype(np.float64), inp.dy.reshape(-1, D).astype(np.float64)
+    term = float(np.sqrt(np.mean((rstd_ref.reshape(-1, 1) * dy64 * inp.gamma.astype(np.float64)) ** 2)))
+    pu.check_close("dx", pu.to_host64(dx), ref["dx"], tol, bf16_output=bf, floor_rms=term)
+    pu.check_close("dgamma", pu.to_host64(dg), ref["dgamma"], pu.TOL_SUMS)
+    np.testing.assert_allclose(pu.to_host64(sg), ref["s_gamma"], rtol=pu.TOL_SUMS)
+    np.testing.assert_allclose(pu.to_host64(big), ref["big_sq"], rtol=pu.TOL_SUMS)
+    # plain call (no per-example outputs) gives the same dx and dgamma
+    dx2, dg2, none_s, none_b = binding.rms_bwd_ex(x, dy, gamma, eps, 0)
+    torch.cuda.synchronize()
+    assert none_s is None and none_b is None
+    pu.check_close("dgamma(plain)", pu.to_host64(dg2), ref["dgamma"], pu.TOL_SUMS)
+    if not saved:
+        assert torch.equal(dx, dx2)
+    if B > 1:
+        out = binding.gns_estimate(sg, big, float(B))
+        torch.cuda.synchronize()
+        _check_gns(out.cpu().numpy().astype(np.float64), oracle.gns_estimate(ref["s_gamma"], ref["big_sq"], float(B)), B)
+
+
 # ------------------------------------------------------------------ estimator alone
 @pytest.mark.parametrize("n_groups,B", [(1, 2), (2, 8), (96, 16), (3, 513)])
 def test_gns_estimate_same_norms_both_sides(n_groups, B):
