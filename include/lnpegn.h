@@ -188,6 +188,35 @@ int gns_estimate(const float *pe_sq, const float *big_sq, int n_groups, int B, f
                  float *out, void *stream);
 
 /*
+ * Online smoothing (Section 4.2: both estimators are smoothed with an exponential moving average
+ * before the ratio is taken).  A "record" is the five floats gns_estimate writes; records [n][5]
+ * (device) holds this step's record for each of n tracked groups (layers, layer types, the total).
+ *   state     [n][3] fp64 (device), rows {m_G2, m_S, w}; owned by the caller, updated in place;
+ *             all-zero bytes = a fresh tracker.  m <- alpha*m + (1-alpha)*v from zero, and w is the
+ *             same recurrence on the constant 1 (= 1 - alpha^t), the weight the average has seen.
+ *   smoothed  [n][3] fp32 (device) or NULL: {m_G2/w, m_S/w, m_S/m_G2}; raw IEEE results, no clamping.
+ *   alpha in [0,1), else EINVAL.  The paper gives neither the recurrence nor alpha.
+ */
+int gns_ema_update(double *state, const float *records, int n, double alpha, float *smoothed, void *stream);
+
+/*
+ * Offline aggregation (Appendix A, last paragraph; Figure 2 caption): over a history records [n][5]
+ * (device) of one group, the plain means of G2 and S, the ratio of the means, and the delete-one
+ * jackknife of that ratio.  out [5] fp32 (device) = {mean_G2, mean_S, B_simple = mean_S/mean_G2,
+ * stderr, bias-corrected B_simple = n*R - (n-1)*mean_i R_(i)}, where R_(i) is the ratio with step i
+ * left out and stderr^2 = (n-1)/n * sum_i (R_(i) - mean R_(.))^2.  n >= 2, else EINVAL.
+ */
+int gns_offline(const float *records, int64_t n, float *out, void *stream);
+
+/*
+ * Linear batch-size schedule of Section 5.1, realised through accumulation steps: host arithmetic,
+ * exact in integers.  Returns ceil(accum_final * tokens_seen / ramp_tokens) kept within
+ * [1, accum_final] (accum_final once tokens_seen >= ramp_tokens or ramp_tokens == 0), or
+ * -LNPEGN_EINVAL for negative arguments or accum_final < 1.
+ */
+int gns_linear_accum_steps(int64_t tokens_seen, int64_t ramp_tokens, int accum_final);
+
+/*
  * Benchmarking aid.  Overrides launch-shape heuristics process-wide; it never changes results
  * beyond floating-point summation order.  key 0: target number of row chunks of ln_bwd_pegn
  * (0 = automatic); key 1: the same for ln_bwd; key 2: waves per workgroup of the row kernel

@@ -19,7 +19,8 @@ STATUS = {0: "LNPEGN_OK", 1: "LNPEGN_EINVAL", 2: "LNPEGN_EUNSUPPORTED", 3: "LNPE
 EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "ln_fwd_stats", "ln_bwd",
            "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning", "lnpegn_set_profile_events",
            "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred",
-           "ln_fwd", "ln_bwd_ex", "rms_fwd", "rms_bwd_ex")
+           "ln_fwd", "ln_bwd_ex", "rms_fwd", "rms_bwd_ex",
+           "gns_ema_update", "gns_offline", "gns_linear_accum_steps")
 PER_EXAMPLE, DEFER, ACCUMULATE = 1, 2, 4
 
 _lib = None
@@ -56,6 +57,9 @@ def load() -> ctypes.CDLL:
     lib.ln_fwd.argtypes = [vp, vp, vp, vp, fp, fp, i, i, i, i, i, f, vp]
     lib.ln_bwd_ex.argtypes = [vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, i, i, i, i, i, f, vp, sz,
                               ctypes.c_uint, vp]
+    lib.gns_ema_update.argtypes = [vp, fp, i, ctypes.c_double, fp, vp]
+    lib.gns_offline.argtypes = [fp, ctypes.c_int64, fp, vp]
+    lib.gns_linear_accum_steps.argtypes = [ctypes.c_int64, ctypes.c_int64, i]
     lib.rms_fwd.argtypes = [vp, vp, vp, fp, i, i, i, i, i, f, vp]
     lib.rms_bwd_ex.argtypes = [vp, vp, vp, fp, vp, fp, fp, fp, i, i, i, i, i, f, vp, sz, ctypes.c_uint, vp]
     lib.gns_estimate.argtypes = [fp, fp, i, i, f, fp, vp]
@@ -65,7 +69,7 @@ def load() -> ctypes.CDLL:
     for name in ("ln_fwd_stats", "ln_bwd", "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning",
                  "lnpegn_set_profile_events", "lnpegn_stream_probe", "ln_bwd_deferred",
                  "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred", "ln_fwd", "ln_bwd_ex",
-                 "rms_fwd", "rms_bwd_ex"):
+                 "rms_fwd", "rms_bwd_ex", "gns_ema_update", "gns_offline", "gns_linear_accum_steps"):
         getattr(lib, name).restype = i
     _lib = lib
     return lib
@@ -108,6 +112,41 @@ def workspace_bytes(B: int, T: int, D: int, dtype: int) -> int:
 def alloc_workspace(B: int, T: int, D: int, dtype: int, device="cuda"):
     torch = _torch()
     return torch.empty(workspace_bytes(B, T, D, dtype), dtype=torch.uint8, device=device)
+
+
+def gns_ema_update(state, records, alpha: float, smoothed=None, stream=None):
+    """state [n,3] fp64 (updated in place), records [n,5] fp32 -> smoothed [n,3] fp32."""
+    torch = _torch()
+    n = state.shape[0]
+    if state.dtype != torch.float64 or tuple(state.shape) != (n, 3) or not state.is_contiguous():
+        raise ValueError("state must be a contiguous [n,3] float64 tensor")
+    if records.dtype != torch.float32 or tuple(records.shape) != (n, 5) or not records.is_contiguous():
+        raise ValueError("records must be a contiguous [n,5] float32 tensor")
+    smoothed = torch.empty((n, 3), dtype=torch.float32, device=state.device) if smoothed is None else smoothed
+    rc = load().gns_ema_update(_ptr(state), _ptr(records), n,
+                               float(alpha), _ptr(smoothed), _stream(stream))
+    if rc:
+        raise LnpegnError("gns_ema_update", rc)
+    return smoothed
+
+
+def gns_offline(records, out=None, stream=None):
+    """records [n,5] fp32 history of one group -> out[5] = mean_G2, mean_S, B_simple, stderr, B_simple_jack."""
+    torch = _torch()
+    if records.dtype != torch.float32 or records.dim() != 2 or records.shape[1] != 5 or not records.is_contiguous():
+        raise ValueError("records must be a contiguous [n,5] float32 tensor")
+    out = torch.empty(5, dtype=torch.float32, device=records.device) if out is None else out
+    rc = load().gns_offline(_ptr(records), records.shape[0], _ptr(out), _stream(stream))
+    if rc:
+        raise LnpegnError("gns_offline", rc)
+    return out
+
+
+def gns_linear_accum_steps(tokens_seen: int, ramp_tokens: int, accum_final: int) -> int:
+    rc = load().gns_linear_accum_steps(tokens_seen, ramp_tokens, accum_final)
+    if rc < 0:
+        raise LnpegnError("gns_linear_accum_steps", -rc)
+    return rc
 
 
 def set_tuning(key: int, value: int) -> None:

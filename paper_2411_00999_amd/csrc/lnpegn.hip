@@ -7,6 +7,7 @@
 
 #include "../../include/lnpegn.h"
 #include "lnpegn_finalize.h"
+#include "lnpegn_tracker.h"
 #include "lnpegn_rows.h"
 
 namespace lnpegn {
@@ -525,6 +526,30 @@ int gns_estimate(const float *pe_sq, const float *big_sq, int n_groups, int B, f
     gns_estimate_kernel<<<dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
         pe_sq, big_sq, n_groups, B, pe_scale, out);
     return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+}
+
+int gns_ema_update(double *state, const float *records, int n, double alpha, float *smoothed, void *stream)
+{
+    if (!state || !records || n <= 0 || !(alpha >= 0.0 && alpha < 1.0)) return LNPEGN_EINVAL;
+    gns_ema_update_kernel<<<dim3((n + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+        state, records, n, alpha, smoothed);
+    return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+}
+
+int gns_offline(const float *records, int64_t n, float *out, void *stream)
+{
+    if (!records || !out || n < 2) return LNPEGN_EINVAL;
+    gns_offline_kernel<<<dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(records, n, out);
+    return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+}
+
+int gns_linear_accum_steps(int64_t tokens_seen, int64_t ramp_tokens, int accum_final)
+{
+    if (tokens_seen < 0 || ramp_tokens < 0 || accum_final < 1) return -LNPEGN_EINVAL;
+    if (ramp_tokens == 0 || tokens_seen >= ramp_tokens) return accum_final;
+    const __int128 num = (__int128)accum_final * tokens_seen;
+    const int64_t a = (int64_t)((num + ramp_tokens - 1) / ramp_tokens);
+    return a < 1 ? 1 : (a > accum_final ? accum_final : (int)a);
 }
 
 int lnpegn_set_tuning(int key, int value)

@@ -144,3 +144,21 @@ def test_workloads_are_seeded_and_representable():
     assert int((col_rms > 10).sum()) == 8              # 1% of the channels carry the x20 outliers
     r = workloads.round_to_bf16(np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0078125], np.float32))
     assert np.array_equal(r, np.array([1.0, 1.015625, 1.0078125], np.float32))  # ties to even
+
+
+def test_linear_accum_steps_host_function_matches_oracle():
+    """Host-only integer arithmetic: callable without a GPU."""
+    import numpy as np
+    from oracle import gns_tracker_oracle as trk
+    from paper_2411_00999_amd import binding
+    rng = np.random.default_rng(3)
+    cases = [(0, 800, 8), (1, 800, 8), (101, 800, 8), (799, 800, 8), (800, 800, 8), (5, 0, 7), (0, 0, 1),
+             (2 ** 62, 2 ** 63 - 1, 2 ** 31 - 1)]
+    cases += [(int(t), int(r), int(a)) for t, r, a in zip(rng.integers(0, 2 ** 62, 300),
+                                                          rng.integers(1, 2 ** 62, 300), rng.integers(1, 2 ** 20, 300))]
+    for t, r, a in cases:
+        assert binding.gns_linear_accum_steps(t, r, a) == trk.linear_accum_steps(t, r, a), (t, r, a)
+    import pytest
+    for bad in [(-1, 10, 2), (1, -10, 2), (1, 10, 0)]:
+        with pytest.raises(binding.LnpegnError):
+            binding.gns_linear_accum_steps(*bad)

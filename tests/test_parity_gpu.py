@@ -442,3 +442,95 @@ def test_full_size_workloads(cfg):
         ubar = u.mean(0)
         closed = ((n / 2.0) * np.sum((a - ubar) ** 2) + np.sum((u - ubar) ** 2)) / (2 * n - 1)
         assert got[3] == pytest.approx(closed, rel=pu.TOL_GNS)
+
+
+# ------------------------------------------------------------------ GNS tracker: EMA, offline jackknife, schedule
+def _records(g2, s):
+    """[n,5] fp32 records with G2 and S in the places gns_estimate writes them."""
+    rec = np.zeros((len(g2), 5), dtype=np.float32)
+    rec[:, 2], rec[:, 3] = g2, s
+    rec[:, 4] = rec[:, 3] / rec[:, 2]
+    return rec
+
+
+@pytest.mark.parametrize("n,alpha", [(1, 0.9), (3, 0.0), (300, 0.95), (1000, 0.999)])
+def test_ema_tracker_against_oracle(n, alpha):
+    import torch
+    from oracle import gns_tracker_oracle as trk
+    from paper_2411_00999_amd import binding
+    rng = np.random.default_rng(workloads.BASE_SEED + n)
+    state = torch.zeros((n, 3), dtype=torch.float64, device="cuda")
+    ref = trk.ema_init(n)
+    for step in range(25):
+        rec = _records(rng.normal(2.0, 1.0, n), rng.normal(50.0, 20.0, n))
+        smoothed = binding.gns_ema_update(state, torch.from_numpy(rec).cuda(), alpha)
+        torch.cuda.synchronize()
+        ref = trk.ema_update(ref, rec[:, 2].astype(np.float64), rec[:, 3].astype(np.float64), alpha)
+        np.testing.assert_allclose(state.cpu().numpy(), ref, rtol=1e-13, atol=0)
+        np.testing.assert_allclose(smoothed.cpu().numpy().astype(np.float64), trk.ema_read(ref), rtol=pu.TOL_F32)
+
+
+def test_ema_tracker_follows_gns_estimate_records():
+    """End to end on the device: per-example norms -> gns_estimate record -> smoothed estimate."""
+    import torch
+    from oracle import gns_tracker_oracle as trk
+    from paper_2411_00999_amd import binding
+    state = torch.zeros((1, 3), dtype=torch.float64, device="cuda")
+    ref = trk.ema_init(1)
+    for layer in range(4):
+        inp = workloads.make_inputs(1, layer=layer, B=4, T=16, D=64, signal=True)
+        gpu = pu.run_gpu(inp, pegn=True)
+        dev = gpu["_dev"]
+        rec = binding.gns_estimate(torch.stack([dev["sg"], dev["sb"]]), dev["big"], 4.0)
+        smoothed = binding.gns_ema_update(state, rec.reshape(1, 5), 0.9)
+        torch.cuda.synchronize()
+        r = oracle.ln_bwd_pegn(inp.x, inp.dy, inp.gamma, workloads.EPS, want_dx=False, want_pe=False)
+        est = oracle.gns_estimate(np.stack([r["s_gamma"], r["s_beta"]]), r["big_sq"], 4.0)
+        ref = trk.ema_update(ref, [est["G2"]], [est["S"]], 0.9)
+        np.testing.assert_allclose(smoothed.cpu().numpy().astype(np.float64), trk.ema_read(ref), rtol=1e-4)
+
+
+@pytest.mark.parametrize("n", [2, 3, 17, 257, 2000])
+def test_offline_jackknife_against_brute_force_oracle(n):
+    import torch
+    from oracle import gns_tracker_oracle as trk
+    from paper_2411_00999_amd import binding
+    rng = np.random.default_rng(workloads.BASE_SEED + 7 * n)
+    rec = _records(rng.normal(3.0, 0.5, n), rng.normal(6.0, 2.0, n))
+    out = binding.gns_offline(torch.from_numpy(rec).cuda())
+    torch.cuda.synchronize()
+    ref = trk.offline_gns(rec[:, 2].astype(np.float64), rec[:, 3].astype(np.float64))
+    got = out.cpu().numpy().astype(np.float64)
+    want = [ref[k] for k in ("mean_G2", "mean_S", "B_simple", "stderr", "B_simple_jack")]
+    np.testing.assert_allclose(got, want, rtol=pu.TOL_F32)
+
+
+def test_offline_jackknife_long_history_and_hand_example():
+    import json
+    import os
+    import torch
+    from oracle import gns_tracker_oracle as trk
+    from paper_2411_00999_amd import binding
+    rng = np.random.default_rng(workloads.BASE_SEED + 99)
+    n = 300_001
+    rec = _records(rng.normal(3.0, 0.5, n), rng.normal(6.0, 2.0, n))
+    out = binding.gns_offline(torch.from_numpy(rec).cuda()).cpu().numpy().astype(np.float64)
+    ref = trk.offline_gns_sums(rec[:, 2].astype(np.float64), rec[:, 3].astype(np.float64))
+    np.testing.assert_allclose(out, [ref[k] for k in ("mean_G2", "mean_S", "B_simple", "stderr", "B_simple_jack")],
+                               rtol=pu.TOL_F32)
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "gns_tracker_hand_example.json")))["jackknife"]
+    out = binding.gns_offline(torch.from_numpy(_records(g["G2"], g["S"])).cuda()).cpu().numpy()
+    np.testing.assert_allclose(out, [2.0, 4.0, 2.0, np.sqrt(37.0) / 9.0, 19.0 / 9.0], rtol=1e-6)
+
+
+def test_tracker_argument_errors():
+    import torch
+    from paper_2411_00999_amd import binding
+    rec = torch.zeros((1, 5), dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.LnpegnError):
+        binding.gns_offline(rec)                                   # n < 2
+    st = torch.zeros((1, 3), dtype=torch.float64, device="cuda")
+    for alpha in (1.0, -0.1, float("nan")):
+        with pytest.raises(binding.LnpegnError):
+            binding.gns_ema_update(st, rec, alpha)
+    assert torch.count_nonzero(st).item() == 0
