@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per row-kernel launch counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the
 # stream probe of known size); see profiles/ln_bwd_rows_workload3_rocprofv3.md.  Re-measure after any
 # change to the row kernel or its launch shape.  Workloads without a measurement report null.
-MEASURED_TRAFFIC_BYTES = {3: 411_300_000}
+MEASURED_TRAFFIC_BYTES = {3: 411_200_000}
 
 
 # ----------------------------------------------------------------------------- HIP events
