@@ -1,0 +1,38 @@
+"""TEST INFRASTRUCTURE -- NOT PART OF THE PRODUCT PATH.
+
+Slow fp64 definition of the linear-layer simultaneous per-example gradient-norm computation
+(Section 3, Algorithm 1): for activations x [B,T,K] entering a linear layer and gradients g [B,T,L]
+of the loss with respect to its outputs,
+
+    step 1   w_b[k,l] = sum_t x[b,t,k] * g[b,t,l]        (every middle dimension is flattened into t)
+    step 2   s_w[b]   = sum_{k,l} w_b[k,l]^2
+    step 3   w'[k,l]  = sum_b w_b[k,l]
+
+Step 4 (mean over b, times B^2) is the estimator's business (gns_estimate with pe_scale = B), as
+for the LayerNorm path: s_w is returned raw.  The per-example tensor is materialised here on
+purpose -- that is the definition; one matrix product per example is the only library step.
+Nothing here is imported by the HIP package.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def linear_pegn(x, g, want_pe: bool = False) -> dict:
+    """x [B,T,K], g [B,T,L] -> dict(w [K,L], s [B], pe [B,K,L] or None), all float64."""
+    x = np.asarray(x, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    if x.ndim != 3 or g.ndim != 3 or x.shape[:2] != g.shape[:2]:
+        raise ValueError("x must be [B,T,K] and g [B,T,L] with the same B and T")
+    B, T, K = x.shape
+    L = g.shape[2]
+    w = np.zeros((K, L))
+    s = np.zeros(B)
+    pe = np.zeros((B, K, L)) if want_pe else None
+    for b in range(B):
+        w_b = x[b].T @ g[b]                 # step 1 for this example
+        s[b] = np.sum(w_b * w_b)            # step 2
+        w += w_b                            # step 3
+        if want_pe:
+            pe[b] = w_b
+    return dict(w=w, s=s, pe=pe)
