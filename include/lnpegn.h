@@ -217,6 +217,23 @@ int gns_offline(const float *records, int64_t n, float *out, void *stream);
 int gns_linear_accum_steps(int64_t tokens_seen, int64_t ramp_tokens, int accum_final);
 
 /*
+ * Linear-layer simultaneous per-example gradient norms (Section 3, Algorithm 1, steps 1-3).
+ *   x [B,T,K] activations entering the layer, g [B,T,L] gradients w.r.t. its outputs (device,
+ *   row-major contiguous, dt = bf16 or fp32; every middle dimension flattened into T).
+ *   w [K,L] fp32 (device): sum_b w_b, w_b[k,l] = sum_t x[b,t,k] g[b,t,l]; overwritten, or added to
+ *     with LNPEGN_ACCUMULATE (the only flag accepted).
+ *   s [B] fp32: raw ||w_b||^2 (step 4's mean and B^2 are gns_estimate's pe_scale, as for LayerNorm).
+ *   big_sq [1] fp32 or NULL: ||w||^2 of the (accumulated) weight gradient.
+ * The per-example tensor [B,K,L] is never written to memory.  bf16 with K % 8 == 0, L % 8 == 0 and
+ * 16-byte aligned x, g runs on the matrix cores (fp32 accumulation); anything else takes a slow
+ * scalar kernel.  workspace: linear_pegn_workspace_bytes(...) bytes, 256-byte aligned, caller-owned,
+ * contents scratch.  K*L <= 2^31.  Enqueued on stream, never synchronises; status codes as above.
+ */
+size_t linear_pegn_workspace_bytes(int B, int T, int K, int L, lnpegn_dtype dt);
+int linear_pegn(const void *x, const void *g, float *w, float *s, float *big_sq, int B, int T, int K, int L,
+                lnpegn_dtype dt, void *workspace, size_t workspace_bytes, unsigned flags, void *stream);
+
+/*
  * Benchmarking aid.  Overrides launch-shape heuristics process-wide; it never changes results
  * beyond floating-point summation order.  key 0: target number of row chunks of ln_bwd_pegn
  * (0 = automatic); key 1: the same for ln_bwd; key 2: waves per workgroup of the row kernel

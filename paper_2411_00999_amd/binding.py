@@ -20,7 +20,8 @@ EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "ln_fwd_stats", "ln
            "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning", "lnpegn_set_profile_events",
            "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred",
            "ln_fwd", "ln_bwd_ex", "rms_fwd", "rms_bwd_ex",
-           "gns_ema_update", "gns_offline", "gns_linear_accum_steps")
+           "gns_ema_update", "gns_offline", "gns_linear_accum_steps",
+           "linear_pegn_workspace_bytes", "linear_pegn")
 PER_EXAMPLE, DEFER, ACCUMULATE = 1, 2, 4
 
 _lib = None
@@ -60,6 +61,9 @@ def load() -> ctypes.CDLL:
     lib.gns_ema_update.argtypes = [vp, fp, i, ctypes.c_double, fp, vp]
     lib.gns_offline.argtypes = [fp, ctypes.c_int64, fp, vp]
     lib.gns_linear_accum_steps.argtypes = [ctypes.c_int64, ctypes.c_int64, i]
+    lib.linear_pegn_workspace_bytes.argtypes = [i, i, i, i, i]
+    lib.linear_pegn_workspace_bytes.restype = sz
+    lib.linear_pegn.argtypes = [vp, vp, fp, fp, fp, i, i, i, i, i, vp, sz, ctypes.c_uint, vp]
     lib.rms_fwd.argtypes = [vp, vp, vp, fp, i, i, i, i, i, f, vp]
     lib.rms_bwd_ex.argtypes = [vp, vp, vp, fp, vp, fp, fp, fp, i, i, i, i, i, f, vp, sz, ctypes.c_uint, vp]
     lib.gns_estimate.argtypes = [fp, fp, i, i, f, fp, vp]
@@ -69,7 +73,8 @@ def load() -> ctypes.CDLL:
     for name in ("ln_fwd_stats", "ln_bwd", "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning",
                  "lnpegn_set_profile_events", "lnpegn_stream_probe", "ln_bwd_deferred",
                  "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred", "ln_fwd", "ln_bwd_ex",
-                 "rms_fwd", "rms_bwd_ex", "gns_ema_update", "gns_offline", "gns_linear_accum_steps"):
+                 "rms_fwd", "rms_bwd_ex", "gns_ema_update", "gns_offline", "gns_linear_accum_steps",
+                 "linear_pegn"):
         getattr(lib, name).restype = i
     _lib = lib
     return lib
@@ -147,6 +152,32 @@ def gns_linear_accum_steps(tokens_seen: int, ramp_tokens: int, accum_final: int)
     if rc < 0:
         raise LnpegnError("gns_linear_accum_steps", -rc)
     return rc
+
+
+def linear_pegn(x, g, w=None, accumulate=False, s=None, big_sq=None, workspace=None, stream=None):
+    """x [B,T,K], g [B,T,L] -> (w [K,L] fp32, s [B] fp32, big_sq [1] fp32)."""
+    torch = _torch()
+    B, T, K = _check3(x)
+    B2, T2, L = _check3(g)
+    if (B2, T2) != (B, T) or g.dtype != x.dtype:
+        raise ValueError("x and g must agree in B, T and dtype")
+    f32 = dict(dtype=torch.float32, device=x.device)
+    if w is None:
+        if accumulate:
+            raise ValueError("accumulate needs the buffer to add to")
+        w = torch.empty((K, L), **f32)
+    if w.dtype != torch.float32 or tuple(w.shape) != (K, L) or not w.is_contiguous():
+        raise ValueError("w must be a contiguous [K,L] float32 tensor")
+    s = torch.empty(B, **f32) if s is None else s
+    big_sq = torch.empty(1, **f32) if big_sq is None else big_sq
+    if workspace is None:
+        nbytes = load().linear_pegn_workspace_bytes(B, T, K, L, _dt(x))
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=x.device)
+    rc = load().linear_pegn(_ptr(x), _ptr(g), _ptr(w), _ptr(s), _ptr(big_sq), B, T, K, L, _dt(x),
+                            _ptr(workspace), workspace.numel(), ACCUMULATE if accumulate else 0, _stream(stream))
+    if rc:
+        raise LnpegnError("linear_pegn", rc)
+    return w, s, big_sq
 
 
 def set_tuning(key: int, value: int) -> None:

@@ -1,0 +1,371 @@
+// Linear-layer simultaneous per-example gradient norms (Section 3, Algorithm 1) for gfx950:
+//   w_b[k,l] = sum_t x[b,t,k] g[b,t,l]   (step 1; never leaves the chip)
+//   s[b]     = sum_{k,l} w_b[k,l]^2      (step 2)
+//   w'[k,l]  = sum_b w_b[k,l]            (step 3)
+// One MFMA contraction per example with two accumulator sets per wave: the example's own tile, squared
+// and folded into the running total at every example boundary.  The paper materialises [B,K,L] and
+// pays its I/O (Section 3.1, Appendix E); here the only extra HBM traffic is B floats per tile.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/lnpegn.h"
+#include "lnpegn_device.h"
+
+namespace lnpegn {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+// Workgroup tile: 256 (k) x 128 (l) outputs, 64 positions t per LDS stage, 8 waves as 4 (k) x 2 (l),
+// each wave 64 x 64 = 2 x 2 MFMA tiles of 32 x 32.  Operands sit in LDS transposed, [column][t], so an
+// MFMA operand (8 consecutive t of one column) is one 16-byte read; rows are padded to 144 bytes,
+// which spreads 16 consecutive columns over all 64 banks.
+constexpr int kTileK = 256, kTileL = 128, kStageT = 64, kThreads = 512, kWaves = 8;
+constexpr int kPitch = 144;                                   // bytes per LDS row (64 t x 2 B + 16)
+constexpr int kStageBytes = (kTileK + kTileL) * kPitch;       // 55,296
+constexpr int kMaxSplit = 64;
+
+struct LinArgs {
+    const uint16_t *x;      // [B,T,K] bf16
+    const uint16_t *g;      // [B,T,L] bf16
+    float *out;             // nsplit == 1: w [K,L]; else partial totals [nsplit][K][L]
+    float *tile_s;          // [ntiles*kWaves][B] per-wave parts of s[b]
+    double *tile_big;       // [ntiles*kWaves] per-wave parts of ||w'||^2 (nsplit == 1 only)
+    int B, T, K, L;
+    int tiles_k, tiles_l, nsplit, b_per_split;
+    int accumulate;         // nsplit == 1: add the total to what out holds
+};
+
+__device__ __forceinline__ int xcd_spread(int bid, int n)
+{
+    // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous run of logical
+    // tiles (k fastest), so that workgroups sharing an operand share an L2.
+    const int q = n >> 3, r = n & 7, xcd = bid & 7, loc = bid >> 3;
+    return xcd * q + (xcd < r ? xcd : r) + loc;
+}
+
+__global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
+{
+    __shared__ __align__(16) unsigned char lds[2][kStageBytes];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int ntiles = a.tiles_k * a.tiles_l;
+    const int tile = xcd_spread(blockIdx.x, ntiles);
+    const int split = blockIdx.y;
+    const int k0 = (tile % a.tiles_k) * kTileK, l0 = (tile / a.tiles_k) * kTileL;
+    const int b_begin = split * a.b_per_split;
+    const int b_end = b_begin + a.b_per_split < a.B ? b_begin + a.b_per_split : a.B;
+    const int nst = (a.T + kStageT - 1) / kStageT;
+    const int nstages = (b_end - b_begin) * nst;
+
+    // ---- loader role: waves 0-3 bring 64 columns of x each, waves 4-5 bring 64 columns of g each.
+    // A lane owns an 8 (t) x 8 (column) block: eight 16-byte row loads, transposed in registers.
+    const bool loads = wave < 6;
+    const bool from_x = wave < 4;
+    const int sub = from_x ? wave : wave - 4;
+    const int tb = lane & 7, cg = lane >> 3;
+    const int ncols = from_x ? a.K : a.L;
+    const int col = (from_x ? k0 : l0) + sub * 64 + cg * 8;
+    const bool col_ok = loads && col < ncols;                 // K, L are multiples of 8: all or nothing
+    const uint16_t *src = from_x ? a.x : a.g;
+    const int lds_row = (from_x ? 0 : kTileK) + sub * 64 + cg * 8;
+    u32x4_t raw[8];
+
+    auto fetch = [&](int st) {
+        // branch-free: a load that would fall outside reads the tensor's first vector instead and is
+        // replaced by zeros afterwards
+        const int b = b_begin + st / nst;
+        const int t0 = (st % nst) * kStageT + tb * 8;
+        const int64_t first = ((int64_t)b * a.T + t0) * ncols + col;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const bool ok = col_ok && t0 + j < a.T;
+            const u32x4_t v = *reinterpret_cast<const u32x4_t *>(src + (ok ? first + (int64_t)j * ncols : 0));
+            raw[j] = ok ? v : u32x4_t{0u, 0u, 0u, 0u};
+        }
+    };
+    auto stash = [&](int buf) {
+        if (!loads) return;
+        unsigned char *base = lds[buf] + lds_row * kPitch + tb * 16;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {                          // column i of the block
+            u32x4_t o;
+#pragma unroll
+            for (int tp = 0; tp < 4; ++tp) {                   // positions 2tp, 2tp+1
+                const uint32_t u = raw[2 * tp][i >> 1], v = raw[2 * tp + 1][i >> 1];
+                o[tp] = (i & 1) ? ((u >> 16) | (v & 0xffff0000u)) : ((u & 0xffffu) | (v << 16));
+            }
+            *reinterpret_cast<u32x4_t *>(base + i * kPitch) = o;
+        }
+    };
+
+    // ---- compute role: wave (wm, wn) owns outputs k0 + wm*64 .. +64, l0 + wn*64 .. +64
+    const int wm = wave & 3, wn = wave >> 2;
+    const int frag_off = (lane & 31) * kPitch + (lane >> 5) * 16;
+    const int a_off = (wm * 64) * kPitch + frag_off;
+    const int b_off = (kTileK + wn * 64) * kPitch + frag_off;
+    f32x16_t acc[2][2], tot[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                acc[mi][ni][i] = 0.f;
+                tot[mi][ni][i] = 0.f;
+            }
+
+    if (nstages > 0) {
+        fetch(0);
+        stash(0);
+    }
+    __syncthreads();
+    for (int st = 0; st < nstages; ++st) {
+        const int buf = st & 1;
+        if (st + 1 < nstages) fetch(st + 1);
+        const unsigned char *sa = lds[buf] + a_off, *sb = lds[buf] + b_off;
+#pragma unroll
+        for (int kk = 0; kk < kStageT / 16; ++kk) {
+            bf16x8_t fa[2], fb[2];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+                fa[mi] = *reinterpret_cast<const bf16x8_t *>(sa + mi * 32 * kPitch + kk * 32);
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                fb[ni] = *reinterpret_cast<const bf16x8_t *>(sb + ni * 32 * kPitch + kk * 32);
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+        }
+        if (st % nst == nst - 1) {
+            // example boundary: step 2 on this wave's 64 x 64 part, then fold it into the total (step 3)
+            float ssq = 0.f;
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float v = acc[mi][ni][i];
+                        ssq = fmaf(v, v, ssq);
+                        tot[mi][ni][i] += v;
+                        acc[mi][ni][i] = 0.f;
+                    }
+            ssq = wave_sum(ssq);
+            if (lane == 0) a.tile_s[(int64_t)(tile * kWaves + wave) * a.B + b_begin + st / nst] = ssq;
+        }
+        if (st + 1 < nstages) stash(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- write the total: lane holds rows (i/4)*8 + (lane/32)*4 + i%4, column lane%32 of each 32x32 tile
+    float *out = a.out + (a.nsplit > 1 ? (int64_t)split * a.K * a.L : 0);
+    double bsq = 0.0;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const int l = l0 + wn * 64 + ni * 32 + (lane & 31);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int k = k0 + wm * 64 + mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+                if (k < a.K && l < a.L) {
+                    float *p = out + (int64_t)k * a.L + l;
+                    float v = tot[mi][ni][i];
+                    if (a.accumulate && a.nsplit == 1) v += *p;
+                    *p = v;
+                    bsq += (double)v * (double)v;
+                }
+            }
+        }
+    if (a.nsplit == 1) {
+        bsq = wave_sum_f64(bsq);
+        if (lane == 0) a.tile_big[tile * kWaves + wave] = bsq;
+    }
+}
+
+// Any shape, any alignment, fp32 or bf16: one thread per output (k,l), fp32 FMA over t, no MFMA.
+// Correct, not fast; covers what the MFMA kernel does not take.
+template <typename T>
+__global__ __launch_bounds__(256) void linear_pegn_generic_kernel(const T *x, const T *g, float *w, float *blk_s,
+                                                                  double *blk_big, int B, int Tn, int K, int L,
+                                                                  int accumulate)
+{
+    __shared__ float slots[4];
+    __shared__ double dslots[4];
+    const int l = blockIdx.x * 16 + (threadIdx.x & 15), k = blockIdx.y * 16 + (threadIdx.x >> 4);
+    const bool ok = k < K && l < L;
+    const int blk = blockIdx.y * gridDim.x + blockIdx.x;
+    float total = 0.f;
+    for (int b = 0; b < B; ++b) {
+        float acc = 0.f;
+        if (ok) {
+            const T *px = x + (int64_t)b * Tn * K + k, *pg = g + (int64_t)b * Tn * L + l;
+            for (int t = 0; t < Tn; ++t)
+                acc = fmaf(load_elem<T>(px, (int64_t)t * K), load_elem<T>(pg, (int64_t)t * L), acc);
+        }
+        total += acc;
+        const float ssq = block_sum(acc * acc, slots);
+        if (threadIdx.x == 0) blk_s[(int64_t)blk * B + b] = ssq;
+    }
+    double bsq = 0.0;
+    if (ok) {
+        float *p = w + (int64_t)k * L + l;
+        if (accumulate) total += *p;
+        *p = total;
+        bsq = (double)total * (double)total;
+    }
+    bsq = block_sum_f64(bsq, dslots);
+    if (threadIdx.x == 0) blk_big[blk] = bsq;
+}
+
+// w = (accumulate ? w : 0) + sum over splits, in split order; per-block parts of ||w||^2.
+__global__ __launch_bounds__(256) void linear_sum_splits_kernel(const float *part, float *w, double *blk_big,
+                                                                int64_t n, int nsplit, int accumulate)
+{
+    __shared__ double dslots[4];
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    double bsq = 0.0;
+    if (i < n) {
+        float v = accumulate ? w[i] : 0.f;
+        for (int s = 0; s < nsplit; ++s) v += part[(int64_t)s * n + i];
+        w[i] = v;
+        bsq = (double)v * (double)v;
+    }
+    bsq = block_sum_f64(bsq, dslots);
+    if (threadIdx.x == 0) blk_big[blockIdx.x] = bsq;
+}
+
+// s[b] = sum of its parts (fp64, part order); big_sq = sum of the parts of ||w'||^2.  One workgroup.
+__global__ __launch_bounds__(256) void linear_final_kernel(const float *part_s, int nparts, const double *part_big,
+                                                           int64_t nbig, float *s, float *big_sq, int B)
+{
+    __shared__ double dslots[4];
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        double t = 0.0;
+        for (int p = 0; p < nparts; ++p) t += (double)part_s[(int64_t)p * B + b];
+        s[b] = (float)t;
+    }
+    if (big_sq) {
+        double t = 0.0;
+        for (int64_t i = threadIdx.x; i < nbig; i += blockDim.x) t += part_big[i];
+        t = block_sum_f64(t, dslots);
+        if (threadIdx.x == 0) big_sq[0] = (float)t;
+    }
+}
+
+struct LinPlan {
+    bool mfma;
+    int tiles_k, tiles_l, nsplit, b_per_split;
+    int nparts;            // rows of the s parts
+    int64_t nbig;          // entries of the ||w'||^2 parts
+    size_t off_s, off_big, off_part, bytes;
+};
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+LinPlan make_lin_plan(int B, int T, int K, int L, int dt, bool aligned)
+{
+    LinPlan p{};
+    p.mfma = dt == LNPEGN_BF16 && K % 8 == 0 && L % 8 == 0 && aligned;
+    if (p.mfma) {
+        p.tiles_k = (K + kTileK - 1) / kTileK;
+        p.tiles_l = (L + kTileL - 1) / kTileL;
+        const int ntiles = p.tiles_k * p.tiles_l;
+        // enough workgroups for 256 CUs: split the examples when the output has few tiles
+        int want = (256 + ntiles - 1) / ntiles;
+        if (want > B) want = B;
+        if (want > kMaxSplit) want = kMaxSplit;
+        p.b_per_split = (B + want - 1) / want;
+        p.nsplit = (B + p.b_per_split - 1) / p.b_per_split;
+        p.nparts = ntiles * kWaves;
+        p.nbig = p.nsplit == 1 ? (int64_t)ntiles * kWaves : ((int64_t)K * L + 255) / 256;
+    } else {
+        p.tiles_k = (K + 15) / 16;
+        p.tiles_l = (L + 15) / 16;
+        p.nsplit = 1;
+        p.b_per_split = B;
+        p.nparts = p.tiles_k * p.tiles_l;
+        p.nbig = p.nparts;
+    }
+    p.off_s = 0;
+    p.off_big = align256(p.off_s + (size_t)p.nparts * B * sizeof(float));
+    p.off_part = align256(p.off_big + (size_t)p.nbig * sizeof(double));
+    p.bytes = p.off_part + (p.nsplit > 1 ? (size_t)p.nsplit * K * L * sizeof(float) : 0);
+    return p;
+}
+
+bool lin_shape_ok(int B, int T, int K, int L)
+{
+    return B > 0 && T > 0 && K > 0 && L > 0 && (int64_t)K * L <= ((int64_t)1 << 31);
+}
+
+}  // namespace
+}  // namespace lnpegn
+
+using namespace lnpegn;
+
+extern "C" {
+
+size_t linear_pegn_workspace_bytes(int B, int T, int K, int L, lnpegn_dtype dt)
+{
+    if (!lin_shape_ok(B, T, K, L) || (dt != LNPEGN_F32 && dt != LNPEGN_BF16)) return 0;
+    // sized for either kernel, whatever the alignment of the pointers turns out to be
+    const size_t m = make_lin_plan(B, T, K, L, dt, true).bytes, g = make_lin_plan(B, T, K, L, dt, false).bytes;
+    return m > g ? m : g;
+}
+
+int linear_pegn(const void *x, const void *g, float *w, float *s, float *big_sq, int B, int T, int K, int L,
+                lnpegn_dtype dt, void *workspace, size_t workspace_bytes, unsigned flags, void *stream)
+{
+    if (!lin_shape_ok(B, T, K, L) || !x || !g || !w || !s || !workspace) return LNPEGN_EINVAL;
+    if (flags & ~(unsigned)LNPEGN_ACCUMULATE) return LNPEGN_EINVAL;
+    if (dt != LNPEGN_F32 && dt != LNPEGN_BF16) return LNPEGN_EUNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return LNPEGN_EINVAL;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(g)) & 15u) == 0;
+    const LinPlan p = make_lin_plan(B, T, K, L, dt, aligned);
+    if (workspace_bytes < p.bytes) return LNPEGN_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int accumulate = (flags & LNPEGN_ACCUMULATE) ? 1 : 0;
+    char *ws = static_cast<char *>(workspace);
+    float *part_s = reinterpret_cast<float *>(ws + p.off_s);
+    double *part_big = reinterpret_cast<double *>(ws + p.off_big);
+    float *part_w = reinterpret_cast<float *>(ws + p.off_part);
+    if (p.mfma) {
+        LinArgs a{};
+        a.x = static_cast<const uint16_t *>(x);
+        a.g = static_cast<const uint16_t *>(g);
+        a.out = p.nsplit > 1 ? part_w : w;
+        a.tile_s = part_s;
+        a.tile_big = part_big;
+        a.B = B; a.T = T; a.K = K; a.L = L;
+        a.tiles_k = p.tiles_k; a.tiles_l = p.tiles_l; a.nsplit = p.nsplit; a.b_per_split = p.b_per_split;
+        a.accumulate = accumulate;
+        linear_pegn_kernel<<<dim3(p.tiles_k * p.tiles_l, p.nsplit), dim3(kThreads), 0, st>>>(a);
+        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        if (p.nsplit > 1) {
+            const int64_t n = (int64_t)K * L;
+            linear_sum_splits_kernel<<<dim3((unsigned)p.nbig), dim3(256), 0, st>>>(part_w, w, part_big, n, p.nsplit,
+                                                                                  accumulate);
+            if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        }
+    } else {
+        const dim3 grid(p.tiles_l, p.tiles_k);
+        if (dt == LNPEGN_BF16)
+            linear_pegn_generic_kernel<bf16_t><<<grid, dim3(256), 0, st>>>(
+                static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(g), w, part_s, part_big, B, T, K, L,
+                accumulate);
+        else
+            linear_pegn_generic_kernel<float><<<grid, dim3(256), 0, st>>>(
+                static_cast<const float *>(x), static_cast<const float *>(g), w, part_s, part_big, B, T, K, L,
+                accumulate);
+        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    }
+    linear_final_kernel<<<dim3(1), dim3(256), 0, st>>>(part_s, p.nparts, part_big, p.nbig, s, big_sq, B);
+    return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+}
+
+}  // extern "C"

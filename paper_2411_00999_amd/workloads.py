@@ -160,3 +160,30 @@ def make_inputs(config: int, layer: int = 0, B: Optional[int] = None, T: Optiona
     elif dtype != "f32":
         raise ValueError(f"unknown dtype {dtype}")
     return LNInputs(config, layer, B, T, D, dtype, EPS, x, dy, gamma, beta)
+
+
+# ----------------------------------------------------------------------------- linear layers
+# Shapes of the linear layers next to the LayerNorm workloads: (B, T, K, L).  "gpt111m" are the four
+# projections of a block with hidden size 768 (Section 4), "gpt1p3b" the MLP up-projection of the
+# hidden-2048 model of Section 5.2; inputs are what such a layer sees: unit-variance activations
+# after a LayerNorm and small zero-mean output gradients.
+LINEAR_SHAPES = {
+    "gpt111m_qkv": (8, 1024, 768, 2304),
+    "gpt111m_proj": (8, 1024, 768, 768),
+    "gpt111m_up": (8, 1024, 768, 3072),
+    "gpt111m_down": (8, 1024, 3072, 768),
+    "gpt1p3b_up": (16, 2048, 2048, 8192),
+}
+
+
+def make_linear_inputs(seed: int, B: int, T: int, K: int, L: int, dtype: str = "bf16", signal: float = 0.0):
+    """(x [B,T,K], g [B,T,L]) float32 arrays (already rounded to bf16 values when dtype is "bf16").
+    ``signal`` > 0 adds to g a fixed [T,L] pattern shared by every example."""
+    rng = np.random.default_rng(BASE_SEED + 500_000 + seed)
+    x = _normal(rng, (B, T, K))
+    g = _normal(rng, (B, T, L), 1e-3)
+    if signal > 0.0:
+        g += _normal(rng, (1, T, L), signal)
+    if dtype == "bf16":
+        x, g = round_to_bf16(x), round_to_bf16(g)
+    return x, g

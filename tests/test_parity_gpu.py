@@ -534,3 +534,103 @@ def test_tracker_argument_errors():
         with pytest.raises(binding.LnpegnError):
             binding.gns_ema_update(st, rec, alpha)
     assert torch.count_nonzero(st).item() == 0
+
+
+# ------------------------------------------------------------------ linear-layer per-example norms (Algorithm 1)
+def _run_linear(x, g, dtype, w0=None):
+    import torch
+    from paper_2411_00999_amd import binding
+    xd, gd = pu.to_device(x, dtype), pu.to_device(g, dtype)
+    w = None if w0 is None else torch.from_numpy(w0.astype(np.float32)).cuda()
+    w, s, big = binding.linear_pegn(xd, gd, w=w, accumulate=w0 is not None)
+    torch.cuda.synchronize()
+    return pu.to_host64(w), pu.to_host64(s), pu.to_host64(big)
+
+
+def _check_linear(x, g, got, w0=None):
+    from oracle import linear_pegn_oracle as lin
+    ref = lin.linear_pegn(x, g)
+    w_ref = ref["w"] if w0 is None else ref["w"] + w0.astype(np.float32).astype(np.float64)
+    w, s, big = got
+    pu.check_close("w", w, w_ref, pu.TOL_SUMS)
+    np.testing.assert_allclose(s, ref["s"], rtol=pu.TOL_SUMS, err_msg="s")
+    np.testing.assert_allclose(big, [np.sum(w_ref ** 2)], rtol=pu.TOL_SUMS, err_msg="big_sq")
+
+
+@pytest.mark.parametrize("B,T,K,L", [
+    (2, 64, 256, 128),        # exactly one tile, one stage
+    (3, 70, 264, 136),        # ragged in T, K and L; examples split over workgroups
+    (1, 1, 8, 8),             # smallest the matrix-core kernel takes
+    (5, 200, 768, 768),       # hidden 768, several tiles
+    (16, 33, 520, 1032),
+    (2, 64, 4096, 2048),      # 256 tiles: no split over examples, totals written by the tile kernel
+    (3, 129, 4104, 2056),     # the same with ragged edges
+    (70, 16, 256, 128),       # more examples than the largest split
+])
+def test_linear_pegn_matrix_core_kernel(B, T, K, L):
+    x, g = workloads.make_linear_inputs(B * 1000 + T, B, T, K, L, "bf16")
+    _check_linear(x, g, _run_linear(x, g, "bf16"))
+
+
+@pytest.mark.parametrize("B,T,K,L", [(3, 70, 264, 136), (2, 64, 4096, 2048)])
+def test_linear_pegn_accumulates_into_the_weight_gradient(B, T, K, L):
+    x, g = workloads.make_linear_inputs(77, B, T, K, L, "bf16")
+    w0 = np.random.default_rng(workloads.BASE_SEED + 78).normal(0, 1e-2, (K, L))
+    _check_linear(x, g, _run_linear(x, g, "bf16", w0=w0), w0=w0)
+
+
+@pytest.mark.parametrize("dtype,B,T,K,L", [("f32", 3, 17, 50, 36), ("bf16", 2, 9, 100, 7), ("f32", 2, 64, 256, 128),
+                                           ("f32", 1, 1, 1, 1)])
+def test_linear_pegn_generic_kernel(dtype, B, T, K, L):
+    x, g = workloads.make_linear_inputs(B * 1000 + K, B, T, K, L, dtype)
+    _check_linear(x, g, _run_linear(x, g, dtype))
+    w0 = np.random.default_rng(workloads.BASE_SEED + 79).normal(0, 1e-2, (K, L))
+    _check_linear(x, g, _run_linear(x, g, dtype, w0=w0), w0=w0)
+
+
+def test_linear_pegn_special_cases_and_estimate():
+    import torch
+    from paper_2411_00999_amd import binding
+    B, T, K, L = 4, 96, 512, 256
+    x, g = workloads.make_linear_inputs(5, B, T, K, L, "bf16", signal=1e-3)
+    # identical examples: every s equal, w = B * w_0
+    xi, gi = np.repeat(x[:1], B, 0), np.repeat(g[:1], B, 0)
+    w, s, big = _run_linear(xi, gi, "bf16")
+    np.testing.assert_allclose(s, s[0], rtol=1e-6)
+    np.testing.assert_allclose(big[0], B * B * s[0], rtol=1e-5)
+    # T = 1: the product form of Section 2.2
+    x1, g1 = workloads.make_linear_inputs(6, 6, 1, 264, 136, "bf16")
+    _, s1, _ = _run_linear(x1, g1, "bf16")
+    np.testing.assert_allclose(s1, (x1[:, 0].astype(np.float64) ** 2).sum(1) * (g1[:, 0].astype(np.float64) ** 2).sum(1),
+                               rtol=1e-5)
+    # repeated calls are bitwise reproducible, and the norms feed the estimator (one group)
+    xd, gd = pu.to_device(x, "bf16"), pu.to_device(g, "bf16")
+    a = binding.linear_pegn(xd, gd)
+    b = binding.linear_pegn(xd, gd)
+    torch.cuda.synchronize()
+    assert all(torch.equal(p, q) for p, q in zip(a, b))
+    est = binding.gns_estimate(a[1], a[2], float(B)).cpu().numpy().astype(np.float64)
+    from oracle import linear_pegn_oracle as lin
+    ref = lin.linear_pegn(x, g)
+    _check_gns(est, oracle.gns_estimate(ref["s"], [np.sum(ref["w"] ** 2)], float(B)), B)
+
+
+def test_linear_pegn_argument_errors():
+    import torch
+    from paper_2411_00999_amd import binding
+    lib = binding.load()
+    x = torch.zeros((2, 8, 16), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((16, 16), dtype=torch.float32, device="cuda")
+    s = torch.zeros(2, dtype=torch.float32, device="cuda")
+    ws = torch.zeros(lib.linear_pegn_workspace_bytes(2, 8, 16, 16, 1), dtype=torch.uint8, device="cuda")
+    args = lambda **kw: [kw.get("x", x.data_ptr()), x.data_ptr(), w.data_ptr(), s.data_ptr(), None,
+                         kw.get("B", 2), 8, 16, 16, kw.get("dt", 1), ws.data_ptr(), kw.get("wsb", ws.numel()),
+                         kw.get("flags", 0), None]
+    assert lib.linear_pegn(*args()) == 0
+    assert lib.linear_pegn(*args(x=None)) == 1
+    assert lib.linear_pegn(*args(B=0)) == 1
+    assert lib.linear_pegn(*args(flags=1)) == 1
+    assert lib.linear_pegn(*args(dt=7)) == 2
+    assert lib.linear_pegn(*args(wsb=16)) == 3
+    assert lib.linear_pegn_workspace_bytes(0, 8, 16, 16, 1) == 0
+    torch.cuda.synchronize()
