@@ -64,30 +64,40 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
     const bool loads = wave < 6;
     const bool from_x = wave < 4;
     const int sub = from_x ? wave : wave - 4;
-    const int tb = lane & 7, cg = lane >> 3;
+    const int cg = lane & 7, tb = lane >> 3;                  // 8 adjacent lanes read one 128-byte line
     const int ncols = from_x ? a.K : a.L;
     const int col = (from_x ? k0 : l0) + sub * 64 + cg * 8;
     const bool col_ok = loads && col < ncols;                 // K, L are multiples of 8: all or nothing
     const uint16_t *src = from_x ? a.x : a.g;
-    const int lds_row = (from_x ? 0 : kTileK) + sub * 64 + cg * 8;
+    // Column cg*8 + i of a wave's 64 goes to LDS row i*8 + cg: the eight lanes of a line then write
+    // eight consecutive rows (bank-conflict free), and the compute side undoes the permutation when
+    // it names its outputs (an MFMA row can be any column as long as the result is filed under it).
+    const int lds_row = (from_x ? 0 : kTileK) + sub * 64 + cg;
     u32x4_t raw[8];
 
+    unsigned raw_ok = 0;                                       // bit j: row j of the block exists
     auto fetch = [&](int st) {
-        // branch-free: a load that would fall outside reads the tensor's first vector instead and is
-        // replaced by zeros afterwards
+        // branch-free, and nothing here waits for the data: a load that would fall outside reads the
+        // tensor's first vector instead and is replaced by zeros when the block is transposed
         const int b = b_begin + st / nst;
         const int t0 = (st % nst) * kStageT + tb * 8;
         const int64_t first = ((int64_t)b * a.T + t0) * ncols + col;
+        raw_ok = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const bool ok = col_ok && t0 + j < a.T;
-            const u32x4_t v = *reinterpret_cast<const u32x4_t *>(src + (ok ? first + (int64_t)j * ncols : 0));
-            raw[j] = ok ? v : u32x4_t{0u, 0u, 0u, 0u};
+            raw_ok |= (ok ? 1u : 0u) << j;
+            raw[j] = *reinterpret_cast<const u32x4_t *>(src + (ok ? first + (int64_t)j * ncols : 0));
         }
     };
     auto stash = [&](int buf) {
         if (!loads) return;
         unsigned char *base = lds[buf] + lds_row * kPitch + tb * 16;
+        if (raw_ok != 0xffu) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (!((raw_ok >> j) & 1u)) raw[j] = u32x4_t{0u, 0u, 0u, 0u};
+        }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {                          // column i of the block
             u32x4_t o;
@@ -96,7 +106,7 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
                 const uint32_t u = raw[2 * tp][i >> 1], v = raw[2 * tp + 1][i >> 1];
                 o[tp] = (i & 1) ? ((u >> 16) | (v & 0xffff0000u)) : ((u & 0xffffu) | (v << 16));
             }
-            *reinterpret_cast<u32x4_t *>(base + i * kPitch) = o;
+            *reinterpret_cast<u32x4_t *>(base + i * 8 * kPitch) = o;
         }
     };
 
@@ -161,17 +171,19 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
         __syncthreads();
     }
 
-    // ---- write the total: lane holds rows (i/4)*8 + (lane/32)*4 + i%4, column lane%32 of each 32x32 tile
+    // ---- write the total: lane holds rows (i/4)*8 + (lane/32)*4 + i%4, column lane%32 of each 32x32 tile,
+    // both in LDS row numbering; unperm() gives the column of x (of g) that sits in an LDS row
+    auto unperm = [](int p) { return (p & 7) * 8 + (p >> 3); };
     float *out = a.out + (a.nsplit > 1 ? (int64_t)split * a.K * a.L : 0);
     double bsq = 0.0;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) {
-            const int l = l0 + wn * 64 + ni * 32 + (lane & 31);
+            const int l = l0 + wn * 64 + unperm(ni * 32 + (lane & 31));
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int k = k0 + wm * 64 + mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+                const int k = k0 + wm * 64 + unperm(mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3));
                 if (k < a.K && l < a.L) {
                     float *p = out + (int64_t)k * a.L + l;
                     float v = tot[mi][ni][i];
