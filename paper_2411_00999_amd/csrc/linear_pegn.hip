@@ -126,14 +126,20 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
                 tot[mi][ni][i] = 0.f;
             }
 
-    if (nstages > 0) {
+    // Pipeline: stage st is multiplied out of LDS buffer st&1 while stage st+1 is transposed into the
+    // other buffer and stage st+2 is in flight from memory, so a load has a whole iteration to land.
+    if (loads && nstages > 0) {
         fetch(0);
         stash(0);
+        if (nstages > 1) fetch(1);
     }
     __syncthreads();
     for (int st = 0; st < nstages; ++st) {
         const int buf = st & 1;
-        if (st + 1 < nstages) fetch(st + 1);
+        if (loads) {
+            if (st + 1 < nstages) stash(buf ^ 1);
+            if (st + 2 < nstages) fetch(st + 2);
+        }
         const unsigned char *sa = lds[buf] + a_off, *sb = lds[buf] + b_off;
 #pragma unroll
         for (int kk = 0; kk < kStageT / 16; ++kk) {
@@ -167,7 +173,6 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
             ssq = wave_sum(ssq);
             if (lane == 0) a.tile_s[(int64_t)(tile * kWaves + wave) * a.B + b_begin + st / nst] = ssq;
         }
-        if (st + 1 < nstages) stash(buf ^ 1);
         __syncthreads();
     }
 
