@@ -256,21 +256,22 @@ __global__ __launch_bounds__(256) void linear_sum_splits_kernel(const float *par
     if (threadIdx.x == 0) blk_big[blockIdx.x] = bsq;
 }
 
-// s[b] = sum of its parts (fp64, part order); big_sq = sum of the parts of ||w'||^2.  One workgroup.
-__global__ __launch_bounds__(256) void linear_final_kernel(const float *part_s, int nparts, const double *part_big,
-                                                           int64_t nbig, float *s, float *big_sq, int B)
+// s[b] = sum of its parts, big_sq = sum of the parts of ||w'||^2; fp64, in an order fixed by the launch
+// shape alone (lane p % 64 takes parts p, p + 64, ...; then the wave's fixed-order sum).  Workgroup b
+// serves example b; workgroup B serves big_sq.
+__global__ __launch_bounds__(64) void linear_final_kernel(const float *part_s, int nparts, const double *part_big,
+                                                          int64_t nbig, float *s, float *big_sq, int B)
 {
-    __shared__ double dslots[4];
-    for (int b = threadIdx.x; b < B; b += blockDim.x) {
-        double t = 0.0;
-        for (int p = 0; p < nparts; ++p) t += (double)part_s[(int64_t)p * B + b];
-        s[b] = (float)t;
-    }
-    if (big_sq) {
-        double t = 0.0;
-        for (int64_t i = threadIdx.x; i < nbig; i += blockDim.x) t += part_big[i];
-        t = block_sum_f64(t, dslots);
-        if (threadIdx.x == 0) big_sq[0] = (float)t;
+    const int b = blockIdx.x, lane = threadIdx.x;
+    double t = 0.0;
+    if (b < B) {
+        for (int p = lane; p < nparts; p += 64) t += (double)part_s[(int64_t)p * B + b];
+        t = wave_sum_f64(t);
+        if (lane == 0) s[b] = (float)t;
+    } else if (big_sq) {
+        for (int64_t i = lane; i < nbig; i += 64) t += part_big[i];
+        t = wave_sum_f64(t);
+        if (lane == 0) big_sq[0] = (float)t;
     }
 }
 
@@ -381,7 +382,7 @@ int linear_pegn(const void *x, const void *g, float *w, float *s, float *big_sq,
                 accumulate);
         if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
     }
-    linear_final_kernel<<<dim3(1), dim3(256), 0, st>>>(part_s, p.nparts, part_big, p.nbig, s, big_sq, B);
+    linear_final_kernel<<<dim3(B + 1), dim3(64), 0, st>>>(part_s, p.nparts, part_big, p.nbig, s, big_sq, B);
     return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
 }
 
