@@ -31,7 +31,7 @@ struct LinArgs {
     const uint16_t *x;      // [B,T,K] bf16
     const uint16_t *g;      // [B,T,L] bf16
     float *out;             // nsplit == 1: w [K,L]; else partial totals [nsplit][K][L]
-    float *tile_s;          // [ntiles*kWaves][B] per-wave parts of s[b]
+    float *tile_s;          // [B][ntiles*kWaves] per-wave parts of s[b]
     double *tile_big;       // [ntiles*kWaves] per-wave parts of ||w'||^2 (nsplit == 1 only)
     int B, T, K, L;
     int tiles_k, tiles_l, nsplit, b_per_split;
@@ -49,7 +49,8 @@ __device__ __forceinline__ int xcd_spread(int bid, int n)
 __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
 {
     __shared__ __align__(16) unsigned char lds[2][kStageBytes];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: branches on it are scalar
     const int ntiles = a.tiles_k * a.tiles_l;
     const int tile = xcd_spread(blockIdx.x, ntiles);
     const int split = blockIdx.y;
@@ -76,22 +77,28 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
     u32x4_t raw[8];
 
     unsigned raw_ok = 0;                                       // bit j: row j of the block exists
-    auto fetch = [&](int st) {
-        // branch-free, and nothing here waits for the data: a load that would fall outside reads the
-        // tensor's first vector instead and is replaced by zeros when the block is transposed
-        const int b = b_begin + st / nst;
-        const int t0 = (st % nst) * kStageT + tb * 8;
-        const int64_t first = ((int64_t)b * a.T + t0) * ncols + col;
+    int fb = b_begin, fs = 0;                                  // the next stage to fetch: example, stage in it
+    const int colx = col_ok ? col : 0;
+    auto fetch = [&]() {
+        // nothing here waits for the data; a row past the end of the example is read from the
+        // example's last row instead and replaced by zeros when the block is transposed
+        const int rows_left = a.T - fs * kStageT;
+        const uint16_t *base = src + ((int64_t)fb * a.T + fs * kStageT) * ncols + colx;
         raw_ok = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const bool ok = col_ok && t0 + j < a.T;
+            const int r = tb * 8 + j;
+            const bool ok = col_ok && r < rows_left;
             raw_ok |= (ok ? 1u : 0u) << j;
-            raw[j] = *reinterpret_cast<const u32x4_t *>(src + (ok ? first + (int64_t)j * ncols : 0));
+            const int rc = r < rows_left ? r : rows_left - 1;
+            raw[j] = *reinterpret_cast<const u32x4_t *>(base + (int64_t)rc * ncols);
+        }
+        if (++fs == nst) {
+            fs = 0;
+            ++fb;
         }
     };
     auto stash = [&](int buf) {
-        if (!loads) return;
         unsigned char *base = lds[buf] + lds_row * kPitch + tb * 16;
         if (raw_ok != 0xffu) {
 #pragma unroll
@@ -128,18 +135,11 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
 
     // Pipeline: stage st is multiplied out of LDS buffer st&1 while stage st+1 is transposed into the
     // other buffer and stage st+2 is in flight from memory, so a load has a whole iteration to land.
-    if (loads && nstages > 0) {
-        fetch(0);
-        stash(0);
-        if (nstages > 1) fetch(1);
-    }
-    __syncthreads();
-    for (int st = 0; st < nstages; ++st) {
-        const int buf = st & 1;
-        if (loads) {
-            if (st + 1 < nstages) stash(buf ^ 1);
-            if (st + 2 < nstages) fetch(st + 2);
-        }
+    // Loading and non-loading waves run separate copies of the loop (the branch is scalar), so that in
+    // a loading wave the transpose of one block and the MFMAs of another sit in one basic block and the
+    // scheduler can put the former into the shadow of the latter.
+    int cb = b_begin, cs = 0;                                  // the stage being multiplied
+    auto multiply = [&](int buf) {
         const unsigned char *sa = lds[buf] + a_off, *sb = lds[buf] + b_off;
 #pragma unroll
         for (int kk = 0; kk < kStageT / 16; ++kk) {
@@ -156,24 +156,62 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
                 for (int ni = 0; ni < 2; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
         }
-        if (st % nst == nst - 1) {
-            // example boundary: step 2 on this wave's 64 x 64 part, then fold it into the total (step 3)
-            float ssq = 0.f;
+    };
+    auto example_done = [&]() {
+        // example boundary: step 2 on this wave's 64 x 64 part, then fold it into the total (step 3)
+        float ssq = 0.f;
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
+        for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
+            for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float v = acc[mi][ni][i];
-                        ssq = fmaf(v, v, ssq);
-                        tot[mi][ni][i] += v;
-                        acc[mi][ni][i] = 0.f;
-                    }
-            ssq = wave_sum(ssq);
-            if (lane == 0) a.tile_s[(int64_t)(tile * kWaves + wave) * a.B + b_begin + st / nst] = ssq;
+                for (int i = 0; i < 16; ++i) {
+                    const float v = acc[mi][ni][i];
+                    ssq = fmaf(v, v, ssq);
+                    tot[mi][ni][i] += v;
+                    acc[mi][ni][i] = 0.f;
+                }
+        ssq = wave_sum(ssq);
+        if (lane == 0) a.tile_s[(int64_t)cb * (ntiles * kWaves) + tile * kWaves + wave] = ssq;
+        ++cb;
+    };
+    if (loads) {
+        if (nstages > 0) {
+            fetch();
+            stash(0);
+            if (nstages > 1) fetch();
         }
         __syncthreads();
+        int st = 0;
+        for (; st + 2 < nstages; ++st) {                       // steady state: no conditions in the body
+            stash((st & 1) ^ 1);
+            fetch();
+            multiply(st & 1);
+            if (++cs == nst) {
+                cs = 0;
+                example_done();
+            }
+            __syncthreads();
+        }
+        for (; st < nstages; ++st) {
+            if (st + 1 < nstages) stash((st & 1) ^ 1);
+            multiply(st & 1);
+            if (++cs == nst) {
+                cs = 0;
+                example_done();
+            }
+            __syncthreads();
+        }
+    } else {
+        __syncthreads();
+        for (int st = 0; st < nstages; ++st) {
+            multiply(st & 1);
+            if (++cs == nst) {
+                cs = 0;
+                example_done();
+            }
+            __syncthreads();
+        }
     }
 
     // ---- write the total: lane holds rows (i/4)*8 + (lane/32)*4 + i%4, column lane%32 of each 32x32 tile,
@@ -226,7 +264,7 @@ __global__ __launch_bounds__(256) void linear_pegn_generic_kernel(const T *x, co
         }
         total += acc;
         const float ssq = block_sum(acc * acc, slots);
-        if (threadIdx.x == 0) blk_s[(int64_t)blk * B + b] = ssq;
+        if (threadIdx.x == 0) blk_s[(int64_t)b * (gridDim.x * gridDim.y) + blk] = ssq;
     }
     double bsq = 0.0;
     if (ok) {
@@ -257,21 +295,22 @@ __global__ __launch_bounds__(256) void linear_sum_splits_kernel(const float *par
 }
 
 // s[b] = sum of its parts, big_sq = sum of the parts of ||w'||^2; fp64, in an order fixed by the launch
-// shape alone (lane p % 64 takes parts p, p + 64, ...; then the wave's fixed-order sum).  Workgroup b
-// serves example b; workgroup B serves big_sq.
-__global__ __launch_bounds__(64) void linear_final_kernel(const float *part_s, int nparts, const double *part_big,
-                                                          int64_t nbig, float *s, float *big_sq, int B)
+// shape alone (thread p % 1024 takes parts p, p + 1024, ...; then the fixed-order block sum).
+// Workgroup b serves example b; workgroup B serves big_sq.
+__global__ __launch_bounds__(1024) void linear_final_kernel(const float *part_s, int nparts, const double *part_big,
+                                                            int64_t nbig, float *s, float *big_sq, int B)
 {
-    const int b = blockIdx.x, lane = threadIdx.x;
+    __shared__ double slots[16];
+    const int b = blockIdx.x;
     double t = 0.0;
     if (b < B) {
-        for (int p = lane; p < nparts; p += 64) t += (double)part_s[(int64_t)p * B + b];
-        t = wave_sum_f64(t);
-        if (lane == 0) s[b] = (float)t;
+        for (int p = threadIdx.x; p < nparts; p += 1024) t += (double)part_s[(int64_t)b * nparts + p];
+        t = block_sum_f64(t, slots);
+        if (threadIdx.x == 0) s[b] = (float)t;
     } else if (big_sq) {
-        for (int64_t i = lane; i < nbig; i += 64) t += part_big[i];
-        t = wave_sum_f64(t);
-        if (lane == 0) big_sq[0] = (float)t;
+        for (int64_t i = threadIdx.x; i < nbig; i += 1024) t += part_big[i];
+        t = block_sum_f64(t, slots);
+        if (threadIdx.x == 0) big_sq[0] = (float)t;
     }
 }
 
@@ -382,7 +421,7 @@ int linear_pegn(const void *x, const void *g, float *w, float *s, float *big_sq,
                 accumulate);
         if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
     }
-    linear_final_kernel<<<dim3(B + 1), dim3(64), 0, st>>>(part_s, p.nparts, part_big, p.nbig, s, big_sq, B);
+    linear_final_kernel<<<dim3(B + 1), dim3(1024), 0, st>>>(part_s, p.nparts, part_big, p.nbig, s, big_sq, B);
     return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
 }
 
