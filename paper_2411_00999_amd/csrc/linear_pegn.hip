@@ -48,7 +48,9 @@ __device__ __forceinline__ int xcd_spread(int bid, int n)
 
 __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
 {
-    __shared__ __align__(16) unsigned char lds[2][kStageBytes];
+    // two named buffers rather than an indexed pair: the compiler then knows that writing one and
+    // reading the other never alias, and may interleave the two
+    __shared__ __align__(16) unsigned char lds0[kStageBytes], lds1[kStageBytes];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: branches on it are scalar
     const int ntiles = a.tiles_k * a.tiles_l;
@@ -98,8 +100,8 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
             ++fb;
         }
     };
-    auto stash = [&](int buf) {
-        unsigned char *base = lds[buf] + lds_row * kPitch + tb * 16;
+    auto stash = [&](unsigned char *dst) {
+        unsigned char *base = dst + lds_row * kPitch + tb * 16;
         if (raw_ok != 0xffu) {
 #pragma unroll
             for (int j = 0; j < 8; ++j)
@@ -139,8 +141,8 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
     // a loading wave the transpose of one block and the MFMAs of another sit in one basic block and the
     // scheduler can put the former into the shadow of the latter.
     int cb = b_begin, cs = 0;                                  // the stage being multiplied
-    auto multiply = [&](int buf) {
-        const unsigned char *sa = lds[buf] + a_off, *sb = lds[buf] + b_off;
+    auto multiply = [&](const unsigned char *cur) {
+        const unsigned char *sa = cur + a_off, *sb = cur + b_off;
 #pragma unroll
         for (int kk = 0; kk < kStageT / 16; ++kk) {
             bf16x8_t fa[2], fb[2];
@@ -175,41 +177,60 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
         if (lane == 0) a.tile_s[(int64_t)cb * (ntiles * kWaves) + tile * kWaves + wave] = ssq;
         ++cb;
     };
+    auto interleave = [&]() {
+        // Ask the scheduler for one MFMA, then a handful of the transpose's VALU operations in its
+        // shadow, an LDS write and an LDS read, sixteen times over; the loads for stage st+2 last.
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x020, 8, 0);
+    };
+    auto boundary = [&]() {
+        if (++cs == nst) {
+            cs = 0;
+            example_done();
+        }
+    };
     if (loads) {
         if (nstages > 0) {
             fetch();
-            stash(0);
+            stash(lds0);
             if (nstages > 1) fetch();
         }
         __syncthreads();
         int st = 0;
-        for (; st + 2 < nstages; ++st) {                       // steady state: no conditions in the body
-            stash((st & 1) ^ 1);
+        for (; st + 3 < nstages; st += 2) {                    // steady state: no conditions in the bodies
+            stash(lds1);
             fetch();
-            multiply(st & 1);
-            if (++cs == nst) {
-                cs = 0;
-                example_done();
-            }
+            multiply(lds0);
+            interleave();
+            boundary();
+            __syncthreads();
+            stash(lds0);
+            fetch();
+            multiply(lds1);
+            interleave();
+            boundary();
             __syncthreads();
         }
         for (; st < nstages; ++st) {
-            if (st + 1 < nstages) stash((st & 1) ^ 1);
-            multiply(st & 1);
-            if (++cs == nst) {
-                cs = 0;
-                example_done();
-            }
+            unsigned char *cur = (st & 1) ? lds1 : lds0, *nxt = (st & 1) ? lds0 : lds1;
+            if (st + 1 < nstages) stash(nxt);
+            if (st + 2 < nstages) fetch();
+            multiply(cur);
+            boundary();
             __syncthreads();
         }
     } else {
         __syncthreads();
         for (int st = 0; st < nstages; ++st) {
-            multiply(st & 1);
-            if (++cs == nst) {
-                cs = 0;
-                example_done();
-            }
+            multiply((st & 1) ? lds1 : lds0);
+            boundary();
             __syncthreads();
         }
     }
