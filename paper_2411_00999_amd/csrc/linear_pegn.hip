@@ -15,16 +15,29 @@ namespace lnpegn {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
-// Workgroup tile: 256 (k) x 128 (l) outputs, 64 positions t per LDS stage, 8 waves as 4 (k) x 2 (l),
-// each wave 64 x 64 = 2 x 2 MFMA tiles of 32 x 32.  Operands sit in LDS transposed, [column][t], so an
-// MFMA operand (8 consecutive t of one column) is one 16-byte read; rows are padded to 144 bytes,
-// which spreads 16 consecutive columns over all 64 banks.
+// Workgroup tile: 256 (k) x 128 (l) outputs, 64 positions t per stage, 8 waves as 4 (k) x 2 (l), each
+// wave 64 x 64 = 2 x 2 MFMA tiles of 32 x 32 (v_mfma_f32_32x32x16_bf16).
+//
+// A stage sits in LDS the way it sits in memory, [t][column]: 64 rows of 512 bytes of x followed by 64
+// rows of 256 bytes of g.  It gets there by loads that write LDS directly (no registers in between),
+// three stages deep: one being multiplied, one landed or landing, one just issued.  The MFMA operand
+// of a lane is 8 consecutive t of ONE column, i.e. a column of that layout; the transposing LDS read
+// (ds_read_b64_tr_b16: 16 lanes read a 4 x 16 block as 4 rows, each lane receives one column of it)
+// delivers exactly that, two reads per operand.  The four rows of such a block are a whole row pitch
+// apart, which is a multiple of all banks, so the 16-byte chunks of row r are stored at chunk index
+// c ^ 4*(r & 3); a direct-to-LDS load writes a wave's 64 chunks contiguously, so the swizzle is applied
+// by choosing which chunk of memory each lane fetches.
 constexpr int kTileK = 256, kTileL = 128, kStageT = 64, kThreads = 512, kWaves = 8;
-constexpr int kPitch = 144;                                   // bytes per LDS row (64 t x 2 B + 16)
-constexpr int kStageBytes = (kTileK + kTileL) * kPitch;       // 55,296
+constexpr int kXRow = kTileK * 2, kGRow = kTileL * 2;          // bytes per LDS row
+constexpr int kXBytes = kStageT * kXRow, kGBytes = kStageT * kGRow;
+constexpr int kStageBytes = kXBytes + kGBytes;                // 49,152
+constexpr int kBufs = 3;
+constexpr int kLoadsPerWave = kStageBytes / 1024 / kWaves;    // 6 direct loads of 1 KiB per wave and stage
 constexpr int kMaxSplit = 64;
 
 struct LinArgs {
@@ -46,11 +59,20 @@ __device__ __forceinline__ int xcd_spread(int bid, int n)
     return xcd * q + (xcd < r ? xcd : r) + loc;
 }
 
+// One direct-to-LDS load: every active lane moves 16 bytes from base + voff to LDS address
+// lds_addr + 16*lane.  Written in assembly so that the compiler does not know of it: it would make the
+// wave wait for the data before the next barrier, and the point is to wait two stages later.
+__device__ __forceinline__ void load_to_lds(uint32_t lds_addr, uint32_t voff, const void *base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory");
+}
+
 __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
 {
-    // two named buffers rather than an indexed pair: the compiler then knows that writing one and
-    // reading the other never alias, and may interleave the two
-    __shared__ __align__(16) unsigned char lds0[kStageBytes], lds1[kStageBytes];
+    __shared__ __align__(1024) unsigned char lds[kBufs * kStageBytes];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: branches on it are scalar
     const int ntiles = a.tiles_k * a.tiles_l;
@@ -61,69 +83,74 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
     const int b_end = b_begin + a.b_per_split < a.B ? b_begin + a.b_per_split : a.B;
     const int nst = (a.T + kStageT - 1) / kStageT;
     const int nstages = (b_end - b_begin) * nst;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
 
-    // ---- loader role: waves 0-3 bring 64 columns of x each, waves 4-5 bring 64 columns of g each.
-    // A lane owns an 8 (t) x 8 (column) block: eight 16-byte row loads, transposed in registers.
-    const bool loads = wave < 6;
-    const bool from_x = wave < 4;
-    const int sub = from_x ? wave : wave - 4;
-    const int cg = lane & 7, tb = lane >> 3;                  // 8 adjacent lanes read one 128-byte line
-    const int ncols = from_x ? a.K : a.L;
-    const int col = (from_x ? k0 : l0) + sub * 64 + cg * 8;
-    const bool col_ok = loads && col < ncols;                 // K, L are multiples of 8: all or nothing
-    const uint16_t *src = from_x ? a.x : a.g;
-    // Column cg*8 + i of a wave's 64 goes to LDS row i*8 + cg: the eight lanes of a line then write
-    // eight consecutive rows (bank-conflict free), and the compute side undoes the permutation when
-    // it names its outputs (an MFMA row can be any column as long as the result is filed under it).
-    const int lds_row = (from_x ? 0 : kTileK) + sub * 64 + cg;
-    u32x4_t raw[8];
-
-    unsigned raw_ok = 0;                                       // bit j: row j of the block exists
-    int fb = b_begin, fs = 0;                                  // the next stage to fetch: example, stage in it
-    const int colx = col_ok ? col : 0;
-    auto fetch = [&]() {
-        // nothing here waits for the data; a row past the end of the example is read from the
-        // example's last row instead and replaced by zeros when the block is transposed
-        const int rows_left = a.T - fs * kStageT;
-        const uint16_t *base = src + ((int64_t)fb * a.T + fs * kStageT) * ncols + colx;
-        raw_ok = 0;
+    // ---- loading: the 48 KiB of a stage are 48 loads of 1 KiB; wave w issues loads 6w .. 6w+5.
+    // Loads 0..31 are rows 2i, 2i+1 of x (32 chunks each), loads 32..47 rows 4j .. 4j+3 of g (16 chunks).
+    // Per load and lane: the row and the chunk of memory that belongs at this lane's LDS position.
+    uint32_t voff[kLoadsPerWave];        // byte offset from the stage's first element of x (or g)
+    int lrow[kLoadsPerWave];             // row within the stage
+    bool lcol_ok[kLoadsPerWave];         // the chunk's columns exist (edge tiles)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int r = tb * 8 + j;
-            const bool ok = col_ok && r < rows_left;
-            raw_ok |= (ok ? 1u : 0u) << j;
-            const int rc = r < rows_left ? r : rows_left - 1;
-            raw[j] = *reinterpret_cast<const u32x4_t *>(base + (int64_t)rc * ncols);
+    for (int n = 0; n < kLoadsPerWave; ++n) {
+        const int i = wave * kLoadsPerWave + n;
+        if (i < 32) {
+            const int r = 2 * i + (lane >> 5), c = (lane & 31) ^ ((r & 3) << 2);
+            lrow[n] = r;
+            lcol_ok[n] = k0 + c * 8 < a.K;
+            voff[n] = (uint32_t)(((int64_t)r * a.K + c * 8) * 2);
+        } else {
+            const int r = 4 * (i - 32) + (lane >> 4), c = (lane & 15) ^ ((r & 3) << 2);
+            lrow[n] = r;
+            lcol_ok[n] = l0 + c * 8 < a.L;
+            voff[n] = (uint32_t)(((int64_t)r * a.L + c * 8) * 2);
+        }
+    }
+    // A workgroup whose tile lies inside the matrix, on examples that are whole stages long, never has
+    // a lane without data: it issues exactly six loads per wave and stage and may count on that when it
+    // waits.  Any other workgroup masks lanes, zero-fills their chunks and waits for everything.
+    const bool regular = a.T % kStageT == 0 && k0 + kTileK <= a.K && l0 + kTileL <= a.L;
+    int fb = b_begin, fs = 0;                                  // the next stage to fetch: example, stage in it
+    auto fetch = [&](int buf) {
+        const int64_t row0 = (int64_t)fb * a.T + fs * kStageT;
+        const uint16_t *xs = a.x + row0 * a.K + k0, *gs = a.g + row0 * a.L + l0;
+        const uint32_t dst = lds_base + buf * kStageBytes + wave * kLoadsPerWave * 1024;
+        if (regular) {
+#pragma unroll
+            for (int n = 0; n < kLoadsPerWave; ++n)
+                load_to_lds(dst + n * 1024, voff[n], wave * kLoadsPerWave + n < 32 ? (const void *)xs : (const void *)gs);
+        } else {
+            const int rows_left = a.T - fs * kStageT;
+#pragma unroll
+            for (int n = 0; n < kLoadsPerWave; ++n) {
+                if (lcol_ok[n] && lrow[n] < rows_left)
+                    load_to_lds(dst + n * 1024, voff[n],
+                                wave * kLoadsPerWave + n < 32 ? (const void *)xs : (const void *)gs);
+                else
+                    *reinterpret_cast<u32x4_t *>(lds + buf * kStageBytes + (wave * kLoadsPerWave + n) * 1024 +
+                                                 lane * 16) = u32x4_t{0u, 0u, 0u, 0u};
+            }
         }
         if (++fs == nst) {
             fs = 0;
             ++fb;
         }
     };
-    auto stash = [&](unsigned char *dst) {
-        unsigned char *base = dst + lds_row * kPitch + tb * 16;
-        if (raw_ok != 0xffu) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (!((raw_ok >> j) & 1u)) raw[j] = u32x4_t{0u, 0u, 0u, 0u};
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {                          // column i of the block
-            u32x4_t o;
-#pragma unroll
-            for (int tp = 0; tp < 4; ++tp) {                   // positions 2tp, 2tp+1
-                const uint32_t u = raw[2 * tp][i >> 1], v = raw[2 * tp + 1][i >> 1];
-                o[tp] = (i & 1) ? ((u >> 16) | (v & 0xffff0000u)) : ((u & 0xffffu) | (v << 16));
-            }
-            *reinterpret_cast<u32x4_t *>(base + i * 8 * kPitch) = o;
-        }
-    };
 
-    // ---- compute role: wave (wm, wn) owns outputs k0 + wm*64 .. +64, l0 + wn*64 .. +64
+    // ---- multiplying: wave (wm, wn) owns outputs k0 + wm*64 .. +64, l0 + wn*64 .. +64.
+    // For a transposing read, lane s of a 16-lane group reads row s/4 of the block, columns 4*(s%4) .. +3;
+    // group g of the wave takes columns (g%2)*16 .. +15 of the 32 and positions (g/2)*8 .. +7 of the 16.
     const int wm = wave & 3, wn = wave >> 2;
-    const int frag_off = (lane & 31) * kPitch + (lane >> 5) * 16;
-    const int a_off = (wm * 64) * kPitch + frag_off;
-    const int b_off = (kTileK + wn * 64) * kPitch + frag_off;
+    const int s16 = lane & 15, grp = lane >> 4;
+    const int rr = (grp >> 1) * 8 + (s16 >> 2);                // row within the 16 positions (first of two reads)
+    uint32_t a_addr[2], b_addr[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int qa = wm * 8 + i * 4 + (grp & 1) * 2 + ((s16 & 3) >> 1);
+        const int qb = wn * 8 + i * 4 + (grp & 1) * 2 + ((s16 & 3) >> 1);
+        a_addr[i] = rr * kXRow + ((qa ^ ((s16 >> 2) << 2)) * 16) + (s16 & 1) * 8;
+        b_addr[i] = kXBytes + rr * kGRow + ((qb ^ ((s16 >> 2) << 2)) * 16) + (s16 & 1) * 8;
+    }
     f32x16_t acc[2][2], tot[2][2];
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
@@ -134,32 +161,34 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
                 acc[mi][ni][i] = 0.f;
                 tot[mi][ni][i] = 0.f;
             }
-
-    // Pipeline: stage st is multiplied out of LDS buffer st&1 while stage st+1 is transposed into the
-    // other buffer and stage st+2 is in flight from memory, so a load has a whole iteration to land.
-    // Loading and non-loading waves run separate copies of the loop (the branch is scalar), so that in
-    // a loading wave the transpose of one block and the MFMAs of another sit in one basic block and the
-    // scheduler can put the former into the shadow of the latter.
-    int cb = b_begin, cs = 0;                                  // the stage being multiplied
-    auto multiply = [&](const unsigned char *cur) {
-        const unsigned char *sa = cur + a_off, *sb = cur + b_off;
+    auto multiply = [&](int buf) {
+        const uint32_t base = lds_base + buf * kStageBytes;
 #pragma unroll
         for (int kk = 0; kk < kStageT / 16; ++kk) {
-            bf16x8_t fa[2], fb[2];
+            bf16x8_t fa[2], fb2[2];
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-                fa[mi] = *reinterpret_cast<const bf16x8_t *>(sa + mi * 32 * kPitch + kk * 32);
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-                fb[ni] = *reinterpret_cast<const bf16x8_t *>(sb + ni * 32 * kPitch + kk * 32);
+            for (int i = 0; i < 2; ++i) {
+                const uint32_t pa = base + a_addr[i] + kk * 16 * kXRow, pb = base + b_addr[i] + kk * 16 * kGRow;
+                const s16x4_t a_lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(uintptr_t)pa);
+                const s16x4_t a_hi =
+                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(uintptr_t)(pa + 4 * kXRow));
+                const s16x4_t b_lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(uintptr_t)pb);
+                const s16x4_t b_hi =
+                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(uintptr_t)(pb + 4 * kGRow));
+                fa[i] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(a_lo, a_hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                fb2[i] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(b_lo, b_hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < 2; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb2[ni], acc[mi][ni], 0, 0, 0);
         }
     };
-    auto example_done = [&]() {
+    int cb = b_begin, cs = 0;                                  // the stage being multiplied
+    auto boundary = [&]() {
+        if (++cs < nst) return;
+        cs = 0;
         // example boundary: step 2 on this wave's 64 x 64 part, then fold it into the total (step 3)
         float ssq = 0.f;
 #pragma unroll
@@ -177,77 +206,34 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
         if (lane == 0) a.tile_s[(int64_t)cb * (ntiles * kWaves) + tile * kWaves + wave] = ssq;
         ++cb;
     };
-    auto interleave = [&]() {
-        // Ask the scheduler for one MFMA, then a handful of the transpose's VALU operations in its
-        // shadow, an LDS write and an LDS read, sixteen times over; the loads for stage st+2 last.
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);
-            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x020, 8, 0);
-    };
-    auto boundary = [&]() {
-        if (++cs == nst) {
-            cs = 0;
-            example_done();
-        }
-    };
-    if (loads) {
-        if (nstages > 0) {
-            fetch();
-            stash(lds0);
-            if (nstages > 1) fetch();
-        }
+
+    // ---- pipeline: before multiplying stage st a wave waits for its own loads of that stage (those of
+    // stage st+1, issued later, may still be under way), the barrier then says that every wave's part has
+    // landed and that stage st-1 has been read by all, so its buffer can take stage st+2.
+    if (nstages > 0) fetch(0);
+    if (nstages > 1) fetch(1);
+    for (int st = 0; st < nstages; ++st) {
+        if (regular && st + 1 < nstages)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerWave) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        int st = 0;
-        for (; st + 3 < nstages; st += 2) {                    // steady state: no conditions in the bodies
-            stash(lds1);
-            fetch();
-            multiply(lds0);
-            interleave();
-            boundary();
-            __syncthreads();
-            stash(lds0);
-            fetch();
-            multiply(lds1);
-            interleave();
-            boundary();
-            __syncthreads();
-        }
-        for (; st < nstages; ++st) {
-            unsigned char *cur = (st & 1) ? lds1 : lds0, *nxt = (st & 1) ? lds0 : lds1;
-            if (st + 1 < nstages) stash(nxt);
-            if (st + 2 < nstages) fetch();
-            multiply(cur);
-            boundary();
-            __syncthreads();
-        }
-    } else {
-        __syncthreads();
-        for (int st = 0; st < nstages; ++st) {
-            multiply((st & 1) ? lds1 : lds0);
-            boundary();
-            __syncthreads();
-        }
+        if (st + 2 < nstages) fetch((st + 2) % kBufs);
+        multiply(st % kBufs);
+        boundary();
     }
 
-    // ---- write the total: lane holds rows (i/4)*8 + (lane/32)*4 + i%4, column lane%32 of each 32x32 tile,
-    // both in LDS row numbering; unperm() gives the column of x (of g) that sits in an LDS row
-    auto unperm = [](int p) { return (p & 7) * 8 + (p >> 3); };
+    // ---- write the total: lane holds rows (i/4)*8 + (lane/32)*4 + i%4, column lane%32 of each 32x32 tile
     float *out = a.out + (a.nsplit > 1 ? (int64_t)split * a.K * a.L : 0);
     double bsq = 0.0;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) {
-            const int l = l0 + wn * 64 + unperm(ni * 32 + (lane & 31));
+            const int l = l0 + wn * 64 + ni * 32 + (lane & 31);
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int k = k0 + wm * 64 + unperm(mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3));
+                const int k = k0 + wm * 64 + mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
                 if (k < a.K && l < a.L) {
                     float *p = out + (int64_t)k * a.L + l;
                     float v = tot[mi][ni][i];
