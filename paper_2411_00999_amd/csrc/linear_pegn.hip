@@ -161,20 +161,26 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
                 acc[mi][ni][i] = 0.f;
                 tot[mi][ni][i] = 0.f;
             }
+    typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+    typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
     auto multiply = [&](int buf) {
-        const uint32_t base = lds_base + buf * kStageBytes;
+        // one address per operand row block and stage; everything else is an immediate offset
+        const lds_byte_t *base = (const lds_byte_t *)lds + buf * kStageBytes;
+        const lds_byte_t *pa[2] = {base + a_addr[0], base + a_addr[1]};
+        const lds_byte_t *pb[2] = {base + b_addr[0], base + b_addr[1]};
 #pragma unroll
         for (int kk = 0; kk < kStageT / 16; ++kk) {
             bf16x8_t fa[2], fb2[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const uint32_t pa = base + a_addr[i] + kk * 16 * kXRow, pb = base + b_addr[i] + kk * 16 * kGRow;
-                const s16x4_t a_lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(uintptr_t)pa);
+                const s16x4_t a_lo =
+                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(pa[i] + kk * 16 * kXRow));
                 const s16x4_t a_hi =
-                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(uintptr_t)(pa + 4 * kXRow));
-                const s16x4_t b_lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(uintptr_t)pb);
+                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(pa[i] + kk * 16 * kXRow + 4 * kXRow));
+                const s16x4_t b_lo =
+                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(pb[i] + kk * 16 * kGRow));
                 const s16x4_t b_hi =
-                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(uintptr_t)(pb + 4 * kGRow));
+                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(pb[i] + kk * 16 * kGRow + 4 * kGRow));
                 fa[i] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(a_lo, a_hi, 0, 1, 2, 3, 4, 5, 6, 7));
                 fb2[i] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(b_lo, b_hi, 0, 1, 2, 3, 4, 5, 6, 7));
             }
