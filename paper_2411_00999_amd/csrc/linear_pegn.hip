@@ -20,25 +20,38 @@ typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
-// Workgroup tile: 256 (k) x 128 (l) outputs, 64 positions t per stage, 8 waves as 4 (k) x 2 (l), each
-// wave 64 x 64 = 2 x 2 MFMA tiles of 32 x 32 (v_mfma_f32_32x32x16_bf16).
+// Workgroup tile: (WM*MI*32) (k) x (WN*NI*32) (l) outputs, 64 positions t per stage, WM x WN waves, each
+// wave MI x NI MFMA tiles of 32 x 32 (v_mfma_f32_32x32x16_bf16).
 //
-// A stage sits in LDS the way it sits in memory, [t][column]: 64 rows of 512 bytes of x followed by 64
-// rows of 256 bytes of g.  It gets there by loads that write LDS directly (no registers in between),
-// three stages deep: one being multiplied, one landed or landing, one just issued.  The MFMA operand
-// of a lane is 8 consecutive t of ONE column, i.e. a column of that layout; the transposing LDS read
+// A stage sits in LDS the way it sits in memory, [t][column]: 64 rows of x followed by 64 rows of g.
+// It gets there by loads that write LDS directly (no registers in between), three stages deep: one
+// being multiplied, one landed or landing, one just issued.  The MFMA operand of a lane is 8
+// consecutive t of ONE column, i.e. a column of that layout; the transposing LDS read
 // (ds_read_b64_tr_b16: 16 lanes read a 4 x 16 block as 4 rows, each lane receives one column of it)
 // delivers exactly that, two reads per operand.  The four rows of such a block are a whole row pitch
 // apart, which is a multiple of all banks, so the 16-byte chunks of row r are stored at chunk index
 // c ^ 4*(r & 3); a direct-to-LDS load writes a wave's 64 chunks contiguously, so the swizzle is applied
 // by choosing which chunk of memory each lane fetches.
-constexpr int kTileK = 256, kTileL = 128, kStageT = 64, kThreads = 512, kWaves = 8;
-constexpr int kXRow = kTileK * 2, kGRow = kTileL * 2;          // bytes per LDS row
-constexpr int kXBytes = kStageT * kXRow, kGBytes = kStageT * kGRow;
-constexpr int kStageBytes = kXBytes + kGBytes;                // 49,152
-constexpr int kBufs = 3;
-constexpr int kLoadsPerWave = kStageBytes / 1024 / kWaves;    // 6 direct loads of 1 KiB per wave and stage
-constexpr int kMaxSplit = 64;
+constexpr int kStageT = 64, kBufs = 3, kMaxSplit = 64;
+
+template <int WM, int WN, int MI, int NI>
+struct LinCfg {
+    static constexpr int kWaves = WM * WN, kThreads = 64 * kWaves;
+    static constexpr int kTileK = WM * MI * 32, kTileL = WN * NI * 32;
+    static constexpr int kXRow = kTileK * 2, kGRow = kTileL * 2;          // bytes per LDS row
+    static constexpr int kXBytes = kStageT * kXRow, kGBytes = kStageT * kGRow;
+    static constexpr int kStageBytes = kXBytes + kGBytes;
+    static constexpr int kXLoads = kXBytes / 1024, kLoads = kStageBytes / 1024;   // direct loads of 1 KiB
+    static constexpr int kLoadsPerWave = kLoads / kWaves;
+    static_assert(kLoads % kWaves == 0, "loads must divide evenly over the waves");
+    static_assert(kXRow >= 256 && kGRow >= 256 && kXRow <= 1024 && kGRow <= 1024, "row of 16..64 chunks");
+    static_assert(kBufs * kStageBytes <= 160 * 1024, "three stages must fit in LDS");
+};
+// 8 waves (two per SIMD, so one can issue MFMAs while the other waits for LDS), each 64 x 64: 256 x 128
+// per workgroup.  Measured against 4 waves of 128 x 64 (one per SIMD, fewer LDS reads per MFMA): the
+// lone wave cannot cover its own LDS latency and is 30 % slower.
+#define LIN_CFG 4, 2, 2, 2
+typedef LinCfg<LIN_CFG> Cfg;
 
 struct LinArgs {
     const uint16_t *x;      // [B,T,K] bf16
@@ -70,46 +83,51 @@ __device__ __forceinline__ void load_to_lds(uint32_t lds_addr, uint32_t voff, co
                  : "memory");
 }
 
-__global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
+template <typename C, int WM, int WN, int MI, int NI>
+__device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
 {
+    constexpr int kWaves = C::kWaves, kLoadsPerWave = C::kLoadsPerWave, kStageBytes = C::kStageBytes;
+    constexpr int kXRow = C::kXRow, kGRow = C::kGRow, kXBytes = C::kXBytes;
+    constexpr int kXChunks = kXRow / 16, kGChunks = kGRow / 16;       // 16-byte chunks per row
+    constexpr int kXRowsPerLoad = 64 / kXChunks, kGRowsPerLoad = 64 / kGChunks;
     __shared__ __align__(1024) unsigned char lds[kBufs * kStageBytes];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: branches on it are scalar
     const int ntiles = a.tiles_k * a.tiles_l;
     const int tile = xcd_spread(blockIdx.x, ntiles);
     const int split = blockIdx.y;
-    const int k0 = (tile % a.tiles_k) * kTileK, l0 = (tile / a.tiles_k) * kTileL;
+    const int k0 = (tile % a.tiles_k) * C::kTileK, l0 = (tile / a.tiles_k) * C::kTileL;
     const int b_begin = split * a.b_per_split;
     const int b_end = b_begin + a.b_per_split < a.B ? b_begin + a.b_per_split : a.B;
     const int nst = (a.T + kStageT - 1) / kStageT;
     const int nstages = (b_end - b_begin) * nst;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
 
-    // ---- loading: the 48 KiB of a stage are 48 loads of 1 KiB; wave w issues loads 6w .. 6w+5.
-    // Loads 0..31 are rows 2i, 2i+1 of x (32 chunks each), loads 32..47 rows 4j .. 4j+3 of g (16 chunks).
-    // Per load and lane: the row and the chunk of memory that belongs at this lane's LDS position.
+    // ---- loading: a stage is kLoads loads of 1 KiB; wave w issues loads w*kLoadsPerWave .. +kLoadsPerWave-1.
+    // The first kXLoads are rows of x, the rest rows of g.  Per load and lane: the row and the chunk of
+    // memory that belongs at this lane's LDS position.
     uint32_t voff[kLoadsPerWave];        // byte offset from the stage's first element of x (or g)
     int lrow[kLoadsPerWave];             // row within the stage
     bool lcol_ok[kLoadsPerWave];         // the chunk's columns exist (edge tiles)
 #pragma unroll
     for (int n = 0; n < kLoadsPerWave; ++n) {
         const int i = wave * kLoadsPerWave + n;
-        if (i < 32) {
-            const int r = 2 * i + (lane >> 5), c = (lane & 31) ^ ((r & 3) << 2);
+        if (i < C::kXLoads) {
+            const int r = kXRowsPerLoad * i + lane / kXChunks, c = (lane % kXChunks) ^ ((r & 3) << 2);
             lrow[n] = r;
             lcol_ok[n] = k0 + c * 8 < a.K;
             voff[n] = (uint32_t)(((int64_t)r * a.K + c * 8) * 2);
         } else {
-            const int r = 4 * (i - 32) + (lane >> 4), c = (lane & 15) ^ ((r & 3) << 2);
+            const int r = kGRowsPerLoad * (i - C::kXLoads) + lane / kGChunks, c = (lane % kGChunks) ^ ((r & 3) << 2);
             lrow[n] = r;
             lcol_ok[n] = l0 + c * 8 < a.L;
             voff[n] = (uint32_t)(((int64_t)r * a.L + c * 8) * 2);
         }
     }
     // A workgroup whose tile lies inside the matrix, on examples that are whole stages long, never has
-    // a lane without data: it issues exactly six loads per wave and stage and may count on that when it
-    // waits.  Any other workgroup masks lanes, zero-fills their chunks and waits for everything.
-    const bool regular = a.T % kStageT == 0 && k0 + kTileK <= a.K && l0 + kTileL <= a.L;
+    // a lane without data: it issues the same number of loads per wave at every stage and may count on
+    // that when it waits.  Any other workgroup masks lanes, zero-fills their chunks and waits for all.
+    const bool regular = a.T % kStageT == 0 && k0 + C::kTileK <= a.K && l0 + C::kTileL <= a.L;
     int fb = b_begin, fs = 0;                                  // the next stage to fetch: example, stage in it
     auto fetch = [&](int buf) {
         const int64_t row0 = (int64_t)fb * a.T + fs * kStageT;
@@ -118,14 +136,15 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
         if (regular) {
 #pragma unroll
             for (int n = 0; n < kLoadsPerWave; ++n)
-                load_to_lds(dst + n * 1024, voff[n], wave * kLoadsPerWave + n < 32 ? (const void *)xs : (const void *)gs);
+                load_to_lds(dst + n * 1024, voff[n],
+                            wave * kLoadsPerWave + n < C::kXLoads ? (const void *)xs : (const void *)gs);
         } else {
             const int rows_left = a.T - fs * kStageT;
 #pragma unroll
             for (int n = 0; n < kLoadsPerWave; ++n) {
                 if (lcol_ok[n] && lrow[n] < rows_left)
                     load_to_lds(dst + n * 1024, voff[n],
-                                wave * kLoadsPerWave + n < 32 ? (const void *)xs : (const void *)gs);
+                                wave * kLoadsPerWave + n < C::kXLoads ? (const void *)xs : (const void *)gs);
                 else
                     *reinterpret_cast<u32x4_t *>(lds + buf * kStageBytes + (wave * kLoadsPerWave + n) * 1024 +
                                                  lane * 16) = u32x4_t{0u, 0u, 0u, 0u};
@@ -137,25 +156,28 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
         }
     };
 
-    // ---- multiplying: wave (wm, wn) owns outputs k0 + wm*64 .. +64, l0 + wn*64 .. +64.
+    // ---- multiplying: wave (wm, wn) owns outputs k0 + wm*MI*32 .. , l0 + wn*NI*32 .. .
     // For a transposing read, lane s of a 16-lane group reads row s/4 of the block, columns 4*(s%4) .. +3;
     // group g of the wave takes columns (g%2)*16 .. +15 of the 32 and positions (g/2)*8 .. +7 of the 16.
-    const int wm = wave & 3, wn = wave >> 2;
+    const int wm = wave % WM, wn = wave / WM;
     const int s16 = lane & 15, grp = lane >> 4;
     const int rr = (grp >> 1) * 8 + (s16 >> 2);                // row within the 16 positions (first of two reads)
-    uint32_t a_addr[2], b_addr[2];
+    uint32_t a_addr[MI], b_addr[NI];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int qa = wm * 8 + i * 4 + (grp & 1) * 2 + ((s16 & 3) >> 1);
-        const int qb = wn * 8 + i * 4 + (grp & 1) * 2 + ((s16 & 3) >> 1);
-        a_addr[i] = rr * kXRow + ((qa ^ ((s16 >> 2) << 2)) * 16) + (s16 & 1) * 8;
-        b_addr[i] = kXBytes + rr * kGRow + ((qb ^ ((s16 >> 2) << 2)) * 16) + (s16 & 1) * 8;
+    for (int i = 0; i < MI; ++i) {
+        const int q = (wm * MI + i) * 4 + (grp & 1) * 2 + ((s16 & 3) >> 1);
+        a_addr[i] = rr * kXRow + ((q ^ ((s16 >> 2) << 2)) * 16) + (s16 & 1) * 8;
     }
-    f32x16_t acc[2][2], tot[2][2];
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int i = 0; i < NI; ++i) {
+        const int q = (wn * NI + i) * 4 + (grp & 1) * 2 + ((s16 & 3) >> 1);
+        b_addr[i] = kXBytes + rr * kGRow + ((q ^ ((s16 >> 2) << 2)) * 16) + (s16 & 1) * 8;
+    }
+    f32x16_t acc[MI][NI], tot[MI][NI];
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 acc[mi][ni][i] = 0.f;
@@ -164,30 +186,28 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
     typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
     typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
     auto multiply = [&](int buf) {
-        // one address per operand row block and stage; everything else is an immediate offset
         const lds_byte_t *base = (const lds_byte_t *)lds + buf * kStageBytes;
-        const lds_byte_t *pa[2] = {base + a_addr[0], base + a_addr[1]};
-        const lds_byte_t *pb[2] = {base + b_addr[0], base + b_addr[1]};
 #pragma unroll
         for (int kk = 0; kk < kStageT / 16; ++kk) {
-            bf16x8_t fa[2], fb2[2];
+            bf16x8_t fa[MI], fb2[NI];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const s16x4_t a_lo =
-                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(pa[i] + kk * 16 * kXRow));
-                const s16x4_t a_hi =
-                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(pa[i] + kk * 16 * kXRow + 4 * kXRow));
-                const s16x4_t b_lo =
-                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(pb[i] + kk * 16 * kGRow));
-                const s16x4_t b_hi =
-                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(pb[i] + kk * 16 * kGRow + 4 * kGRow));
-                fa[i] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(a_lo, a_hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                fb2[i] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(b_lo, b_hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            for (int i = 0; i < MI; ++i) {
+                const lds_byte_t *p = base + a_addr[i] + kk * 16 * kXRow;
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p);
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p + 4 * kXRow));
+                fa[i] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             }
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
+            for (int i = 0; i < NI; ++i) {
+                const lds_byte_t *p = base + b_addr[i] + kk * 16 * kGRow;
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p);
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p + 4 * kGRow));
+                fb2[i] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
 #pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb2[ni], acc[mi][ni], 0, 0, 0);
         }
     };
@@ -195,12 +215,12 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
     auto boundary = [&]() {
         if (++cs < nst) return;
         cs = 0;
-        // example boundary: step 2 on this wave's 64 x 64 part, then fold it into the total (step 3)
+        // example boundary: step 2 on this wave's part, then fold it into the total (step 3)
         float ssq = 0.f;
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
+            for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const float v = acc[mi][ni][i];
@@ -233,13 +253,13 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
     float *out = a.out + (a.nsplit > 1 ? (int64_t)split * a.K * a.L : 0);
     double bsq = 0.0;
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-            const int l = l0 + wn * 64 + ni * 32 + (lane & 31);
+        for (int ni = 0; ni < NI; ++ni) {
+            const int l = l0 + (wn * NI + ni) * 32 + (lane & 31);
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int k = k0 + wm * 64 + mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+                const int k = k0 + (wm * MI + mi) * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
                 if (k < a.K && l < a.L) {
                     float *p = out + (int64_t)k * a.L + l;
                     float v = tot[mi][ni][i];
@@ -253,6 +273,11 @@ __global__ __launch_bounds__(kThreads) void linear_pegn_kernel(LinArgs a)
         bsq = wave_sum_f64(bsq);
         if (lane == 0) a.tile_big[tile * kWaves + wave] = bsq;
     }
+}
+
+__global__ __launch_bounds__(Cfg::kThreads) void linear_pegn_kernel(LinArgs a)
+{
+    linear_pegn_body<Cfg, LIN_CFG>(a);
 }
 
 // Any shape, any alignment, fp32 or bf16: one thread per output (k,l), fp32 FMA over t, no MFMA.
@@ -342,8 +367,8 @@ LinPlan make_lin_plan(int B, int T, int K, int L, int dt, bool aligned)
     LinPlan p{};
     p.mfma = dt == LNPEGN_BF16 && K % 8 == 0 && L % 8 == 0 && aligned;
     if (p.mfma) {
-        p.tiles_k = (K + kTileK - 1) / kTileK;
-        p.tiles_l = (L + kTileL - 1) / kTileL;
+        p.tiles_k = (K + Cfg::kTileK - 1) / Cfg::kTileK;
+        p.tiles_l = (L + Cfg::kTileL - 1) / Cfg::kTileL;
         const int ntiles = p.tiles_k * p.tiles_l;
         // enough workgroups for 256 CUs: split the examples when the output has few tiles
         int want = (256 + ntiles - 1) / ntiles;
@@ -351,8 +376,8 @@ LinPlan make_lin_plan(int B, int T, int K, int L, int dt, bool aligned)
         if (want > kMaxSplit) want = kMaxSplit;
         p.b_per_split = (B + want - 1) / want;
         p.nsplit = (B + p.b_per_split - 1) / p.b_per_split;
-        p.nparts = ntiles * kWaves;
-        p.nbig = p.nsplit == 1 ? (int64_t)ntiles * kWaves : ((int64_t)K * L + 255) / 256;
+        p.nparts = ntiles * Cfg::kWaves;
+        p.nbig = p.nsplit == 1 ? (int64_t)ntiles * Cfg::kWaves : ((int64_t)K * L + 255) / 256;
     } else {
         p.tiles_k = (K + 15) / 16;
         p.tiles_l = (L + 15) / 16;
@@ -414,7 +439,7 @@ int linear_pegn(const void *x, const void *g, float *w, float *s, float *big_sq,
         a.B = B; a.T = T; a.K = K; a.L = L;
         a.tiles_k = p.tiles_k; a.tiles_l = p.tiles_l; a.nsplit = p.nsplit; a.b_per_split = p.b_per_split;
         a.accumulate = accumulate;
-        linear_pegn_kernel<<<dim3(p.tiles_k * p.tiles_l, p.nsplit), dim3(kThreads), 0, st>>>(a);
+        linear_pegn_kernel<<<dim3(p.tiles_k * p.tiles_l, p.nsplit), dim3(Cfg::kThreads), 0, st>>>(a);
         if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
         if (p.nsplit > 1) {
             const int64_t n = (int64_t)K * L;
