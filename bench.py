@@ -117,6 +117,58 @@ def build_layers(cfg, n_layers, stats_mode, log):
     return layers, shared, host_inputs
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def linear_leg(shape_name, steps, warmup, log):
+    """Linear-layer simultaneous per-example norms (Algorithm 1) on one layer: whole-call time over
+    `steps` calls with HIP events on the launch stream, against the dense bf16 MFMA peak; the library's
+    plain weight-gradient GEMM (no per-example norms) on the same operands is timed beside it."""
+    import torch
+    from paper_2411_00999_amd import binding, workloads
+    B, T, K, L = workloads.LINEAR_SHAPES[shape_name]
+    torch.manual_seed(workloads.BASE_SEED % (2 ** 31))
+    x = torch.randn((B, T, K), device="cuda").to(torch.bfloat16)
+    g = (torch.randn((B, T, L), device="cuda") * 1e-3).to(torch.bfloat16)
+    lib = binding.load()
+    ws = torch.empty(max(256, lib.linear_pegn_workspace_bytes(B, T, K, L, binding.BF16)), dtype=torch.uint8,
+                     device="cuda")
+    w = torch.empty((K, L), dtype=torch.float32, device="cuda")
+    s = torch.empty(B, dtype=torch.float32, device="cuda")
+    big = torch.empty(1, dtype=torch.float32, device="cuda")
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    ms = timed(lambda: binding.linear_pegn(x, g, w=w, s=s, big_sq=big, workspace=ws))
+    x2, g2 = x.reshape(-1, K), g.reshape(-1, L)
+    ms_gemm = timed(lambda: torch.mm(x2.t(), g2))
+    flops = 2.0 * B * T * K * L
+    tf = flops / ms / 1e9
+    est = binding.gns_estimate(s, big, float(B)).cpu().numpy().astype(float)
+    log(f"linear_pegn {shape_name}: {ms:.3f} ms = {tf:.0f} TFLOP/s; plain bf16 GEMM {flops / ms_gemm / 1e9:.0f} TFLOP/s")
+    return {
+        "workload": f"{shape_name}: x [B={B},T={T},K={K}] g [B,T,L={L}] bf16 -> w' [K,L] fp32, s [B], ||w'||^2",
+        "ms_per_call": round(ms, 4),
+        "roofline": {"kernel": "linear_pegn_kernel + linear_final_kernel (whole call)", "bound": "mfma",
+                     "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "algorithmic_flops_per_call": flops},
+        "library_plain_gemm": {"what": "torch.mm(x^T, g) in bf16: the weight gradient alone, no per-example norms",
+                               "ms_per_call": round(ms_gemm, 4), "TFLOPs": round(flops / ms_gemm / 1e9, 1)},
+        "B_simple_this_layer": est[4],
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -132,6 +184,10 @@ def main():
                     help="profiling aid: skip the plain ln_bwd, the other reduction mode and the probe, so "
                          "that a kernel trace of this run holds fused dispatches only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-linear", action="store_true", help="skip the linear-layer per-example-norm leg")
+    ap.add_argument("--linear-only", action="store_true",
+                    help="run only the linear-layer leg (for profiling that kernel) and print its object")
+    ap.add_argument("--linear-shape", default="gpt1p3b_up", help="a key of workloads.LINEAR_SHAPES")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
 
@@ -139,6 +195,16 @@ def main():
         print("bench.py: this build runs on ONE GPU (the path shards along the batch dimension; see "
               "DESIGN.md); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
+
+    def log0(msg):
+        if not args.quiet:
+            print(msg, file=sys.stderr, flush=True)
+
+    if args.linear_only:
+        if args.gpus != 1:
+            sys.exit("this build runs on one GPU only: use --gpus 1")
+        print(json.dumps(linear_leg(args.linear_shape, args.steps, args.warmup, log0)), flush=True)
+        return
 
     def log(msg):
         if not args.quiet:
@@ -342,6 +408,13 @@ def main():
         parity = {"layer0_dgamma_l2_rel": err_dg, "layer0_s_gamma_max_rel": err_sg,
                   "ok": bool(err_dg < 1e-5 and err_sg < 1e-5)}
 
+    linear = None
+    if not (args.no_linear or args.only_fused):
+        layers.clear()
+        sh.clear()
+        torch.cuda.empty_cache()
+        linear = linear_leg(args.linear_shape, 20, 3, log)
+
     out = {
         "metric": "fused LN bwd+per-example norms GB/s, % HBM peak, overhead vs plain ln_bwd",
         "value": round(bytes_per_step / t_fused / 1e9, 2),
@@ -380,6 +453,7 @@ def main():
         },
         "cpu_baseline": cpu_baseline,
         "parity_spot_check": parity,
+        "linear_pegn": linear,
     }
     def clean(o):      # NaN (skipped legs) -> null, so the line stays valid JSON
         if isinstance(o, dict):

@@ -36,3 +36,22 @@ def linear_pegn(x, g, want_pe: bool = False) -> dict:
         if want_pe:
             pe[b] = w_b
     return dict(w=w, s=s, pe=pe)
+
+
+def linear_pegn_entries(x, g, ks, ls) -> np.ndarray:
+    """Selected entries of step 3, one by one: w'[k,l] = sum_b sum_t x[b,t,k] * g[b,t,l] for each pair
+    (ks[i], ls[i]).  For shapes whose full [K,L] result is out of the oracle's reach."""
+    x = np.asarray(x)
+    g = np.asarray(g)
+    out = np.empty(len(ks))
+    for i, (k, l) in enumerate(zip(ks, ls)):
+        out[i] = np.sum(x[:, :, k].astype(np.float64) * g[:, :, l].astype(np.float64))
+    return out
+
+
+def gram_sq_norm(x_b, g_b) -> float:
+    """Step 2 for ONE example without forming w_b: the three-dimensional form of Section 2.2,
+    n_b^2 = <X_b X_b^T, G_b G_b^T>_F  (X_b [T,K], G_b [T,L]; O(T^2) memory)."""
+    x_b = np.asarray(x_b, dtype=np.float64)
+    g_b = np.asarray(g_b, dtype=np.float64)
+    return float(np.sum((x_b @ x_b.T) * (g_b @ g_b.T)))

@@ -57,6 +57,16 @@ def test_gram_form(o=lin):
         assert r["s"][b] == pytest.approx(np.sum((x[b] @ x[b].T) * (g[b] @ g[b].T)), rel=1e-12)
 
 
+def test_sampled_entries_and_gram_form_agree_with_the_full_definition(o=lin):
+    """The two helpers used where the full result is out of reach are pinned to the definition here."""
+    x, g = _rand(3, 9, 6, 5, seed=11)
+    r = o.linear_pegn(x, g)
+    ks, ls = [0, 5, 2, 3], [4, 0, 2, 1]
+    np.testing.assert_allclose(o.linear_pegn_entries(x, g, ks, ls), r["w"][ks, ls], rtol=1e-12, atol=1e-13)
+    for b in range(3):
+        assert o.gram_sq_norm(x[b], g[b]) == pytest.approx(r["s"][b], rel=1e-12)
+
+
 def test_weight_gradient_is_the_flattened_contraction(o=lin):
     x, g = _rand(3, 5, 4, 6, seed=4)
     r = o.linear_pegn(x, g)

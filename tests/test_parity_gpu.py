@@ -615,6 +615,36 @@ def test_linear_pegn_special_cases_and_estimate():
     _check_gns(est, oracle.gns_estimate(ref["s"], [np.sum(ref["w"] ** 2)], float(B)), B)
 
 
+@pytest.mark.parametrize("name", ["gpt111m_qkv", "gpt1p3b_up"])
+def test_linear_pegn_full_size_sampled(name):
+    """Full-size layers in the configuration the benchmark times.  The full [B,K,L] definition is out
+    of the oracle's reach here, so: sampled entries of w' one by one, s[b] of two examples by the Gram
+    form of Section 2.2 (pinned to the definition on the CPU), and big_sq against the w' it came with."""
+    import torch
+    from oracle import linear_pegn_oracle as lin
+    from paper_2411_00999_amd import binding
+    B, T, K, L = workloads.LINEAR_SHAPES[name]
+    torch.manual_seed(workloads.BASE_SEED % (2 ** 31))
+    # drawn on the device (the host generator would need minutes at this size), read back for the oracle
+    xd = torch.randn((B, T, K), device="cuda").to(torch.bfloat16)
+    gd = (torch.randn((B, T, L), device="cuda") * 1e-3 + torch.randn((1, T, L), device="cuda") * 1e-3).to(torch.bfloat16)
+    w, s, big = binding.linear_pegn(xd, gd)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(workloads.BASE_SEED + 5)
+    ks = np.concatenate([rng.integers(0, K, 60), [0, K - 1, 255, 256]])
+    ls = np.concatenate([rng.integers(0, L, 60), [0, L - 1, 127, 128]])
+    x_cols = xd[:, :, torch.from_numpy(ks).cuda()].float().cpu().numpy().astype(np.float64)     # [B,T,n]
+    g_cols = gd[:, :, torch.from_numpy(ls).cuda()].float().cpu().numpy().astype(np.float64)
+    want = lin.linear_pegn_entries(x_cols, g_cols, range(len(ks)), range(len(ks)))
+    got = w[torch.from_numpy(ks).cuda(), torch.from_numpy(ls).cuda()].cpu().numpy().astype(np.float64)
+    rms = float(torch.sqrt(torch.mean(w.double() ** 2)))
+    assert np.all(np.abs(got - want) <= pu.TOL_SUMS * (np.abs(want) + rms)), np.max(np.abs(got - want)) / rms
+    for b in (0, B - 1):
+        ref = lin.gram_sq_norm(xd[b].float().cpu().numpy(), gd[b].float().cpu().numpy())
+        assert float(s[b]) == pytest.approx(ref, rel=pu.TOL_SUMS), b
+    assert float(big[0]) == pytest.approx(float(torch.sum(w.double() ** 2)), rel=pu.TOL_SUMS)
+
+
 def test_linear_pegn_argument_errors():
     import torch
     from paper_2411_00999_amd import binding
