@@ -33,6 +33,10 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 // c ^ 4*(r & 3); a direct-to-LDS load writes a wave's 64 chunks contiguously, so the swizzle is applied
 // by choosing which chunk of memory each lane fetches.
 constexpr int kStageT = 64, kBufs = 3, kMaxSplit = 64;
+#define LIN_STR2(x) #x
+#define LIN_STR(x) LIN_STR2(x)
+#define LIN_XROW 512   // bytes per LDS row of x and of g, as literals for the assembly below
+#define LIN_GROW 256
 
 template <int WM, int WN, int MI, int NI>
 struct LinCfg {
@@ -183,34 +187,63 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
                 acc[mi][ni][i] = 0.f;
                 tot[mi][ni][i] = 0.f;
             }
-    typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
-    typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
-    auto multiply = [&](int buf) {
-        const lds_byte_t *base = (const lds_byte_t *)lds + buf * kStageBytes;
-#pragma unroll
-        for (int kk = 0; kk < kStageT / 16; ++kk) {
-            bf16x8_t fa[MI], fb2[NI];
-#pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                const lds_byte_t *p = base + a_addr[i] + kk * 16 * kXRow;
-                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p);
-                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p + 4 * kXRow));
-                fa[i] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            }
-#pragma unroll
-            for (int i = 0; i < NI; ++i) {
-                const lds_byte_t *p = base + b_addr[i] + kk * 16 * kGRow;
-                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p);
-                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p + 4 * kGRow));
-                fb2[i] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            }
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb2[ni], acc[mi][ni], 0, 0, 0);
-        }
+    // The transposing reads are written in assembly: the compiler's own selection of that instruction
+    // takes no immediate offset (two VALU additions per read), and here the reads of the next 16
+    // positions are issued, with immediate offsets off four per-stage addresses, before the MFMAs of the
+    // current 16 start.  A block first waits for the reads issued by the block before it; the operands
+    // those delivered are passed through it ("+v") so that no MFMA using them can be moved above the wait.
+    static_assert(MI == 2 && NI == 2, "the read blocks below are written for 2 x 2 MFMA tiles per wave");
+    static_assert(kXRow == LIN_XROW && kGRow == LIN_GROW, "row pitches used in the assembly");
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+    struct Frags {
+        u32x2_t a0l, a0h, a1l, a1h, b0l, b0h, b1l, b1h;
     };
+#define LIN_READS(KK)                                                                                          \
+    "ds_read_b64_tr_b16 %0, %8 offset:" LIN_STR((KK) * 16 * LIN_XROW) "\n\t"                                    \
+    "ds_read_b64_tr_b16 %1, %8 offset:" LIN_STR((KK) * 16 * LIN_XROW + 4 * LIN_XROW) "\n\t"                      \
+    "ds_read_b64_tr_b16 %2, %9 offset:" LIN_STR((KK) * 16 * LIN_XROW) "\n\t"                                    \
+    "ds_read_b64_tr_b16 %3, %9 offset:" LIN_STR((KK) * 16 * LIN_XROW + 4 * LIN_XROW) "\n\t"                      \
+    "ds_read_b64_tr_b16 %4, %10 offset:" LIN_STR((KK) * 16 * LIN_GROW) "\n\t"                                   \
+    "ds_read_b64_tr_b16 %5, %10 offset:" LIN_STR((KK) * 16 * LIN_GROW + 4 * LIN_GROW) "\n\t"                     \
+    "ds_read_b64_tr_b16 %6, %11 offset:" LIN_STR((KK) * 16 * LIN_GROW) "\n\t"                                   \
+    "ds_read_b64_tr_b16 %7, %11 offset:" LIN_STR((KK) * 16 * LIN_GROW + 4 * LIN_GROW)
+#define LIN_OUTS(F)                                                                                            \
+    "=&v"(F.a0l), "=&v"(F.a0h), "=&v"(F.a1l), "=&v"(F.a1h), "=&v"(F.b0l), "=&v"(F.b0h), "=&v"(F.b1l), "=&v"(F.b1h)
+#define LIN_KEEP(F)                                                                                            \
+    "+v"(F.a0l), "+v"(F.a0h), "+v"(F.a1l), "+v"(F.a1h), "+v"(F.b0l), "+v"(F.b0h), "+v"(F.b1l), "+v"(F.b1h)
+    auto mfmas = [&](const Frags &f) {
+        const bf16x8_t fa[2] = {
+            __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(f.a0l, f.a0h, 0, 1, 2, 3)),
+            __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(f.a1l, f.a1h, 0, 1, 2, 3))};
+        const bf16x8_t fb2[2] = {
+            __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(f.b0l, f.b0h, 0, 1, 2, 3)),
+            __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(f.b1l, f.b1h, 0, 1, 2, 3))};
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb2[ni], acc[mi][ni], 0, 0, 0);
+    };
+    auto multiply = [&](int buf) {
+        const uint32_t base = lds_base + buf * kStageBytes;
+        const uint32_t pa0 = base + a_addr[0], pa1 = base + a_addr[1], pb0 = base + b_addr[0], pb1 = base + b_addr[1];
+        Frags f0, f1;
+        asm volatile(LIN_READS(0) : LIN_OUTS(f0) : "v"(pa0), "v"(pa1), "v"(pb0), "v"(pb1) : "memory");
+        asm volatile(LIN_READS(1) : LIN_OUTS(f1) : "v"(pa0), "v"(pa1), "v"(pb0), "v"(pb1) : "memory");
+        asm volatile("s_waitcnt lgkmcnt(8)" : LIN_KEEP(f0) : : "memory");
+        mfmas(f0);
+        asm volatile(LIN_READS(2) : LIN_OUTS(f0) : "v"(pa0), "v"(pa1), "v"(pb0), "v"(pb1) : "memory");
+        asm volatile("s_waitcnt lgkmcnt(8)" : LIN_KEEP(f1) : : "memory");
+        mfmas(f1);
+        asm volatile(LIN_READS(3) : LIN_OUTS(f1) : "v"(pa0), "v"(pa1), "v"(pb0), "v"(pb1) : "memory");
+        asm volatile("s_waitcnt lgkmcnt(8)" : LIN_KEEP(f0) : : "memory");
+        mfmas(f0);
+        asm volatile("s_waitcnt lgkmcnt(0)" : LIN_KEEP(f1) : : "memory");
+        mfmas(f1);
+    };
+#undef LIN_READS
+#undef LIN_OUTS
+#undef LIN_KEEP
     int cb = b_begin, cs = 0;                                  // the stage being multiplied
     auto boundary = [&]() {
         if (++cs < nst) return;
