@@ -224,12 +224,13 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
             for (int ni = 0; ni < 2; ++ni)
                 acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb2[ni], acc[mi][ni], 0, 0, 0);
     };
-    auto multiply = [&](int buf) {
+    auto multiply = [&](int buf, bool refill, int refill_buf) {
         const uint32_t base = lds_base + buf * kStageBytes;
         const uint32_t pa0 = base + a_addr[0], pa1 = base + a_addr[1], pb0 = base + b_addr[0], pb1 = base + b_addr[1];
         Frags f0, f1;
         asm volatile(LIN_READS(0) : LIN_OUTS(f0) : "v"(pa0), "v"(pa1), "v"(pb0), "v"(pb1) : "memory");
         asm volatile(LIN_READS(1) : LIN_OUTS(f1) : "v"(pa0), "v"(pa1), "v"(pb0), "v"(pb1) : "memory");
+        if (refill) fetch(refill_buf);                         // stage st+2 goes out while the first reads land
         asm volatile("s_waitcnt lgkmcnt(8)" : LIN_KEEP(f0) : : "memory");
         mfmas(f0);
         asm volatile(LIN_READS(2) : LIN_OUTS(f0) : "v"(pa0), "v"(pa1), "v"(pb0), "v"(pb1) : "memory");
@@ -277,8 +278,7 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
         else
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (st + 2 < nstages) fetch((st + 2) % kBufs);
-        multiply(st % kBufs);
+        multiply(st % kBufs, st + 2 < nstages, (st + 2) % kBufs);
         boundary();
     }
 
