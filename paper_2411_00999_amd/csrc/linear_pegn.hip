@@ -132,10 +132,13 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
     // a lane without data: it issues the same number of loads per wave at every stage and may count on
     // that when it waits.  Any other workgroup masks lanes, zero-fills their chunks and waits for all.
     const bool regular = a.T % kStageT == 0 && k0 + C::kTileK <= a.K && l0 + C::kTileL <= a.L;
-    int fb = b_begin, fs = 0;                                  // the next stage to fetch: example, stage in it
+    // The stage to fetch next is tracked by two running pointers: rows are contiguous in memory, within
+    // an example and from one example to the next, so a stage is 64 rows further unless it is the short
+    // last stage of an example.
+    int fs = 0;                                                // stage within the example
+    const int last_rows = a.T - (nst - 1) * kStageT;           // rows of an example's last stage (64 if whole)
+    const uint16_t *xs = a.x + (int64_t)b_begin * a.T * a.K + k0, *gs = a.g + (int64_t)b_begin * a.T * a.L + l0;
     auto fetch = [&](int buf) {
-        const int64_t row0 = (int64_t)fb * a.T + fs * kStageT;
-        const uint16_t *xs = a.x + row0 * a.K + k0, *gs = a.g + row0 * a.L + l0;
         const uint32_t dst = lds_base + buf * kStageBytes + wave * kLoadsPerWave * 1024;
         if (regular) {
 #pragma unroll
@@ -143,7 +146,7 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
                 load_to_lds(dst + n * 1024, voff[n],
                             wave * kLoadsPerWave + n < C::kXLoads ? (const void *)xs : (const void *)gs);
         } else {
-            const int rows_left = a.T - fs * kStageT;
+            const int rows_left = fs == nst - 1 ? last_rows : kStageT;
 #pragma unroll
             for (int n = 0; n < kLoadsPerWave; ++n) {
                 if (lcol_ok[n] && lrow[n] < rows_left)
@@ -154,10 +157,10 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
                                                  lane * 16) = u32x4_t{0u, 0u, 0u, 0u};
             }
         }
-        if (++fs == nst) {
-            fs = 0;
-            ++fb;
-        }
+        const int rows = fs == nst - 1 ? last_rows : kStageT;
+        xs += (int64_t)rows * a.K;
+        gs += (int64_t)rows * a.L;
+        fs = fs == nst - 1 ? 0 : fs + 1;
     };
 
     // ---- multiplying: wave (wm, wn) owns outputs k0 + wm*MI*32 .. , l0 + wn*NI*32 .. .
@@ -230,10 +233,10 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
         Frags f0, f1;
         asm volatile(LIN_READS(0) : LIN_OUTS(f0) : "v"(pa0), "v"(pa1), "v"(pb0), "v"(pb1) : "memory");
         asm volatile(LIN_READS(1) : LIN_OUTS(f1) : "v"(pa0), "v"(pa1), "v"(pb0), "v"(pb1) : "memory");
-        if (refill) fetch(refill_buf);                         // stage st+2 goes out while the first reads land
         asm volatile("s_waitcnt lgkmcnt(8)" : LIN_KEEP(f0) : : "memory");
         mfmas(f0);
         asm volatile(LIN_READS(2) : LIN_OUTS(f0) : "v"(pa0), "v"(pa1), "v"(pb0), "v"(pb1) : "memory");
+        if (refill) fetch(refill_buf);                         // stage st+2 goes out in the shadow of those MFMAs
         asm volatile("s_waitcnt lgkmcnt(8)" : LIN_KEEP(f1) : : "memory");
         mfmas(f1);
         asm volatile(LIN_READS(3) : LIN_OUTS(f1) : "v"(pa0), "v"(pa1), "v"(pb0), "v"(pb1) : "memory");
@@ -272,13 +275,16 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
     // landed and that stage st-1 has been read by all, so its buffer can take stage st+2.
     if (nstages > 0) fetch(0);
     if (nstages > 1) fetch(1);
+    int cur = 0, nxt2 = 2;                                     // buffers of stage st and of stage st+2
     for (int st = 0; st < nstages; ++st) {
         if (regular && st + 1 < nstages)
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerWave) : "memory");
         else
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        multiply(st % kBufs, st + 2 < nstages, (st + 2) % kBufs);
+        multiply(cur, st + 2 < nstages, nxt2);
+        cur = cur == kBufs - 1 ? 0 : cur + 1;
+        nxt2 = nxt2 == kBufs - 1 ? 0 : nxt2 + 1;
         boundary();
     }
 
