@@ -234,6 +234,24 @@ int linear_pegn(const void *x, const void *g, float *w, float *s, float *big_sq,
                 lnpegn_dtype dt, void *workspace, size_t workspace_bytes, unsigned flags, void *stream);
 
 /*
+ * Embedding-layer simultaneous per-example gradient norms (Appendix B, embedding-layer algorithm,
+ * steps 1-4; step 5's mean and B^2 are gns_estimate's pe_scale).
+ *   ids [B,T] token ids (device; int32, or int64 when ids_are_int64 != 0); an id outside [0,V) is
+ *     skipped: its row of g contributes to nothing.
+ *   g [B,T,D] gradients w.r.t. the embedding outputs (device, row-major contiguous, bf16 or fp32).
+ *   w [V,D] fp32 (device): sum_b w_b, w_b[v,:] = sum_{t: ids[b,t]=v} g[b,t,:]; every row overwritten
+ *     (rows of absent ids with zeros), or added to with LNPEGN_ACCUMULATE (the only flag accepted).
+ *   s [B] fp32: raw ||w_b||^2.   big_sq [1] fp32 or NULL: ||w||^2 of the (accumulated) gradient.
+ * Neither the one-hot tensor nor [B,V,D] is formed; each row of g is read once; no atomics (bitwise
+ * reproducible).  workspace: embedding_pegn_workspace_bytes(...) bytes (0 if the shape is invalid or
+ * no device is present: the sort's scratch is sized for the current device), 256-byte aligned,
+ * caller-owned, contents scratch.  B*T < 2^31, V < 2^30.  Enqueued on stream, never synchronises.
+ */
+size_t embedding_pegn_workspace_bytes(int B, int T, int D, int V);
+int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, float *s, float *big_sq, int B, int T,
+                   int D, int V, lnpegn_dtype dt, void *workspace, size_t workspace_bytes, unsigned flags, void *stream);
+
+/*
  * Benchmarking aid.  Overrides launch-shape heuristics process-wide; it never changes results
  * beyond floating-point summation order.  key 0: target number of row chunks of ln_bwd_pegn
  * (0 = automatic); key 1: the same for ln_bwd; key 2: waves per workgroup of the row kernel

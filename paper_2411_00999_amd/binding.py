@@ -21,7 +21,7 @@ EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "ln_fwd_stats", "ln
            "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred",
            "ln_fwd", "ln_bwd_ex", "rms_fwd", "rms_bwd_ex",
            "gns_ema_update", "gns_offline", "gns_linear_accum_steps",
-           "linear_pegn_workspace_bytes", "linear_pegn")
+           "linear_pegn_workspace_bytes", "linear_pegn", "embedding_pegn_workspace_bytes", "embedding_pegn")
 PER_EXAMPLE, DEFER, ACCUMULATE = 1, 2, 4
 
 _lib = None
@@ -64,6 +64,9 @@ def load() -> ctypes.CDLL:
     lib.linear_pegn_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.linear_pegn_workspace_bytes.restype = sz
     lib.linear_pegn.argtypes = [vp, vp, fp, fp, fp, i, i, i, i, i, vp, sz, ctypes.c_uint, vp]
+    lib.embedding_pegn_workspace_bytes.argtypes = [i, i, i, i]
+    lib.embedding_pegn_workspace_bytes.restype = sz
+    lib.embedding_pegn.argtypes = [vp, i, vp, fp, fp, fp, i, i, i, i, i, vp, sz, ctypes.c_uint, vp]
     lib.rms_fwd.argtypes = [vp, vp, vp, fp, i, i, i, i, i, f, vp]
     lib.rms_bwd_ex.argtypes = [vp, vp, vp, fp, vp, fp, fp, fp, i, i, i, i, i, f, vp, sz, ctypes.c_uint, vp]
     lib.gns_estimate.argtypes = [fp, fp, i, i, f, fp, vp]
@@ -74,7 +77,7 @@ def load() -> ctypes.CDLL:
                  "lnpegn_set_profile_events", "lnpegn_stream_probe", "ln_bwd_deferred",
                  "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred", "ln_fwd", "ln_bwd_ex",
                  "rms_fwd", "rms_bwd_ex", "gns_ema_update", "gns_offline", "gns_linear_accum_steps",
-                 "linear_pegn"):
+                 "linear_pegn", "embedding_pegn"):
         getattr(lib, name).restype = i
     _lib = lib
     return lib
@@ -177,6 +180,34 @@ def linear_pegn(x, g, w=None, accumulate=False, s=None, big_sq=None, workspace=N
                             _ptr(workspace), workspace.numel(), ACCUMULATE if accumulate else 0, _stream(stream))
     if rc:
         raise LnpegnError("linear_pegn", rc)
+    return w, s, big_sq
+
+
+def embedding_pegn(ids, g, V: int, w=None, accumulate=False, s=None, big_sq=None, workspace=None, stream=None):
+    """ids [B,T] int32/int64, g [B,T,D] -> (w [V,D] fp32, s [B] fp32, big_sq [1] fp32)."""
+    torch = _torch()
+    B, T, D = _check3(g)
+    if tuple(ids.shape) != (B, T) or not ids.is_contiguous() or ids.dtype not in (torch.int32, torch.int64):
+        raise ValueError("ids must be a contiguous [B,T] int32 or int64 tensor")
+    f32 = dict(dtype=torch.float32, device=g.device)
+    if w is None:
+        if accumulate:
+            raise ValueError("accumulate needs the buffer to add to")
+        w = torch.empty((V, D), **f32)
+    if w.dtype != torch.float32 or tuple(w.shape) != (V, D) or not w.is_contiguous():
+        raise ValueError("w must be a contiguous [V,D] float32 tensor")
+    s = torch.empty(B, **f32) if s is None else s
+    big_sq = torch.empty(1, **f32) if big_sq is None else big_sq
+    if workspace is None:
+        nbytes = load().embedding_pegn_workspace_bytes(B, T, D, V)
+        if nbytes == 0:
+            raise LnpegnError("embedding_pegn_workspace_bytes", 1)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=g.device)
+    rc = load().embedding_pegn(_ptr(ids), 1 if ids.dtype == torch.int64 else 0, _ptr(g), _ptr(w), _ptr(s), _ptr(big_sq),
+                               B, T, D, V, _dt(g), _ptr(workspace), workspace.numel(),
+                               ACCUMULATE if accumulate else 0, _stream(stream))
+    if rc:
+        raise LnpegnError("embedding_pegn", rc)
     return w, s, big_sq
 
 

@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblnpegn.so")
-SOURCES = [os.path.join(CSRC, "lnpegn.hip"), os.path.join(CSRC, "linear_pegn.hip")]
+SOURCES = [os.path.join(CSRC, f) for f in ("lnpegn.hip", "linear_pegn.hip", "embedding_pegn.hip")]
 HEADERS = [os.path.join(CSRC, h) for h in ("lnpegn_device.h", "lnpegn_rows.h", "lnpegn_finalize.h", "lnpegn_tracker.h")]
 HEADERS.append(os.path.join(os.path.dirname(HERE), "include", "lnpegn.h"))
 

@@ -1,0 +1,291 @@
+// Embedding-layer simultaneous per-example gradient norms (Appendix B, embedding-layer algorithm) for gfx950:
+//   w_b[v,d] = sum_{t: ids[b,t] = v} g[b,t,d]     (steps 1-2; the one-hot tensor and [B,V,D] are never formed)
+//   s[b]     = sum_{v,d} w_b[v,d]^2               (step 3)
+//   w'[v,d]  = sum_b w_b[v,d]                     (step 4)
+// The positions p = b*T + t are sorted by id (stable, so positions ascend inside an id and the rows of one
+// example are adjacent).  One wave then walks an id's rows in that order with the columns spread over its
+// lanes: the running sum is cut at every change of example, where its squared norm is that example's share
+// of step 3, and the pieces add up to the row of w'.  Every row of g is read once; nothing is atomic, so the
+// results are bitwise reproducible.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <cstring>
+#include <rocprim/device/device_radix_sort.hpp>
+
+#include "../../include/lnpegn.h"
+#include "lnpegn_device.h"
+
+namespace lnpegn {
+namespace {
+
+constexpr int kColBlock = 512;      // columns per wave: 8 per lane
+constexpr int kChunk = 8;           // sorted positions whose segment heads one wave looks after
+constexpr int kWavesPerBlock = 4;
+constexpr int kNormBlocks = 1024;   // workgroups of the ||w'||^2 pass in accumulate mode
+
+__global__ __launch_bounds__(256) void emb_prepare_kernel(const void *ids, int ids_i64, uint32_t *keys,
+                                                          uint32_t *vals, float *scratch, int64_t n,
+                                                          int64_t nscratch, int V)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) {
+        const int64_t id = ids_i64 ? static_cast<const int64_t *>(ids)[i] : (int64_t) static_cast<const int32_t *>(ids)[i];
+        keys[i] = (id >= 0 && id < V) ? (uint32_t)id : (uint32_t)V;    // out of range: sorted behind, skipped
+        vals[i] = (uint32_t)i;
+    }
+    for (int64_t j = i; j < nscratch; j += (int64_t)gridDim.x * 256) scratch[j] = 0.f;
+}
+
+__global__ __launch_bounds__(256) void emb_fill_kernel(float *p, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0.f;
+}
+
+// eight columns of one row, added into sub: 16-byte loads when the row allows, element loads otherwise
+__device__ __forceinline__ void add_row(const bf16_t *g, int64_t p, int D, int c0, bool vec, float (&sub)[8])
+{
+    const bf16_t *row = g + p * D + c0;
+    if (vec) {
+        const uint4 r = *reinterpret_cast<const uint4 *>(row);
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            sub[2 * i] += __builtin_bit_cast(float, w[i] << 16);
+            sub[2 * i + 1] += __builtin_bit_cast(float, w[i] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (c0 + i < D) sub[i] += load_elem<bf16_t>(row, i);
+    }
+}
+
+__device__ __forceinline__ void add_row(const float *g, int64_t p, int D, int c0, bool vec, float (&sub)[8])
+{
+    const float *row = g + p * D + c0;
+    if (vec) {
+        const float4 lo = *reinterpret_cast<const float4 *>(row), hi = *reinterpret_cast<const float4 *>(row + 4);
+        sub[0] += lo.x; sub[1] += lo.y; sub[2] += lo.z; sub[3] += lo.w;
+        sub[4] += hi.x; sub[5] += hi.y; sub[6] += hi.z; sub[7] += hi.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (c0 + i < D) sub[i] += row[i];
+    }
+}
+
+// keys/vals: positions sorted by id.  contrib [ncb][n]: share of s[b] found at the first position of every
+// (id, example) run, zero elsewhere.  bigpart [ncb][n]: squared norm of the finished row of w' at the
+// position heading the id's segment, zero elsewhere (not used when accumulating).
+template <typename T>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void emb_segments_kernel(
+    const T *g, const uint32_t *keys, const uint32_t *vals, float *w, float *contrib, float *bigpart, int64_t n,
+    int Tn, int D, int V, int accumulate, int vec_ok)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t i0 = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * kChunk;
+    const int cb = blockIdx.y, c0 = cb * kColBlock + lane * 8;
+    const bool has_cols = c0 < D;
+    const bool vec = vec_ok && c0 + 8 <= D;
+    for (int64_t i = i0; i < i0 + kChunk && i < n; ++i) {
+        const uint32_t v = keys[i];
+        if (v >= (uint32_t)V || (i > 0 && keys[i - 1] == v)) continue;      // not the head of a segment
+        float tot[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) tot[k] = 0.f;
+        int64_t j = i;
+        while (j < n && keys[j] == v) {
+            // one (id, example) run: positions ascend, so it ends where the example number changes
+            const int64_t first = vals[j];
+            const int64_t b = first / Tn;
+            float sub[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) sub[k] = 0.f;
+            int64_t p = first;
+            while (true) {
+                if (has_cols) add_row(g, p, D, c0, vec, sub);
+                ++j;
+                if (j >= n || keys[j] != v) break;
+                p = vals[j];
+                if (p / Tn != b) break;
+            }
+            float sq = 0.f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                sq = fmaf(sub[k], sub[k], sq);
+                tot[k] += sub[k];
+            }
+            sq = wave_sum(sq);
+            if (lane == 0) contrib[(int64_t)cb * n + first] = sq;
+        }
+        float sq = 0.f;
+        if (has_cols) {
+            float *row = w + (int64_t)v * D + c0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (c0 + k < D) {
+                    const float r = accumulate ? row[k] + tot[k] : tot[k];
+                    row[k] = r;
+                    sq = fmaf(r, r, sq);
+                }
+            }
+        }
+        if (!accumulate) {
+            sq = wave_sum(sq);
+            if (lane == 0) bigpart[(int64_t)cb * n + vals[i]] = sq;
+        }
+    }
+}
+
+// partial sums of squares of w (accumulate mode: every row counts, not only those touched)
+__global__ __launch_bounds__(256) void emb_wnorm_kernel(const float *w, int64_t n, double *part)
+{
+    __shared__ double slots[4];
+    double t = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        t += (double)w[i] * (double)w[i];
+    t = block_sum_f64(t, slots);
+    if (threadIdx.x == 0) part[blockIdx.x] = t;
+}
+
+// s[b] = sum over column blocks and positions of example b of contrib; big_sq from its parts.  fp64, fixed order.
+__global__ __launch_bounds__(1024) void emb_final_kernel(const float *contrib, const float *bigpart,
+                                                         const double *wpart, int nwpart, float *s, float *big_sq,
+                                                         int B, int Tn, int ncb, int64_t n)
+{
+    __shared__ double slots[16];
+    const int b = blockIdx.x;
+    double t = 0.0;
+    if (b < B) {
+        for (int c = 0; c < ncb; ++c)
+            for (int i = threadIdx.x; i < Tn; i += 1024) t += (double)contrib[(int64_t)c * n + (int64_t)b * Tn + i];
+        t = block_sum_f64(t, slots);
+        if (threadIdx.x == 0) s[b] = (float)t;
+    } else if (big_sq) {
+        if (wpart) {
+            for (int i = threadIdx.x; i < nwpart; i += 1024) t += wpart[i];
+        } else {
+            for (int64_t i = threadIdx.x; i < (int64_t)ncb * n; i += 1024) t += (double)bigpart[i];
+        }
+        t = block_sum_f64(t, slots);
+        if (threadIdx.x == 0) big_sq[0] = (float)t;
+    }
+}
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+int key_bits(int V)
+{
+    int bits = 1;
+    while (bits < 32 && ((uint64_t)1 << bits) <= (uint64_t)V) ++bits;   // keys run up to V inclusive
+    return bits;
+}
+
+struct EmbPlan {
+    int64_t n;
+    int ncb;
+    size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_contrib, off_bigpart, off_wpart, off_temp;
+    size_t temp_bytes, bytes;
+};
+
+bool emb_shape_ok(int B, int T, int D, int V)
+{
+    return B > 0 && T > 0 && D > 0 && V > 0 && (int64_t)B * T < ((int64_t)1 << 31) && V < (1 << 30);
+}
+
+// The sort's own temporary storage is sized by the library for the current device.
+hipError_t make_emb_plan(int B, int T, int D, int V, EmbPlan &p)
+{
+    p.n = (int64_t)B * T;
+    p.ncb = (D + kColBlock - 1) / kColBlock;
+    size_t temp = 0;
+    const hipError_t e = rocprim::radix_sort_pairs(nullptr, temp, (const uint32_t *)nullptr, (uint32_t *)nullptr,
+                                                   (const uint32_t *)nullptr, (uint32_t *)nullptr, (size_t)p.n, 0,
+                                                   key_bits(V), (hipStream_t)0);
+    if (e != hipSuccess) return e;
+    const size_t arr = align256((size_t)p.n * sizeof(uint32_t)), f = align256((size_t)p.ncb * p.n * sizeof(float));
+    p.off_keys_in = 0;
+    p.off_keys_out = p.off_keys_in + arr;
+    p.off_vals_in = p.off_keys_out + arr;
+    p.off_vals_out = p.off_vals_in + arr;
+    p.off_contrib = p.off_vals_out + arr;
+    p.off_bigpart = p.off_contrib + f;            // directly behind contrib: one fill clears both
+    p.off_wpart = p.off_bigpart + f;
+    p.off_temp = p.off_wpart + align256(kNormBlocks * sizeof(double));
+    p.temp_bytes = temp;
+    p.bytes = p.off_temp + align256(temp);
+    return hipSuccess;
+}
+
+}  // namespace
+}  // namespace lnpegn
+
+using namespace lnpegn;
+
+extern "C" {
+
+size_t embedding_pegn_workspace_bytes(int B, int T, int D, int V)
+{
+    if (!emb_shape_ok(B, T, D, V)) return 0;
+    EmbPlan p;
+    return make_emb_plan(B, T, D, V, p) == hipSuccess ? p.bytes : 0;
+}
+
+int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, float *s, float *big_sq, int B, int T,
+                   int D, int V, lnpegn_dtype dt, void *workspace, size_t workspace_bytes, unsigned flags, void *stream)
+{
+    if (!emb_shape_ok(B, T, D, V) || !ids || !g || !w || !s || !workspace) return LNPEGN_EINVAL;
+    if (flags & ~(unsigned)LNPEGN_ACCUMULATE) return LNPEGN_EINVAL;
+    if (dt != LNPEGN_F32 && dt != LNPEGN_BF16) return LNPEGN_EUNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return LNPEGN_EINVAL;
+    EmbPlan p;
+    if (make_emb_plan(B, T, D, V, p) != hipSuccess) return LNPEGN_EHIP;
+    if (workspace_bytes < p.bytes) return LNPEGN_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int accumulate = (flags & LNPEGN_ACCUMULATE) ? 1 : 0;
+    char *ws = static_cast<char *>(workspace);
+    uint32_t *keys_in = reinterpret_cast<uint32_t *>(ws + p.off_keys_in);
+    uint32_t *keys_out = reinterpret_cast<uint32_t *>(ws + p.off_keys_out);
+    uint32_t *vals_in = reinterpret_cast<uint32_t *>(ws + p.off_vals_in);
+    uint32_t *vals_out = reinterpret_cast<uint32_t *>(ws + p.off_vals_out);
+    float *contrib = reinterpret_cast<float *>(ws + p.off_contrib);
+    float *bigpart = reinterpret_cast<float *>(ws + p.off_bigpart);
+    double *wpart = reinterpret_cast<double *>(ws + p.off_wpart);
+    const int64_t nscratch = (int64_t)((p.off_wpart - p.off_contrib) / sizeof(float));
+    const unsigned nblk = (unsigned)((p.n + 255) / 256);
+    emb_prepare_kernel<<<dim3(nblk), dim3(256), 0, st>>>(ids, ids_are_int64, keys_in, vals_in, contrib, p.n, nscratch, V);
+    if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    size_t temp = p.temp_bytes;
+    if (rocprim::radix_sort_pairs(ws + p.off_temp, temp, keys_in, keys_out, vals_in, vals_out, (size_t)p.n, 0,
+                                  key_bits(V), st) != hipSuccess)
+        return LNPEGN_EHIP;
+    if (!accumulate) {
+        const int64_t nw = (int64_t)V * D;
+        const unsigned fb = (unsigned)(nw / 256 / 8 + 1 < 65536 ? nw / 256 / 8 + 1 : 65536);
+        emb_fill_kernel<<<dim3(fb), dim3(256), 0, st>>>(w, nw);
+        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    }
+    const int esz = dt == LNPEGN_BF16 ? 2 : 4;
+    // 8 columns per lane: 16 bytes of bf16, 32 bytes of fp32; rows must keep that alignment
+    const int vec_ok = ((reinterpret_cast<uintptr_t>(g) & 15u) == 0 && ((int64_t)D * esz) % 16 == 0) ? 1 : 0;
+    const dim3 grid((unsigned)((p.n + kChunk * kWavesPerBlock - 1) / (kChunk * kWavesPerBlock)), (unsigned)p.ncb);
+    if (dt == LNPEGN_BF16)
+        emb_segments_kernel<bf16_t><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(
+            static_cast<const bf16_t *>(g), keys_out, vals_out, w, contrib, bigpart, p.n, T, D, V, accumulate, vec_ok);
+    else
+        emb_segments_kernel<float><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(
+            static_cast<const float *>(g), keys_out, vals_out, w, contrib, bigpart, p.n, T, D, V, accumulate, vec_ok);
+    if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    const bool wnorm = accumulate && big_sq;
+    if (wnorm) {
+        emb_wnorm_kernel<<<dim3(kNormBlocks), dim3(256), 0, st>>>(w, (int64_t)V * D, wpart);
+        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    }
+    emb_final_kernel<<<dim3(B + 1), dim3(1024), 0, st>>>(contrib, bigpart, wnorm ? wpart : nullptr, kNormBlocks, s,
+                                                         big_sq, B, T, p.ncb, p.n);
+    return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+}
+
+}  // extern "C"

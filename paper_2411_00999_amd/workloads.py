@@ -187,3 +187,24 @@ def make_linear_inputs(seed: int, B: int, T: int, K: int, L: int, dtype: str = "
     if dtype == "bf16":
         x, g = round_to_bf16(x), round_to_bf16(g)
     return x, g
+
+
+# ----------------------------------------------------------------------------- embedding layer
+# The token embedding of the paper's GPT models: vocabulary 50257, hidden 768 (Section 4) or 2048
+# (Section 5.2).  Ids follow a Zipf law over a randomly ordered vocabulary, which is what text looks
+# like to this layer: a few ids many times per example, most ids never.
+EMBEDDING_SHAPES = {
+    "gpt111m_wte": (8, 1024, 768, 50257),
+    "gpt1p3b_wte": (16, 2048, 2048, 50257),
+}
+
+
+def make_embedding_inputs(seed: int, B: int, T: int, D: int, V: int, dtype: str = "bf16", zipf_a: float = 1.2):
+    """(ids [B,T] int64 in [0,V), g [B,T,D] float32 (rounded to bf16 values when dtype is "bf16"))."""
+    rng = np.random.default_rng(BASE_SEED + 700_000 + seed)
+    order = rng.permutation(V)
+    ids = order[(rng.zipf(zipf_a, size=(B, T)) - 1) % V].astype(np.int64)
+    g = _normal(rng, (B, T, D), 1e-3)
+    if dtype == "bf16":
+        g = round_to_bf16(g)
+    return ids, g

@@ -664,3 +664,101 @@ def test_linear_pegn_argument_errors():
     assert lib.linear_pegn(*args(wsb=16)) == 3
     assert lib.linear_pegn_workspace_bytes(0, 8, 16, 16, 1) == 0
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ embedding-layer per-example norms (Appendix B)
+def _run_embedding(ids, g, V, dtype, w0=None, int32=False):
+    import torch
+    from paper_2411_00999_amd import binding
+    gd = pu.to_device(g, dtype)
+    idd = torch.from_numpy(ids.astype(np.int32 if int32 else np.int64)).cuda()
+    w = None if w0 is None else torch.from_numpy(w0.astype(np.float32)).cuda()
+    w, s, big = binding.embedding_pegn(idd, gd, V, w=w, accumulate=w0 is not None)
+    torch.cuda.synchronize()
+    return pu.to_host64(w), pu.to_host64(s), pu.to_host64(big)
+
+
+def _check_embedding(ids, g, V, got, w0=None):
+    from oracle import embedding_pegn_oracle as emb
+    ref = emb.embedding_pegn(ids, g, V)
+    w_ref = ref["w"] if w0 is None else ref["w"] + w0.astype(np.float32).astype(np.float64)
+    w, s, big = got
+    pu.check_close("w", w, w_ref, pu.TOL_SUMS)
+    absent = np.setdiff1d(np.arange(V), np.unique(ids))
+    if w0 is None and absent.size:
+        assert not w[absent].any(), "rows of absent ids must be exactly zero"
+    np.testing.assert_allclose(s, ref["s"], rtol=pu.TOL_SUMS, err_msg="s")
+    np.testing.assert_allclose(big, [np.sum(w_ref ** 2)], rtol=pu.TOL_SUMS, err_msg="big_sq")
+
+
+@pytest.mark.parametrize("dtype,B,T,D,V", [
+    ("bf16", 4, 128, 768, 1000),      # several column blocks, a ragged last one
+    ("bf16", 3, 70, 2048, 50257),     # GPT-2 vocabulary, most rows absent
+    ("f32", 2, 33, 264, 97),
+    ("bf16", 2, 9, 100, 7),           # D % 8 != 0: element loads
+    ("f32", 1, 1, 1, 1),
+    ("bf16", 16, 64, 512, 31),        # few ids: long runs per id, many examples per id
+])
+def test_embedding_pegn_against_oracle(dtype, B, T, D, V):
+    ids, g = workloads.make_embedding_inputs(B * 100 + T, B, T, D, V, dtype)
+    _check_embedding(ids, g, V, _run_embedding(ids, g, V, dtype))
+    _check_embedding(ids, g, V, _run_embedding(ids, g, V, dtype, int32=True))
+    w0 = np.random.default_rng(workloads.BASE_SEED + 81).normal(0, 1e-2, (V, D))
+    _check_embedding(ids, g, V, _run_embedding(ids, g, V, dtype, w0=w0), w0=w0)
+
+
+def test_embedding_pegn_special_cases():
+    import torch
+    from paper_2411_00999_amd import binding
+    B, T, D, V = 4, 96, 512, 300
+    ids, g = workloads.make_embedding_inputs(9, B, T, D, V, "bf16")
+    g64 = g.astype(np.float64)
+    # one id throughout: s_b = |sum_t g_bt|^2; all ids distinct in an example: s_b = sum_t |g_bt|^2
+    _, s_same, _ = _run_embedding(np.full((B, T), 5), g, V, "bf16")
+    np.testing.assert_allclose(s_same, (g64.sum(1) ** 2).sum(1), rtol=1e-5)
+    distinct = np.stack([np.random.default_rng(b).permutation(V)[:T] for b in range(B)])
+    _, s_dist, _ = _run_embedding(distinct, g, V, "bf16")
+    np.testing.assert_allclose(s_dist, (g64 ** 2).sum((1, 2)), rtol=1e-5)
+    # ids outside [0,V) are skipped: the same result as without those positions' gradients
+    bad = ids.copy()
+    bad[:, ::7] = -3
+    bad[:, 3::11] = V + 5
+    g_masked = g.copy()
+    g_masked[(bad < 0) | (bad >= V)] = 0.0
+    w_bad, s_bad, big_bad = _run_embedding(bad, g, V, "bf16")
+    ok = np.where((bad < 0) | (bad >= V), 0, bad)
+    _check_embedding(ok, g_masked, V, (w_bad, s_bad, big_bad))
+    # bitwise reproducible, and the norms feed the estimator
+    gd, idd = pu.to_device(g, "bf16"), torch.from_numpy(ids).cuda()
+    a = binding.embedding_pegn(idd, gd, V)
+    b = binding.embedding_pegn(idd, gd, V)
+    torch.cuda.synchronize()
+    assert all(torch.equal(p, q) for p, q in zip(a, b))
+    est = binding.gns_estimate(a[1], a[2], float(B)).cpu().numpy().astype(np.float64)
+    from oracle import embedding_pegn_oracle as emb
+    ref = emb.embedding_pegn(ids, g, V)
+    _check_gns(est, oracle.gns_estimate(ref["s"], [np.sum(ref["w"] ** 2)], float(B)), B)
+
+
+def test_embedding_pegn_argument_errors():
+    import torch
+    from paper_2411_00999_amd import binding
+    lib = binding.load()
+    ids = torch.zeros((2, 8), dtype=torch.int32, device="cuda")
+    g = torch.zeros((2, 8, 16), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((5, 16), dtype=torch.float32, device="cuda")
+    s = torch.zeros(2, dtype=torch.float32, device="cuda")
+    nb = lib.embedding_pegn_workspace_bytes(2, 8, 16, 5)
+    assert nb > 0
+    ws = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+    args = lambda **kw: [kw.get("ids", ids.data_ptr()), 0, g.data_ptr(), w.data_ptr(), s.data_ptr(), None,
+                         kw.get("B", 2), 8, 16, 5, kw.get("dt", 1), ws.data_ptr(), kw.get("wsb", ws.numel()),
+                         kw.get("flags", 0), None]
+    assert lib.embedding_pegn(*args()) == 0
+    assert lib.embedding_pegn(*args(ids=None)) == 1
+    assert lib.embedding_pegn(*args(B=0)) == 1
+    assert lib.embedding_pegn(*args(flags=2)) == 1
+    assert lib.embedding_pegn(*args(dt=9)) == 2
+    assert lib.embedding_pegn(*args(wsb=64)) == 3
+    assert lib.embedding_pegn_workspace_bytes(2, 8, 16, 0) == 0
+    torch.cuda.synchronize()
