@@ -3,10 +3,12 @@
 //   s[b]     = sum_{v,d} w_b[v,d]^2               (step 3)
 //   w'[v,d]  = sum_b w_b[v,d]                     (step 4)
 // The positions p = b*T + t are sorted by id (stable, so positions ascend inside an id and the rows of one
-// example are adjacent).  One wave then walks an id's rows in that order with the columns spread over its
-// lanes: the running sum is cut at every change of example, where its squared norm is that example's share
-// of step 3, and the pieces add up to the row of w'.  Every row of g is read once; nothing is atomic, so the
-// results are bitwise reproducible.
+// example are adjacent): a "run" is the rows of one id in one example, a "segment" all runs of one id.
+// Kernel A gives every run to a wave (columns spread over its lanes): the run's sum, squared, is that
+// example's share of step 3; if the run is the id's only one it is also the row of w'.  Otherwise the sum is
+// parked in the workspace and kernel B adds an id's parked sums in example order (at most B of them).
+// Every row of g is read once, an id that fills half the batch still costs no wave more than one example's
+// worth of rows, and nothing is atomic: results are bitwise reproducible.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -75,13 +77,41 @@ __device__ __forceinline__ void add_row(const float *g, int64_t p, int D, int c0
     }
 }
 
-// keys/vals: positions sorted by id.  contrib [ncb][n]: share of s[b] found at the first position of every
-// (id, example) run, zero elsewhere.  bigpart [ncb][n]: squared norm of the finished row of w' at the
-// position heading the id's segment, zero elsewhere (not used when accumulating).
+__device__ __forceinline__ uint32_t lane_value(uint32_t v, int lane)      // lane is wave-uniform
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
+}
+
+// One window of the sorted list: lane l looks at sorted position i + l.  Returns how many of the leading
+// positions satisfy same(key, example), 0..64, and leaves each lane's position value in val.
+struct Window {
+    uint32_t key, val, ex;
+};
+__device__ __forceinline__ Window window_at(const uint32_t *keys, const uint32_t *vals, int64_t i, int64_t n,
+                                             int Tn, int lane)
+{
+    Window w;
+    const bool in = i + lane < n;
+    w.key = in ? keys[i + lane] : 0xffffffffu;
+    w.val = in ? vals[i + lane] : 0u;
+    w.ex = w.val / (uint32_t)Tn;
+    return w;
+}
+__device__ __forceinline__ int leading(bool pred)
+{
+    const uint64_t not_pred = ~__ballot(pred);
+    return not_pred ? __builtin_ctzll(not_pred) : 64;
+}
+
+// Kernel A.  keys/vals: positions sorted by id.  A wave looks after the runs whose first row is among its
+// kChunk sorted positions.  contrib [ncb][n]: the run's share of s[b], stored at the run's first position,
+// zero elsewhere.  runsum [n][D]: the sums of runs that are not their id's only run, at the same index.
+// bigpart [ncb][n]: squared norm of a finished row of w', at the segment's first position (not when
+// accumulating).
 template <typename T>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void emb_segments_kernel(
-    const T *g, const uint32_t *keys, const uint32_t *vals, float *w, float *contrib, float *bigpart, int64_t n,
-    int Tn, int D, int V, int accumulate, int vec_ok)
+__global__ __launch_bounds__(64 * kWavesPerBlock) void emb_runs_kernel(
+    const T *g, const uint32_t *keys, const uint32_t *vals, float *w, float *runsum, float *contrib, float *bigpart,
+    int64_t n, int Tn, int D, int V, int accumulate, int vec_ok)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -91,50 +121,131 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void emb_segments_kernel(
     const bool vec = vec_ok && c0 + 8 <= D;
     for (int64_t i = i0; i < i0 + kChunk && i < n; ++i) {
         const uint32_t v = keys[i];
-        if (v >= (uint32_t)V || (i > 0 && keys[i - 1] == v)) continue;      // not the head of a segment
+        if (v >= (uint32_t)V) break;                            // ids out of range are sorted last
+        const uint32_t first = vals[i], b = first / (uint32_t)Tn;
+        const bool seg_head = i == 0 || keys[i - 1] != v;
+        if (!seg_head && vals[i - 1] / (uint32_t)Tn == b) continue;    // inside a run, not its head
+        float sub[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) sub[k] = 0.f;
+        int64_t j = i;
+        int len;
+        uint32_t next_key = 0xffffffffu;
+        do {                                                    // the run, a window of 64 positions at a time
+            const Window win = window_at(keys, vals, j, n, Tn, lane);
+            len = leading(win.key == v && win.ex == b);
+            for (int r = 0; r < len; r += 4) {                  // four rows in flight, added in order
+                float part[4][8];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) part[u][k] = 0.f;
+                    if (r + u < len && has_cols) add_row(g, (int64_t)lane_value(win.val, r + u), D, c0, vec, part[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) sub[k] += part[u][k];
+            }
+            if (len < 64) next_key = lane_value(win.key, len);  // what follows the run (0xffffffff: nothing)
+            j += len;
+        } while (len == 64);
+        float sq = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) sq = fmaf(sub[k], sub[k], sq);
+        sq = wave_sum(sq);
+        if (lane == 0) contrib[(int64_t)cb * n + first] = sq;
+        const bool only_run = seg_head && next_key != v;
+        if (only_run) {
+            float wsq = 0.f;
+            if (has_cols) {
+                float *row = w + (int64_t)v * D + c0;
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (c0 + k < D) {
+                        const float r = accumulate ? row[k] + sub[k] : sub[k];
+                        row[k] = r;
+                        wsq = fmaf(r, r, wsq);
+                    }
+            }
+            if (!accumulate) {
+                wsq = wave_sum(wsq);
+                if (lane == 0) bigpart[(int64_t)cb * n + first] = wsq;
+            }
+        } else if (has_cols) {
+            float *row = runsum + (int64_t)first * D + c0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (c0 + k < D) row[k] = sub[k];
+        }
+    }
+}
+
+// Kernel B.  A wave looks after the segments (ids) whose first row is among its kChunk sorted positions and
+// that have more than one run: the row of w' is the sum of the runs' parked sums, in example order.
+__global__ __launch_bounds__(64 * kWavesPerBlock) void emb_ids_kernel(
+    const uint32_t *keys, const uint32_t *vals, float *w, const float *runsum, float *bigpart, int64_t n, int Tn,
+    int D, int V, int accumulate)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t i0 = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * kChunk;
+    const int cb = blockIdx.y, c0 = cb * kColBlock + lane * 8;
+    const bool has_cols = c0 < D;
+    for (int64_t i = i0; i < i0 + kChunk && i < n; ++i) {
+        const uint32_t v = keys[i];
+        if (v >= (uint32_t)V) break;
+        if (i > 0 && keys[i - 1] == v) continue;                // not the head of a segment
         float tot[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) tot[k] = 0.f;
-        int64_t j = i;
-        while (j < n && keys[j] == v) {
-            // one (id, example) run: positions ascend, so it ends where the example number changes
-            const int64_t first = vals[j];
-            const int64_t b = first / Tn;
-            float sub[8];
+        // first the number of runs (positions only); an id with one run was finished by kernel A
+        int runs = 0;
+        for (int pass = 0; pass < 2; ++pass) {
+            if (pass == 1 && runs < 2) break;
+            int64_t j = i;
+            uint32_t prev_ex = 0xffffffffu;                      // example of the position before the window
+            int len;
+            do {
+                const Window win = window_at(keys, vals, j, n, Tn, lane);
+                len = leading(win.key == v);
+                // a position heads a run if the one before it belongs to another example
+                uint32_t before = (uint32_t)__shfl_up((int)win.ex, 1);
+                if (lane == 0) before = prev_ex;
+                uint64_t heads = __ballot(lane < len && win.ex != before);
+                if (pass == 0) {
+                    runs += __popcll(heads);
+                } else {
+                    while (heads) {                              // parked sums, in example order
+                        const int r = __builtin_ctzll(heads);
+                        heads &= heads - 1;
+                        if (has_cols) {
+                            const float *row = runsum + (int64_t)lane_value(win.val, r) * D + c0;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) sub[k] = 0.f;
-            int64_t p = first;
-            while (true) {
-                if (has_cols) add_row(g, p, D, c0, vec, sub);
-                ++j;
-                if (j >= n || keys[j] != v) break;
-                p = vals[j];
-                if (p / Tn != b) break;
-            }
-            float sq = 0.f;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                sq = fmaf(sub[k], sub[k], sq);
-                tot[k] += sub[k];
-            }
-            sq = wave_sum(sq);
-            if (lane == 0) contrib[(int64_t)cb * n + first] = sq;
+                            for (int k = 0; k < 8; ++k)
+                                if (c0 + k < D) tot[k] += row[k];
+                        }
+                    }
+                }
+                if (len > 0) prev_ex = lane_value(win.ex, len - 1);
+                j += len;
+            } while (len == 64);
         }
-        float sq = 0.f;
+        if (runs < 2) continue;
+        float wsq = 0.f;
         if (has_cols) {
             float *row = w + (int64_t)v * D + c0;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < 8; ++k)
                 if (c0 + k < D) {
                     const float r = accumulate ? row[k] + tot[k] : tot[k];
                     row[k] = r;
-                    sq = fmaf(r, r, sq);
+                    wsq = fmaf(r, r, wsq);
                 }
-            }
         }
         if (!accumulate) {
-            sq = wave_sum(sq);
-            if (lane == 0) bigpart[(int64_t)cb * n + vals[i]] = sq;
+            wsq = wave_sum(wsq);
+            if (lane == 0) bigpart[(int64_t)cb * n + vals[i]] = wsq;
         }
     }
 }
@@ -186,7 +297,7 @@ int key_bits(int V)
 struct EmbPlan {
     int64_t n;
     int ncb;
-    size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_contrib, off_bigpart, off_wpart, off_temp;
+    size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_contrib, off_bigpart, off_wpart, off_temp, off_runsum;
     size_t temp_bytes, bytes;
 };
 
@@ -215,7 +326,8 @@ hipError_t make_emb_plan(int B, int T, int D, int V, EmbPlan &p)
     p.off_wpart = p.off_bigpart + f;
     p.off_temp = p.off_wpart + align256(kNormBlocks * sizeof(double));
     p.temp_bytes = temp;
-    p.bytes = p.off_temp + align256(temp);
+    p.off_runsum = p.off_temp + align256(temp);
+    p.bytes = p.off_runsum + align256((size_t)p.n * D * sizeof(float));
     return hipSuccess;
 }
 
@@ -271,12 +383,18 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
     // 8 columns per lane: 16 bytes of bf16, 32 bytes of fp32; rows must keep that alignment
     const int vec_ok = ((reinterpret_cast<uintptr_t>(g) & 15u) == 0 && ((int64_t)D * esz) % 16 == 0) ? 1 : 0;
     const dim3 grid((unsigned)((p.n + kChunk * kWavesPerBlock - 1) / (kChunk * kWavesPerBlock)), (unsigned)p.ncb);
+    float *runsum = reinterpret_cast<float *>(ws + p.off_runsum);
     if (dt == LNPEGN_BF16)
-        emb_segments_kernel<bf16_t><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(
-            static_cast<const bf16_t *>(g), keys_out, vals_out, w, contrib, bigpart, p.n, T, D, V, accumulate, vec_ok);
+        emb_runs_kernel<bf16_t><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(
+            static_cast<const bf16_t *>(g), keys_out, vals_out, w, runsum, contrib, bigpart, p.n, T, D, V, accumulate,
+            vec_ok);
     else
-        emb_segments_kernel<float><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(
-            static_cast<const float *>(g), keys_out, vals_out, w, contrib, bigpart, p.n, T, D, V, accumulate, vec_ok);
+        emb_runs_kernel<float><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(
+            static_cast<const float *>(g), keys_out, vals_out, w, runsum, contrib, bigpart, p.n, T, D, V, accumulate,
+            vec_ok);
+    if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    emb_ids_kernel<<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(keys_out, vals_out, w, runsum, bigpart, p.n, T, D, V,
+                                                              accumulate);
     if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
     const bool wnorm = accumulate && big_sq;
     if (wnorm) {
