@@ -169,6 +169,53 @@ def linear_leg(shape_name, steps, warmup, log):
     }
 
 
+def embedding_leg(shape_name, steps, warmup, log):
+    """Embedding-layer simultaneous per-example norms (Appendix B) on one layer: whole-call time (sort,
+    zero-fill of w', run and id kernels, final reduction) against HBM; algorithmic bytes = read g once +
+    write every row of w' once."""
+    import numpy as np
+    import torch
+    from paper_2411_00999_amd import binding, workloads
+    B, T, D, V = workloads.EMBEDDING_SHAPES[shape_name]
+    ids_h, _ = workloads.make_embedding_inputs(1, B, T, 8, V, "f32")
+    ids = torch.from_numpy(ids_h).cuda()
+    torch.manual_seed(workloads.BASE_SEED % (2 ** 31))
+    g = (torch.randn((B, T, D), device="cuda") * 1e-3).to(torch.bfloat16)
+    lib = binding.load()
+    ws = torch.empty(lib.embedding_pegn_workspace_bytes(B, T, D, V), dtype=torch.uint8, device="cuda")
+    w = torch.empty((V, D), dtype=torch.float32, device="cuda")
+    s = torch.empty(B, dtype=torch.float32, device="cuda")
+    big = torch.empty(1, dtype=torch.float32, device="cuda")
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    ms = timed(lambda: binding.embedding_pegn(ids, g, V, w=w, s=s, big_sq=big, workspace=ws))
+    ms_lib = timed(lambda: torch.ops.aten.embedding_dense_backward(g, ids, V, -1, False))
+    alg = B * T * D * 2 + V * D * 4
+    gbs = alg / ms / 1e6
+    log(f"embedding_pegn {shape_name}: {ms:.3f} ms = {gbs:.0f} GB/s algorithmic; library embedding backward {ms_lib:.3f} ms")
+    return {
+        "workload": f"{shape_name}: ids [B={B},T={T}] Zipf over V={V} ({len(np.unique(ids_h))} distinct), g [B,T,D={D}] bf16 "
+                    f"-> w' [V,D] fp32, s [B], ||w'||^2",
+        "ms_per_call": round(ms, 4),
+        "roofline": {"kernel": "embedding_pegn (whole call: sort, fill, runs, ids, final)", "bound": "hbm",
+                     "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_bytes_per_call": alg},
+        "library_plain_backward": {"what": "aten.embedding_dense_backward in bf16: the weight gradient alone (bf16 "
+                                           "result), no per-example norms", "ms_per_call": round(ms_lib, 4)},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -188,6 +235,8 @@ def main():
     ap.add_argument("--linear-only", action="store_true",
                     help="run only the linear-layer leg (for profiling that kernel) and print its object")
     ap.add_argument("--linear-shape", default="gpt1p3b_up", help="a key of workloads.LINEAR_SHAPES")
+    ap.add_argument("--embedding-only", action="store_true", help="run only the embedding-layer leg")
+    ap.add_argument("--embedding-shape", default="gpt1p3b_wte", help="a key of workloads.EMBEDDING_SHAPES")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
 
@@ -204,6 +253,11 @@ def main():
         if args.gpus != 1:
             sys.exit("this build runs on one GPU only: use --gpus 1")
         print(json.dumps(linear_leg(args.linear_shape, args.steps, args.warmup, log0)), flush=True)
+        return
+    if args.embedding_only:
+        if args.gpus != 1:
+            sys.exit("this build runs on one GPU only: use --gpus 1")
+        print(json.dumps(embedding_leg(args.embedding_shape, args.steps, args.warmup, log0)), flush=True)
         return
 
     def log(msg):
@@ -408,12 +462,13 @@ def main():
         parity = {"layer0_dgamma_l2_rel": err_dg, "layer0_s_gamma_max_rel": err_sg,
                   "ok": bool(err_dg < 1e-5 and err_sg < 1e-5)}
 
-    linear = None
+    linear = embedding = None
     if not (args.no_linear or args.only_fused):
         layers.clear()
         sh.clear()
         torch.cuda.empty_cache()
         linear = linear_leg(args.linear_shape, 20, 3, log)
+        embedding = embedding_leg(args.embedding_shape, 20, 3, log)
 
     out = {
         "metric": "fused LN bwd+per-example norms GB/s, % HBM peak, overhead vs plain ln_bwd",
@@ -454,6 +509,7 @@ def main():
         "cpu_baseline": cpu_baseline,
         "parity_spot_check": parity,
         "linear_pegn": linear,
+        "embedding_pegn": embedding,
     }
     def clean(o):      # NaN (skipped legs) -> null, so the line stays valid JSON
         if isinstance(o, dict):

@@ -63,6 +63,41 @@ __device__ __forceinline__ void add_row(const bf16_t *g, int64_t p, int D, int c
     }
 }
 
+// the same eight columns as raw 16-byte loads, for callers that want several rows in flight
+template <typename T>
+struct Row8;
+template <>
+struct Row8<bf16_t> {
+    uint4 a;
+};
+template <>
+struct Row8<float> {
+    float4 a, b;
+};
+__device__ __forceinline__ Row8<bf16_t> load_row8(const bf16_t *g, int64_t p, int D, int c0)
+{
+    return Row8<bf16_t>{*reinterpret_cast<const uint4 *>(g + p * D + c0)};
+}
+__device__ __forceinline__ Row8<float> load_row8(const float *g, int64_t p, int D, int c0)
+{
+    const float *row = g + p * D + c0;
+    return Row8<float>{*reinterpret_cast<const float4 *>(row), *reinterpret_cast<const float4 *>(row + 4)};
+}
+__device__ __forceinline__ void unpack_row8(const Row8<bf16_t> &r, float (&f)[8])
+{
+    const uint32_t w[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = __builtin_bit_cast(float, w[i] << 16);
+        f[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void unpack_row8(const Row8<float> &r, float (&f)[8])
+{
+    f[0] = r.a.x; f[1] = r.a.y; f[2] = r.a.z; f[3] = r.a.w;
+    f[4] = r.b.x; f[5] = r.b.y; f[6] = r.b.z; f[7] = r.b.w;
+}
+
 __device__ __forceinline__ void add_row(const float *g, int64_t p, int D, int c0, bool vec, float (&sub)[8])
 {
     const float *row = g + p * D + c0;
@@ -75,6 +110,32 @@ __device__ __forceinline__ void add_row(const float *g, int64_t p, int D, int c0
         for (int i = 0; i < 8; ++i)
             if (c0 + i < D) sub[i] += row[i];
     }
+}
+
+// eight fp32 columns of a row: out[k] = (add ? row[k] : 0) + in[k], stored; returns the sum of squares
+__device__ __forceinline__ float put_row(float *row, const float (&in)[8], int c0, int D, bool add)
+{
+    float sq = 0.f;
+    if (c0 + 8 <= D && (reinterpret_cast<uintptr_t>(row) & 15u) == 0) {
+        float4 lo = make_float4(in[0], in[1], in[2], in[3]), hi = make_float4(in[4], in[5], in[6], in[7]);
+        if (add) {
+            const float4 a = *reinterpret_cast<const float4 *>(row), b = *reinterpret_cast<const float4 *>(row + 4);
+            lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
+            hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
+        }
+        *reinterpret_cast<float4 *>(row) = lo;
+        *reinterpret_cast<float4 *>(row + 4) = hi;
+        sq = lo.x * lo.x + lo.y * lo.y + lo.z * lo.z + lo.w * lo.w + hi.x * hi.x + hi.y * hi.y + hi.z * hi.z + hi.w * hi.w;
+    } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (c0 + k < D) {
+                const float v = add ? row[k] + in[k] : in[k];
+                row[k] = v;
+                sq = fmaf(v, v, sq);
+            }
+    }
+    return sq;
 }
 
 __device__ __forceinline__ uint32_t lane_value(uint32_t v, int lane)      // lane is wave-uniform
@@ -104,10 +165,11 @@ __device__ __forceinline__ int leading(bool pred)
 }
 
 // Kernel A.  keys/vals: positions sorted by id.  A wave looks after the runs whose first row is among its
-// kChunk sorted positions.  contrib [ncb][n]: the run's share of s[b], stored at the run's first position,
-// zero elsewhere.  runsum [n][D]: the sums of runs that are not their id's only run, at the same index.
-// bigpart [ncb][n]: squared norm of a finished row of w', at the segment's first position (not when
-// accumulating).
+// kChunk sorted positions, and streams their rows eight at a time in sorted order, closing a run wherever
+// the next position starts another.  contrib [ncb][n]: the run's share of s[b], stored at the run's first
+// position, zero elsewhere.  runsum [n][D]: the sums of runs that are not their id's only run, at the same
+// index.  bigpart [ncb][n]: squared norm of a finished row of w', at the segment's first position (not
+// when accumulating).
 template <typename T>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void emb_runs_kernel(
     const T *g, const uint32_t *keys, const uint32_t *vals, float *w, float *runsum, float *contrib, float *bigpart,
@@ -115,69 +177,114 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void emb_runs_kernel(
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t i0 = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * kChunk;
-    const int cb = blockIdx.y, c0 = cb * kColBlock + lane * 8;
+    // the waves of a workgroup take the same positions and neighbouring column blocks: a row of g is then
+    // read whole by one workgroup at one time
+    const int64_t i0 = (int64_t)blockIdx.x * kChunk;
+    const int cb = blockIdx.y * kWavesPerBlock + wave, c0 = cb * kColBlock + lane * 8;
+    if (i0 >= n || cb * kColBlock >= D) return;
     const bool has_cols = c0 < D;
     const bool vec = vec_ok && c0 + 8 <= D;
-    for (int64_t i = i0; i < i0 + kChunk && i < n; ++i) {
-        const uint32_t v = keys[i];
-        if (v >= (uint32_t)V) break;                            // ids out of range are sorted last
-        const uint32_t first = vals[i], b = first / (uint32_t)Tn;
-        const bool seg_head = i == 0 || keys[i - 1] != v;
-        if (!seg_head && vals[i - 1] / (uint32_t)Tn == b) continue;    // inside a run, not its head
-        float sub[8];
+    float sub[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) sub[k] = 0.f;
-        int64_t j = i;
-        int len;
-        uint32_t next_key = 0xffffffffu;
-        do {                                                    // the run, a window of 64 positions at a time
-            const Window win = window_at(keys, vals, j, n, Tn, lane);
-            len = leading(win.key == v && win.ex == b);
-            for (int r = 0; r < len; r += 4) {                  // four rows in flight, added in order
-                float part[4][8];
+    for (int k = 0; k < 8; ++k) sub[k] = 0.f;
+    bool in_run = false;                 // a run of this wave is open (its sum so far is in sub)
+    uint32_t cur_first = 0, cur_key = 0;
+    bool cur_seg_head = false;
+    int64_t pos = i0;                    // next sorted position to look at
+    while (true) {
+        // lane l looks at sorted position pos - 1 + l: lane 0 is the position before, lanes 1..62 are
+        // handled in this round, lane 63 is only looked at as "what follows lane 62"
+        const int64_t q = pos - 1 + lane;
+        const bool in = q >= 0 && q < n;
+        const uint32_t key = in ? keys[q] : 0xffffffffu, val = in ? vals[q] : 0u;
+        const uint32_t ex = val / (uint32_t)Tn;
+        const uint32_t pkey = (uint32_t)__shfl_up((int)key, 1), pex = (uint32_t)__shfl_up((int)ex, 1);
+        const bool valid = key < (uint32_t)V;
+        const uint64_t m_valid = __ballot(valid);
+        const uint64_t m_head = __ballot(valid && lane >= 1 && (key != pkey || ex != pex));     // starts a run
+        const uint64_t m_seg = __ballot(valid && lane >= 1 && key != pkey);                     // starts a segment
+        // the lanes this wave handles now: from the first run head of its chunk (or lane 1 if a run is
+        // open) up to the lane before the first head that belongs to a later chunk, an invalid key, or 63
+        const int64_t chunk_end = i0 + kChunk;
+        int l = 1;
+        if (!in_run) {
+            const uint64_t h = m_head & ~(uint64_t)1;
+            if (!h) {
+                // no run starts in this round; rows seen belong to a run of an earlier chunk
+                if (!(m_valid >> 62 & 1) || pos - 1 + 62 >= chunk_end) return;
+                pos += 62;
+                continue;
+            }
+            l = __builtin_ctzll(h);
+            if (pos - 1 + l >= chunk_end) return;
+        }
+        // end: first lane >= l that is invalid, or a head at a position >= chunk_end
+        int e = l;
+        while (e <= 62) {
+            if (!(m_valid >> e & 1)) break;
+            if ((m_head >> e & 1) && pos - 1 + e >= chunk_end) break;
+            ++e;
+        }
+        // rows l .. e-1, eight in flight: the loads carry no condition (a row past the end repeats the last
+        // one and is dropped afterwards), so that all eight are issued before the first is waited for
+        for (int r = l; r < e; r += 8) {
+            float part[8][8];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 8; ++u)
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) part[u][k] = 0.f;
-                    if (r + u < len && has_cols) add_row(g, (int64_t)lane_value(win.val, r + u), D, c0, vec, part[u]);
+                for (int k = 0; k < 8; ++k) part[u][k] = 0.f;
+            if (vec) {                                           // lanes whose eight columns are a whole vector
+                Row8<T> raw[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int t = r + u < e ? r + u : e - 1;
+                    raw[u] = load_row8(g, (int64_t)lane_value(val, t), D, c0);
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < 8; ++u) unpack_row8(raw[u], part[u]);
+            } else if (has_cols) {                               // ragged or unaligned columns: element loads
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) sub[k] += part[u][k];
+                for (int u = 0; u < 8; ++u)
+                    if (r + u < e) add_row(g, (int64_t)lane_value(val, r + u), D, c0, false, part[u]);
             }
-            if (len < 64) next_key = lane_value(win.key, len);  // what follows the run (0xffffffff: nothing)
-            j += len;
-        } while (len == 64);
-        float sq = 0.f;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) sq = fmaf(sub[k], sub[k], sq);
-        sq = wave_sum(sq);
-        if (lane == 0) contrib[(int64_t)cb * n + first] = sq;
-        const bool only_run = seg_head && next_key != v;
-        if (only_run) {
-            float wsq = 0.f;
-            if (has_cols) {
-                float *row = w + (int64_t)v * D + c0;
+            for (int u = 0; u < 8; ++u) {
+                const int t = r + u;
+                if (t >= e) break;
+                if (m_head >> t & 1) {                           // this row opens a run
+                    in_run = true;
+                    cur_first = lane_value(val, t);
+                    cur_key = lane_value(key, t);
+                    cur_seg_head = (m_seg >> t & 1) != 0;
 #pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    if (c0 + k < D) {
-                        const float r = accumulate ? row[k] + sub[k] : sub[k];
-                        row[k] = r;
-                        wsq = fmaf(r, r, wsq);
+                    for (int k = 0; k < 8; ++k) sub[k] = 0.f;
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k) sub[k] += part[u][k];
+                // the run ends here if the next position is invalid or opens another run; lane 63's
+                // successor is unknown, which is why lane 62 is the last one handled in a round
+                const bool next_valid = (m_valid >> (t + 1) & 1) != 0;
+                if (next_valid && !(m_head >> (t + 1) & 1)) continue;
+                const uint32_t next_key = next_valid ? lane_value(key, t + 1) : 0xffffffffu;
+                float sq = 0.f;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) sq = fmaf(sub[k], sub[k], sq);
+                sq = wave_sum(sq);
+                if (lane == 0) contrib[(int64_t)cb * n + cur_first] = sq;
+                if (cur_seg_head && next_key != cur_key) {      // the id's only run: this is the row of w'
+                    float wsq = has_cols ? put_row(w + (int64_t)cur_key * D + c0, sub, c0, D, accumulate != 0) : 0.f;
+                    if (!accumulate) {
+                        wsq = wave_sum(wsq);
+                        if (lane == 0) bigpart[(int64_t)cb * n + cur_first] = wsq;
                     }
+                } else if (has_cols) {
+                    put_row(runsum + (int64_t)cur_first * D + c0, sub, c0, D, false);
+                }
+                in_run = false;
             }
-            if (!accumulate) {
-                wsq = wave_sum(wsq);
-                if (lane == 0) bigpart[(int64_t)cb * n + first] = wsq;
-            }
-        } else if (has_cols) {
-            float *row = runsum + (int64_t)first * D + c0;
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                if (c0 + k < D) row[k] = sub[k];
         }
+        if (e <= 62) return;              // stopped at an invalid key or at a later chunk's run
+        pos += 62;                        // lane 62 was the last handled: it becomes lane 0 of the next round
     }
 }
 
@@ -189,9 +296,11 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void emb_ids_kernel(
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t i0 = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * kChunk;
-    const int cb = blockIdx.y, c0 = cb * kColBlock + lane * 8;
+    const int64_t i0 = (int64_t)blockIdx.x * kChunk;
+    const int cb = blockIdx.y * kWavesPerBlock + wave, c0 = cb * kColBlock + lane * 8;
+    if (cb * kColBlock >= D) return;
     const bool has_cols = c0 < D;
+    const bool runsum_vec = c0 + 8 <= D && D % 4 == 0 && (reinterpret_cast<uintptr_t>(runsum) & 15u) == 0;
     for (int64_t i = i0; i < i0 + kChunk && i < n; ++i) {
         const uint32_t v = keys[i];
         if (v >= (uint32_t)V) break;
@@ -219,12 +328,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void emb_ids_kernel(
                     while (heads) {                              // parked sums, in example order
                         const int r = __builtin_ctzll(heads);
                         heads &= heads - 1;
-                        if (has_cols) {
-                            const float *row = runsum + (int64_t)lane_value(win.val, r) * D + c0;
-#pragma unroll
-                            for (int k = 0; k < 8; ++k)
-                                if (c0 + k < D) tot[k] += row[k];
-                        }
+                        if (has_cols) add_row(runsum, (int64_t)lane_value(win.val, r), D, c0, runsum_vec, tot);
                     }
                 }
                 if (len > 0) prev_ex = lane_value(win.ex, len - 1);
@@ -232,17 +336,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void emb_ids_kernel(
             } while (len == 64);
         }
         if (runs < 2) continue;
-        float wsq = 0.f;
-        if (has_cols) {
-            float *row = w + (int64_t)v * D + c0;
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                if (c0 + k < D) {
-                    const float r = accumulate ? row[k] + tot[k] : tot[k];
-                    row[k] = r;
-                    wsq = fmaf(r, r, wsq);
-                }
-        }
+        float wsq = has_cols ? put_row(w + (int64_t)v * D + c0, tot, c0, D, accumulate != 0) : 0.f;
         if (!accumulate) {
             wsq = wave_sum(wsq);
             if (lane == 0) bigpart[(int64_t)cb * n + vals[i]] = wsq;
@@ -278,7 +372,17 @@ __global__ __launch_bounds__(1024) void emb_final_kernel(const float *contrib, c
         if (wpart) {
             for (int i = threadIdx.x; i < nwpart; i += 1024) t += wpart[i];
         } else {
-            for (int64_t i = threadIdx.x; i < (int64_t)ncb * n; i += 1024) t += (double)bigpart[i];
+            double t1 = 0.0, t2 = 0.0, t3 = 0.0;               // four loads in flight; the order stays fixed
+            const int64_t m = (int64_t)ncb * n;
+            int64_t i = threadIdx.x;
+            for (; i + 3072 < m; i += 4096) {
+                t += (double)bigpart[i];
+                t1 += (double)bigpart[i + 1024];
+                t2 += (double)bigpart[i + 2048];
+                t3 += (double)bigpart[i + 3072];
+            }
+            for (; i < m; i += 1024) t += (double)bigpart[i];
+            t = (t + t1) + (t2 + t3);
         }
         t = block_sum_f64(t, slots);
         if (threadIdx.x == 0) big_sq[0] = (float)t;
@@ -382,7 +486,7 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
     const int esz = dt == LNPEGN_BF16 ? 2 : 4;
     // 8 columns per lane: 16 bytes of bf16, 32 bytes of fp32; rows must keep that alignment
     const int vec_ok = ((reinterpret_cast<uintptr_t>(g) & 15u) == 0 && ((int64_t)D * esz) % 16 == 0) ? 1 : 0;
-    const dim3 grid((unsigned)((p.n + kChunk * kWavesPerBlock - 1) / (kChunk * kWavesPerBlock)), (unsigned)p.ncb);
+    const dim3 grid((unsigned)((p.n + kChunk - 1) / kChunk), (unsigned)((p.ncb + kWavesPerBlock - 1) / kWavesPerBlock));
     float *runsum = reinterpret_cast<float *>(ws + p.off_runsum);
     if (dt == LNPEGN_BF16)
         emb_runs_kernel<bf16_t><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(
