@@ -9,7 +9,8 @@ LayerNorm layer of the workload, ln_bwd_pegn (dx, dgamma, dbeta, per-example squ
 then one gns_estimate over all layers' norms.  With --reduce deferred (default) the layers'
 small reduction kernels are batched into one lnpegn_reduce_deferred per step, as a backward
 pass over many layers would do; --reduce immediate makes every call self-contained.  Inputs are
-resident in HBM before the timed region starts.  Prints ONE JSON line.
+resident in HBM before the timed region starts.  Prints ONE JSON line: the LayerNorm path's throughput
+with its roofline and CPU baseline, and one object each for the linear-layer and embedding-layer paths.
 """
 from __future__ import annotations
 
@@ -241,8 +242,9 @@ def main():
     args = ap.parse_args()
 
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards along the batch dimension; see "
-              "DESIGN.md); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (the path would shard along the batch dimension: per-example "
+              "norms stay local, only dgamma/dbeta and two scalars per layer cross ranks); --gpus must be 1",
+              file=sys.stderr)
         sys.exit(2)
 
     def log0(msg):
