@@ -256,7 +256,9 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
  * beyond floating-point summation order.  key 0: target number of row chunks of ln_bwd_pegn
  * (0 = automatic); key 1: the same for ln_bwd; key 2: waves per workgroup of the row kernel
  * (0 = automatic, else 1..16); key 3: rows between the sweep starts of consecutive examples,
- * plus one (0 = automatic); key 4: neighbouring chunks on one XCD (0 automatic, 1 never, 2 always).
+ * plus one (0 = automatic); key 4: neighbouring chunks on one XCD (0 automatic, 1 never, 2 always);
+ * key 5: cap on 16-byte vectors per lane and array of the row kernel (0 = automatic, else 1..4: fewer
+ * means more waves share a row).
  * Returns LNPEGN_EINVAL for an unknown key or a value out of range.  Not thread-safe against concurrent launches.
  */
 int lnpegn_set_tuning(int key, int value);

@@ -17,6 +17,7 @@ namespace {
 int g_chunks_pegn = 0;
 int g_chunks_plain = 0;
 int g_waves = 0;
+int g_vpt_max = 0;          // cap on 16-byte vectors per lane and array (0: automatic)
 int g_xcd = -1;        // hand neighbouring chunks to the same XCD: 0 never, 1 always, -1 automatic
 int g_stagger = -1;   // rows between the sweep starts of consecutive examples (-1 = automatic)
 // one-shot profiling events around the row kernel (null = disarmed)
@@ -63,7 +64,8 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
     Plan p{};
     const int E = dt == LNPEGN_BF16 ? 8 : 4;
     const int64_t N = (int64_t)B * T;
-    const int vpt_max = 16 / E;                      // at most 16 elements per lane
+    int vpt_max = 16 / E;                            // at most 16 elements per lane
+    if (g_vpt_max > 0 && g_vpt_max < vpt_max) vpt_max = g_vpt_max;
     p.fast = vector_ok && (D % E == 0) && (D / E <= 64 * vpt_max * 8);
     p.nvec = p.fast ? D / E : 0;
     p.sync = false;
@@ -574,6 +576,10 @@ int lnpegn_set_tuning(int key, int value)
         case 4:
             if (value > 2) return LNPEGN_EINVAL;
             g_xcd = value - 1;          // 0 automatic, 1 never, 2 always
+            return LNPEGN_OK;
+        case 5:
+            if (value > 4) return LNPEGN_EINVAL;
+            g_vpt_max = value;
             return LNPEGN_OK;
         default: return LNPEGN_EINVAL;
     }
