@@ -224,9 +224,9 @@ int gns_linear_accum_steps(int64_t tokens_seen, int64_t ramp_tokens, int accum_f
  *     with LNPEGN_ACCUMULATE (the only flag accepted).
  *   s [B] fp32: raw ||w_b||^2 (step 4's mean and B^2 are gns_estimate's pe_scale, as for LayerNorm).
  *   big_sq [1] fp32 or NULL: ||w||^2 of the (accumulated) weight gradient.
- * The per-example tensor [B,K,L] is never written to memory.  bf16 with K % 8 == 0, L % 8 == 0 and
- * 16-byte aligned x, g runs on the matrix cores (fp32 accumulation); anything else takes a slow
- * scalar kernel.  workspace: linear_pegn_workspace_bytes(...) bytes, 256-byte aligned, caller-owned,
+ * The per-example tensor [B,K,L] is never written to memory.  With 16-byte aligned x, g and K, L
+ * multiples of 8 (bf16) or 4 (fp32) the contraction runs on the matrix cores (bf16 or fp32 MFMA, fp32
+ * accumulation); anything else takes a slow scalar kernel.  workspace: linear_pegn_workspace_bytes(...) bytes, 256-byte aligned, caller-owned,
  * contents scratch.  K*L <= 2^31.  Enqueued on stream, never synchronises; status codes as above.
  */
 size_t linear_pegn_workspace_bytes(int B, int T, int K, int L, lnpegn_dtype dt);

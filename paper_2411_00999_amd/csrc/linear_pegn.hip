@@ -32,17 +32,20 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 // apart, which is a multiple of all banks, so the 16-byte chunks of row r are stored at chunk index
 // c ^ 4*(r & 3); a direct-to-LDS load writes a wave's 64 chunks contiguously, so the swizzle is applied
 // by choosing which chunk of memory each lane fetches.
-constexpr int kStageT = 64, kBufs = 3, kMaxSplit = 64;
+constexpr int kBufs = 3, kMaxSplit = 64;
 #define LIN_STR2(x) #x
 #define LIN_STR(x) LIN_STR2(x)
 #define LIN_XROW 512   // bytes per LDS row of x and of g, as literals for the assembly below
 #define LIN_GROW 256
 
-template <int WM, int WN, int MI, int NI>
+// kElem: bytes per element (2: bf16, 4: fp32).  A stage is 64 positions of bf16 or 32 of fp32: the same
+// 48 KiB either way.
+template <int WM, int WN, int MI, int NI, int kElem>
 struct LinCfg {
     static constexpr int kWaves = WM * WN, kThreads = 64 * kWaves;
     static constexpr int kTileK = WM * MI * 32, kTileL = WN * NI * 32;
-    static constexpr int kXRow = kTileK * 2, kGRow = kTileL * 2;          // bytes per LDS row
+    static constexpr int kStageT = 128 / kElem;
+    static constexpr int kXRow = kTileK * kElem, kGRow = kTileL * kElem;  // bytes per LDS row
     static constexpr int kXBytes = kStageT * kXRow, kGBytes = kStageT * kGRow;
     static constexpr int kStageBytes = kXBytes + kGBytes;
     static constexpr int kXLoads = kXBytes / 1024, kLoads = kStageBytes / 1024;   // direct loads of 1 KiB
@@ -55,11 +58,12 @@ struct LinCfg {
 // per workgroup.  Measured against 4 waves of 128 x 64 (one per SIMD, fewer LDS reads per MFMA): the
 // lone wave cannot cover its own LDS latency and is 30 % slower.
 #define LIN_CFG 4, 2, 2, 2
-typedef LinCfg<LIN_CFG> Cfg;
+typedef LinCfg<LIN_CFG, 2> Cfg;          // tile shape and wave count are the same for both element types
+typedef LinCfg<LIN_CFG, 4> CfgF32;
 
 struct LinArgs {
-    const uint16_t *x;      // [B,T,K] bf16
-    const uint16_t *g;      // [B,T,L] bf16
+    const char *x;          // [B,T,K] bf16 or fp32
+    const char *g;          // [B,T,L]
     float *out;             // nsplit == 1: w [K,L]; else partial totals [nsplit][K][L]
     float *tile_s;          // [B][ntiles*kWaves] per-wave parts of s[b]
     double *tile_big;       // [ntiles*kWaves] per-wave parts of ||w'||^2 (nsplit == 1 only)
@@ -87,9 +91,11 @@ __device__ __forceinline__ void load_to_lds(uint32_t lds_addr, uint32_t voff, co
                  : "memory");
 }
 
-template <typename C, int WM, int WN, int MI, int NI>
+template <typename C, int WM, int WN, int MI, int NI, int kElem>
 __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
 {
+    constexpr bool kF32 = kElem == 4;
+    constexpr int kStageT = C::kStageT, kPerChunk = 16 / kElem;       // elements per 16-byte chunk
     constexpr int kWaves = C::kWaves, kLoadsPerWave = C::kLoadsPerWave, kStageBytes = C::kStageBytes;
     constexpr int kXRow = C::kXRow, kGRow = C::kGRow, kXBytes = C::kXBytes;
     constexpr int kXChunks = kXRow / 16, kGChunks = kGRow / 16;       // 16-byte chunks per row
@@ -116,16 +122,19 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
 #pragma unroll
     for (int n = 0; n < kLoadsPerWave; ++n) {
         const int i = wave * kLoadsPerWave + n;
+        // fp32 operands are read back one element per lane along a row, which needs no swizzle
         if (i < C::kXLoads) {
-            const int r = kXRowsPerLoad * i + lane / kXChunks, c = (lane % kXChunks) ^ ((r & 3) << 2);
+            const int r = kXRowsPerLoad * i + lane / kXChunks;
+            const int c = kF32 ? lane % kXChunks : (lane % kXChunks) ^ ((r & 3) << 2);
             lrow[n] = r;
-            lcol_ok[n] = k0 + c * 8 < a.K;
-            voff[n] = (uint32_t)(((int64_t)r * a.K + c * 8) * 2);
+            lcol_ok[n] = k0 + c * kPerChunk < a.K;
+            voff[n] = (uint32_t)(((int64_t)r * a.K + c * kPerChunk) * kElem);
         } else {
-            const int r = kGRowsPerLoad * (i - C::kXLoads) + lane / kGChunks, c = (lane % kGChunks) ^ ((r & 3) << 2);
+            const int r = kGRowsPerLoad * (i - C::kXLoads) + lane / kGChunks;
+            const int c = kF32 ? lane % kGChunks : (lane % kGChunks) ^ ((r & 3) << 2);
             lrow[n] = r;
-            lcol_ok[n] = l0 + c * 8 < a.L;
-            voff[n] = (uint32_t)(((int64_t)r * a.L + c * 8) * 2);
+            lcol_ok[n] = l0 + c * kPerChunk < a.L;
+            voff[n] = (uint32_t)(((int64_t)r * a.L + c * kPerChunk) * kElem);
         }
     }
     // A workgroup whose tile lies inside the matrix, on examples that are whole stages long, never has
@@ -137,7 +146,7 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
     // last stage of an example.
     int fs = 0;                                                // stage within the example
     const int last_rows = a.T - (nst - 1) * kStageT;           // rows of an example's last stage (64 if whole)
-    const uint16_t *xs = a.x + (int64_t)b_begin * a.T * a.K + k0, *gs = a.g + (int64_t)b_begin * a.T * a.L + l0;
+    const char *xs = a.x + ((int64_t)b_begin * a.T * a.K + k0) * kElem, *gs = a.g + ((int64_t)b_begin * a.T * a.L + l0) * kElem;
     auto fetch = [&](int buf) {
         const uint32_t dst = lds_base + buf * kStageBytes + wave * kLoadsPerWave * 1024;
         if (regular) {
@@ -158,8 +167,8 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
             }
         }
         const int rows = fs == nst - 1 ? last_rows : kStageT;
-        xs += (int64_t)rows * a.K;
-        gs += (int64_t)rows * a.L;
+        xs += (int64_t)rows * a.K * kElem;
+        gs += (int64_t)rows * a.L * kElem;
         fs = fs == nst - 1 ? 0 : fs + 1;
     };
 
@@ -196,7 +205,7 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
     // current 16 start.  A block first waits for the reads issued by the block before it; the operands
     // those delivered are passed through it ("+v") so that no MFMA using them can be moved above the wait.
     static_assert(MI == 2 && NI == 2, "the read blocks below are written for 2 x 2 MFMA tiles per wave");
-    static_assert(kXRow == LIN_XROW && kGRow == LIN_GROW, "row pitches used in the assembly");
+    static_assert(kF32 || (kXRow == LIN_XROW && kGRow == LIN_GROW), "row pitches used in the assembly");
     typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
     struct Frags {
         u32x2_t a0l, a0h, a1l, a1h, b0l, b0h, b1l, b1h;
@@ -227,7 +236,7 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
             for (int ni = 0; ni < 2; ++ni)
                 acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb2[ni], acc[mi][ni], 0, 0, 0);
     };
-    auto multiply = [&](int buf, bool refill, int refill_buf) {
+    auto multiply_bf16 = [&](int buf, bool refill, int refill_buf) {
         const uint32_t base = lds_base + buf * kStageBytes;
         const uint32_t pa0 = base + a_addr[0], pa1 = base + a_addr[1], pb0 = base + b_addr[0], pb1 = base + b_addr[1];
         Frags f0, f1;
@@ -248,6 +257,42 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
 #undef LIN_READS
 #undef LIN_OUTS
 #undef LIN_KEEP
+    // fp32 operands (v_mfma_f32_32x32x2_f32: lane l holds row l%32 of A, column l%32 of B, position l/32 of
+    // the two): one element per lane straight off a row of the stage, no transposition and no swizzle;
+    // every read is one per-stage address plus an immediate.
+    typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+    typedef __attribute__((address_space(3))) float lds_float_t;
+    uint32_t fa_addr[MI], fb_addr[NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) fa_addr[i] = (lane >> 5) * kXRow + ((wm * MI + i) * 32 + (lane & 31)) * 4;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) fb_addr[i] = kXBytes + (lane >> 5) * kGRow + ((wn * NI + i) * 32 + (lane & 31)) * 4;
+    auto multiply_f32 = [&](int buf, bool refill, int refill_buf) {
+        const lds_byte_t *base = (const lds_byte_t *)lds + buf * kStageBytes;
+        const lds_byte_t *pa[MI], *pb[NI];
+#pragma unroll
+        for (int i = 0; i < MI; ++i) pa[i] = base + fa_addr[i];
+#pragma unroll
+        for (int i = 0; i < NI; ++i) pb[i] = base + fb_addr[i];
+#pragma unroll
+        for (int ks = 0; ks < kStageT / 2; ++ks) {
+            float fa[MI], fb2[NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) fa[i] = *(const lds_float_t *)(pa[i] + ks * 2 * kXRow);
+#pragma unroll
+            for (int i = 0; i < NI; ++i) fb2[i] = *(const lds_float_t *)(pb[i] + ks * 2 * kGRow);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[mi], fb2[ni], acc[mi][ni], 0, 0, 0);
+            if (ks == 1 && refill) fetch(refill_buf);          // stage st+2 goes out in the shadow of the MFMAs
+        }
+    };
+    auto multiply = [&](int buf, bool refill, int refill_buf) {
+        if constexpr (kF32) multiply_f32(buf, refill, refill_buf);
+        else multiply_bf16(buf, refill, refill_buf);
+    };
     int cb = b_begin, cs = 0;                                  // the stage being multiplied
     auto boundary = [&]() {
         if (++cs < nst) return;
@@ -314,9 +359,10 @@ __device__ __forceinline__ void linear_pegn_body(const LinArgs &a)
     }
 }
 
+template <int kElem>
 __global__ __launch_bounds__(Cfg::kThreads) void linear_pegn_kernel(LinArgs a)
 {
-    linear_pegn_body<Cfg, LIN_CFG>(a);
+    linear_pegn_body<LinCfg<LIN_CFG, kElem>, LIN_CFG, kElem>(a);
 }
 
 // Any shape, any alignment, fp32 or bf16: one thread per output (k,l), fp32 FMA over t, no MFMA.
@@ -404,7 +450,8 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 LinPlan make_lin_plan(int B, int T, int K, int L, int dt, bool aligned)
 {
     LinPlan p{};
-    p.mfma = dt == LNPEGN_BF16 && K % 8 == 0 && L % 8 == 0 && aligned;
+    const int per_chunk = dt == LNPEGN_BF16 ? 8 : 4;          // elements per 16-byte vector
+    p.mfma = K % per_chunk == 0 && L % per_chunk == 0 && aligned;
     if (p.mfma) {
         p.tiles_k = (K + Cfg::kTileK - 1) / Cfg::kTileK;
         p.tiles_l = (L + Cfg::kTileL - 1) / Cfg::kTileL;
@@ -470,15 +517,18 @@ int linear_pegn(const void *x, const void *g, float *w, float *s, float *big_sq,
     float *part_w = reinterpret_cast<float *>(ws + p.off_part);
     if (p.mfma) {
         LinArgs a{};
-        a.x = static_cast<const uint16_t *>(x);
-        a.g = static_cast<const uint16_t *>(g);
+        a.x = static_cast<const char *>(x);
+        a.g = static_cast<const char *>(g);
         a.out = p.nsplit > 1 ? part_w : w;
         a.tile_s = part_s;
         a.tile_big = part_big;
         a.B = B; a.T = T; a.K = K; a.L = L;
         a.tiles_k = p.tiles_k; a.tiles_l = p.tiles_l; a.nsplit = p.nsplit; a.b_per_split = p.b_per_split;
         a.accumulate = accumulate;
-        linear_pegn_kernel<<<dim3(p.tiles_k * p.tiles_l, p.nsplit), dim3(Cfg::kThreads), 0, st>>>(a);
+        if (dt == LNPEGN_BF16)
+            linear_pegn_kernel<2><<<dim3(p.tiles_k * p.tiles_l, p.nsplit), dim3(Cfg::kThreads), 0, st>>>(a);
+        else
+            linear_pegn_kernel<4><<<dim3(p.tiles_k * p.tiles_l, p.nsplit), dim3(Cfg::kThreads), 0, st>>>(a);
         if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
         if (p.nsplit > 1) {
             const int64_t n = (int64_t)K * L;

@@ -572,6 +572,22 @@ def test_linear_pegn_matrix_core_kernel(B, T, K, L):
     _check_linear(x, g, _run_linear(x, g, "bf16"))
 
 
+@pytest.mark.parametrize("B,T,K,L", [
+    (2, 32, 256, 128),        # one tile, one fp32 stage (32 positions)
+    (3, 70, 260, 132),        # ragged in T, K and L (multiples of 4, not of 8)
+    (1, 1, 4, 4),
+    (5, 96, 768, 768),
+    (2, 64, 4096, 2048),      # no split over examples
+    (3, 33, 4100, 2052),
+])
+def test_linear_pegn_matrix_core_kernel_fp32(B, T, K, L):
+    x, g = workloads.make_linear_inputs(B * 1000 + T + 1, B, T, K, L, "f32")
+    _check_linear(x, g, _run_linear(x, g, "f32"))
+    if K * L < 1 << 20:
+        w0 = np.random.default_rng(workloads.BASE_SEED + 80).normal(0, 1e-2, (K, L))
+        _check_linear(x, g, _run_linear(x, g, "f32", w0=w0), w0=w0)
+
+
 @pytest.mark.parametrize("B,T,K,L", [(3, 70, 264, 136), (2, 64, 4096, 2048)])
 def test_linear_pegn_accumulates_into_the_weight_gradient(B, T, K, L):
     x, g = workloads.make_linear_inputs(77, B, T, K, L, "bf16")
