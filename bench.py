@@ -156,6 +156,21 @@ def linear_leg(shape_name, steps, warmup, log):
     flops = 2.0 * B * T * K * L
     tf = flops / ms / 1e9
     est = binding.gns_estimate(s, big, float(B)).cpu().numpy().astype(float)
+    # the same layer with fp32 operands (fp32 matrix cores), a few calls
+    xf, gf = x.float(), g.float()
+    wsf = torch.empty(max(256, lib.linear_pegn_workspace_bytes(B, T, K, L, binding.F32)), dtype=torch.uint8,
+                      device="cuda")
+    ms_f32 = 0.0
+    for it in range(2 + 5):
+        if it == 2:
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+        binding.linear_pegn(xf, gf, w=w, s=s, big_sq=big, workspace=wsf)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_f32 = e0.elapsed_time(e1) / 5
+    del xf, gf, wsf
     log(f"linear_pegn {shape_name}: {ms:.3f} ms = {tf:.0f} TFLOP/s; plain bf16 GEMM {flops / ms_gemm / 1e9:.0f} TFLOP/s")
     return {
         "workload": f"{shape_name}: x [B={B},T={T},K={K}] g [B,T,L={L}] bf16 -> w' [K,L] fp32, s [B], ||w'||^2",
@@ -166,6 +181,8 @@ def linear_leg(shape_name, steps, warmup, log):
                      "algorithmic_flops_per_call": flops},
         "library_plain_gemm": {"what": "torch.mm(x^T, g) in bf16: the weight gradient alone, no per-example norms",
                                "ms_per_call": round(ms_gemm, 4), "TFLOPs": round(flops / ms_gemm / 1e9, 1)},
+        "fp32_operands": {"ms_per_call": round(ms_f32, 4), "TFLOPs": round(flops / ms_f32 / 1e9, 1),
+                          "peak": 157.3, "frac": round(flops / ms_f32 / 1e9 / 157.3, 4)},
         "B_simple_this_layer": est[4],
     }
 
