@@ -3,28 +3,33 @@
 //   s[b]     = sum_{v,d} w_b[v,d]^2               (step 3)
 //   w'[v,d]  = sum_b w_b[v,d]                     (step 4)
 // The positions p = b*T + t are sorted by id (stable, so positions ascend inside an id and the rows of one
-// example are adjacent): a "run" is the rows of one id in one example, a "segment" all runs of one id.
-// Kernel A gives every run to a wave (columns spread over its lanes): the run's sum, squared, is that
-// example's share of step 3; if the run is the id's only one it is also the row of w'.  Otherwise the sum is
-// parked in the workspace and kernel B adds an id's parked sums in example order (at most B of them).
-// Every row of g is read once, an id that fills half the batch still costs no wave more than one example's
-// worth of rows, and nothing is atomic: results are bitwise reproducible.
+// example are adjacent): a "run" is the rows of one id in one example, a "segment" all runs of one id, a
+// "piece" at most kPiece consecutive sorted positions of one run (a run is cut wherever the sorted index is a
+// multiple of kPiece).  Kernel A gives every piece to a wave (columns spread over its lanes).  A piece that
+// is a whole run yields that example's share of step 3 at once, and the row of w' too if the run is the id's
+// only one.  Every other sum is parked in the workspace and kernel B, one wave per id that has more than one
+// piece, adds the parked sums in sorted order: pieces into runs (squared: step 3), runs into the row of w'.
+// Every row of g is read once, no wave reads more than kChunk + kPiece rows however skewed the ids are, and
+// nothing is atomic: results are bitwise reproducible.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include <cstring>
+#include <mutex>
 #include <rocprim/device/device_radix_sort.hpp>
 
 #include "../../include/lnpegn.h"
 #include "lnpegn_device.h"
 
 namespace lnpegn {
+int g_emb_run_blocks = 4096;        // workgroups of kernel A per column group (each loops over its chunks)
 namespace {
 
 constexpr int kColBlock = 512;      // columns per wave: 8 per lane
-constexpr int kChunk = 8;           // sorted positions whose segment heads one wave looks after
+constexpr int kChunk = 16;          // sorted positions whose piece heads one wave looks after
+constexpr int kPiece = 32;          // longest piece; kChunk + kPiece + 1 lanes of one 64-lane window cover a wave's work
 constexpr int kWavesPerBlock = 4;
-constexpr int kNormBlocks = 1024;   // workgroups of the ||w'||^2 pass in accumulate mode
+constexpr int kNormBlocks = 2048;   // workgroups of the ||w'||^2 pass in accumulate mode
 
 __global__ __launch_bounds__(256) void emb_prepare_kernel(const void *ids, int ids_i64, uint32_t *keys,
                                                           uint32_t *vals, float *scratch, int64_t n,
@@ -39,9 +44,20 @@ __global__ __launch_bounds__(256) void emb_prepare_kernel(const void *ids, int i
     for (int64_t j = i; j < nscratch; j += (int64_t)gridDim.x * 256) scratch[j] = 0.f;
 }
 
+// Zero fill with streaming stores: the zeros are not wanted in any cache (the rows read next are g's), and
+// lines left dirty in the memory-side cache would be written back one by one under the reads that follow.
 __global__ __launch_bounds__(256) void emb_fill_kernel(float *p, int64_t n)
 {
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0.f;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if ((reinterpret_cast<uintptr_t>(p) & 15u) == 0) {
+        typedef __attribute__((ext_vector_type(4))) float f32x4;
+        f32x4 *p4 = reinterpret_cast<f32x4 *>(p);
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        for (; i < n / 4; i += stride) __builtin_nontemporal_store(zero, p4 + i);
+        i = (n / 4) * 4 + (int64_t)blockIdx.x * 256 + threadIdx.x;
+    }
+    for (; i < n; i += stride) p[i] = 0.f;
 }
 
 // eight columns of one row, added into sub: 16-byte loads when the row allows, element loads otherwise
@@ -113,8 +129,10 @@ __device__ __forceinline__ void add_row(const float *g, int64_t p, int D, int c0
 }
 
 // eight fp32 columns of a row: out[k] = (add ? row[k] : 0) + in[k], stored; returns the sum of squares
-__device__ __forceinline__ float put_row(float *row, const float (&in)[8], int c0, int D, bool add)
+// stream: the row will not be read again soon (a row of w'): streaming stores, kept out of the caches
+__device__ __forceinline__ float put_row(float *row, const float (&in)[8], int c0, int D, bool add, bool stream = false)
 {
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
     float sq = 0.f;
     if (c0 + 8 <= D && (reinterpret_cast<uintptr_t>(row) & 15u) == 0) {
         float4 lo = make_float4(in[0], in[1], in[2], in[3]), hi = make_float4(in[4], in[5], in[6], in[7]);
@@ -123,8 +141,13 @@ __device__ __forceinline__ float put_row(float *row, const float (&in)[8], int c
             lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
             hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
         }
-        *reinterpret_cast<float4 *>(row) = lo;
-        *reinterpret_cast<float4 *>(row + 4) = hi;
+        if (stream) {
+            __builtin_nontemporal_store(f32x4{lo.x, lo.y, lo.z, lo.w}, reinterpret_cast<f32x4 *>(row));
+            __builtin_nontemporal_store(f32x4{hi.x, hi.y, hi.z, hi.w}, reinterpret_cast<f32x4 *>(row + 4));
+        } else {
+            *reinterpret_cast<float4 *>(row) = lo;
+            *reinterpret_cast<float4 *>(row + 4) = hi;
+        }
         sq = lo.x * lo.x + lo.y * lo.y + lo.z * lo.z + lo.w * lo.w + hi.x * hi.x + hi.y * hi.y + hi.z * hi.z + hi.w * hi.w;
     } else {
 #pragma unroll
@@ -164,136 +187,276 @@ __device__ __forceinline__ int leading(bool pred)
     return not_pred ? __builtin_ctzll(not_pred) : 64;
 }
 
-// Kernel A.  keys/vals: positions sorted by id.  A wave looks after the runs whose first row is among its
-// kChunk sorted positions, and streams their rows eight at a time in sorted order, closing a run wherever
-// the next position starts another.  contrib [ncb][n]: the run's share of s[b], stored at the run's first
-// position, zero elsewhere.  runsum [n][D]: the sums of runs that are not their id's only run, at the same
-// index.  bigpart [ncb][n]: squared norm of a finished row of w', at the segment's first position (not
-// when accumulating).
-template <typename T>
+// element u (wave-uniform, known at run time) of an array that lives in registers: a switch, so that the array
+// is never indexed by a variable (which would move it to scratch memory)
+template <typename R>
+__device__ __forceinline__ R pick_row(const R (&a)[16], int u)
+{
+    switch (u) {
+        case 0: return a[0];   case 1: return a[1];   case 2: return a[2];   case 3: return a[3];
+        case 4: return a[4];   case 5: return a[5];   case 6: return a[6];   case 7: return a[7];
+        case 8: return a[8];   case 9: return a[9];   case 10: return a[10]; case 11: return a[11];
+        case 12: return a[12]; case 13: return a[13]; case 14: return a[14]; default: return a[15];
+    }
+}
+template <typename R>
+__device__ __forceinline__ R pick_row(const R (&a)[8], int u)
+{
+    switch (u) {
+        case 0: return a[0]; case 1: return a[1]; case 2: return a[2]; case 3: return a[3];
+        case 4: return a[4]; case 5: return a[5]; case 6: return a[6]; default: return a[7];
+    }
+}
+template <typename R>
+__device__ __forceinline__ R pick_row(const R (&a)[1], int)
+{
+    return a[0];
+}
+template <int N>
+__device__ __forceinline__ void pick_floats(const float (&a)[N][8], int u, float (&f)[8])
+{
+#pragma unroll
+    for (int k = 0; k < 8; ++k) f[k] = a[0][k];
+#pragma unroll
+    for (int j = 1; j < N; ++j)
+        if (u == j) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) f[k] = a[j][k];
+        }
+}
+
+// Kernel A.  keys/vals: positions sorted by id.  Ownership: a short segment (at most kShort positions)
+// belongs whole to the wave whose kChunk sorted positions hold its first one, and that wave finishes the id
+// (every run's share of s[b], the row of w').  A longer segment is handed out piece by piece to the waves
+// whose positions hold the pieces' first rows; a piece that is a whole run yields that run's share of s[b],
+// every sum is parked (unless the piece is the id's only one) and the id is marked for kernel B.
+// A wave sees kShort positions back (to tell whether a piece in its chunk belongs to a short segment that an
+// earlier wave owns) and far enough ahead for anything that starts in its chunk; rows are streamed eight at
+// a time.  contrib [ncb][n]: a run's share of s[b], at the run's first position, zero elsewhere.
+// runsum [n][D]: parked sums, at the piece's first position.  multi [n]: set at the sorted index of the first
+// position of a long id that has parked sums; multi_run [n]: of a run that has several pieces.  bigpart [ncb][n]: squared norm of a finished row of w', at the segment's first
+// position (not when accumulating).
+constexpr int kShort = 12;
+static_assert(kShort + kChunk + kPiece < 63 && kShort + kChunk + kShort < 63, "one 64-lane window must cover a wave's work");
+
+// kVec: every lane that has columns has eight whole ones behind an aligned 16-byte boundary (D % 8 == 0 and
+// aligned rows); rows are then fetched as vectors, sixteen bf16 rows or eight fp32 rows in flight.
+template <typename T, bool kVec>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void emb_runs_kernel(
     const T *g, const uint32_t *keys, const uint32_t *vals, float *w, float *runsum, float *contrib, float *bigpart,
-    int64_t n, int Tn, int D, int V, int accumulate, int vec_ok)
+    uint32_t *multi, uint32_t *multi_run, int64_t n, int Tn, int D, int V, int accumulate)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // the waves of a workgroup take the same positions and neighbouring column blocks: a row of g is then
     // read whole by one workgroup at one time
-    const int64_t i0 = (int64_t)blockIdx.x * kChunk;
     const int cb = blockIdx.y * kWavesPerBlock + wave, c0 = cb * kColBlock + lane * 8;
-    if (i0 >= n || cb * kColBlock >= D) return;
+    if (cb * kColBlock >= D) return;
     const bool has_cols = c0 < D;
-    const bool vec = vec_ok && c0 + 8 <= D;
-    float sub[8];
+    const int c_load = has_cols ? c0 : 0;                        // lanes without columns fetch what lane 0 does
+    constexpr int kRows = kVec && sizeof(T) == 2 ? 16 : 8;       // rows in flight
+    // A workgroup takes chunks blockIdx.x, blockIdx.x + gridDim.x, ...; the next chunk's part of the sorted list
+    // is fetched while this chunk's rows are on their way.
+    // Lane l looks at sorted position i0 - kShort - 1 + l: lane 0 only serves as "the position before",
+    // lanes kShort+1 .. kShort+kChunk are the chunk.
+    const int64_t nchunks = (n + kChunk - 1) / kChunk;
+    auto look = [&](int64_t chunk, uint32_t &k, uint32_t &p) {
+        const int64_t q = chunk * kChunk - kShort - 1 + lane;
+        const bool in = chunk < nchunks && q >= 0 && q < n;
+        k = in ? keys[q] : 0xffffffffu;
+        p = in ? vals[q] : 0u;
+    };
+    uint32_t key_next, val_next;
+    look(blockIdx.x, key_next, val_next);
+    for (int64_t chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
+    const int64_t i0 = chunk * kChunk;
+    const int64_t q = i0 - kShort - 1 + lane;
+    const uint32_t key = key_next, val = val_next;
+    look(chunk + gridDim.x, key_next, val_next);
+    const uint32_t ex = val / (uint32_t)Tn;
+    const uint32_t pkey = (uint32_t)__shfl_up((int)key, 1), pex = (uint32_t)__shfl_up((int)ex, 1);
+    const bool valid = key < (uint32_t)V;
+    const uint64_t m_valid = __ballot(valid);
+    const uint64_t m_head = __ballot(valid && lane >= 1 && (key != pkey || ex != pex));     // starts a run
+    const uint64_t m_seg = __ballot(valid && lane >= 1 && key != pkey);                     // starts a segment
+    const uint64_t m_piece = m_head | __ballot(valid && lane >= 1 && q % kPiece == 0);      // starts a piece
+    // is this lane's segment long?  Its first position is the nearest segment head at or below the lane
+    // (not in the window: it lies more than kShort back), its end the next segment head or invalid key
+    // (not in the window: more than kShort ahead of anything this wave may own).
+    const uint64_t upto = ((uint64_t)2 << lane) - 1;
+    const uint64_t heads_below = m_seg & upto, ends_above = (m_seg | ~m_valid) & ~upto;
+    const int seg_first = heads_below ? 63 - __builtin_clzll(heads_below) : -1;
+    const int seg_end = ends_above ? __builtin_ctzll(ends_above) : 64;
+    const uint64_t m_long = __ballot(valid && (seg_first < 0 || seg_end - seg_first > kShort));
+    const uint64_t m_own = m_seg | (m_piece & m_long);                                      // starts something to own
+    const uint64_t chunk_lanes = (((uint64_t)1 << kChunk) - 1) << (kShort + 1);
+    if (!(m_own & chunk_lanes)) continue;                        // nothing starts here
+    const int l = __builtin_ctzll(m_own & chunk_lanes);
+    // rows l .. e-1: up to the first invalid key or the first thing that starts behind the chunk
+    const uint64_t behind = ~(((uint64_t)2 << (kShort + kChunk)) - 1);
+    const uint64_t stop = (~m_valid & ~(((uint64_t)2 << l) - 1)) | (m_own & behind);
+    int e = stop ? __builtin_ctzll(stop) : 63;
+    if (e > 63) e = 63;
+
+    // What happens at a row, as masks over the lanes: the masks are shifted so that bit u is row r + u of the
+    // batch in hand, and a batch in which nothing happens is plain additions.
+    const uint64_t next_starts_run = (m_head | ~m_valid) >> 1, next_starts_seg = (m_seg | ~m_valid) >> 1;
+    const uint64_t next_starts_piece = (m_piece | ~m_valid) >> 1;
+    uint64_t b_opens_id = m_seg >> l;                                        // first row of an id
+    uint64_t b_opens = ((m_long & m_piece) | (~m_long & m_head)) >> l;       // first row of a long id's piece, or of a run
+    uint64_t b_run_head = m_head >> l;
+    uint64_t b_short_run_ends = (~m_long & next_starts_run) >> l;            // last row of a short id's run
+    uint64_t b_piece_ends = (m_long & next_starts_piece) >> l;               // last row of a long id's piece
+    uint64_t b_run_ends = next_starts_run >> l, b_seg_ends = next_starts_seg >> l;
+
+    float sub[8], tot[8];                // the open run or piece; the short id's runs so far
 #pragma unroll
-    for (int k = 0; k < 8; ++k) sub[k] = 0.f;
-    bool in_run = false;                 // a run of this wave is open (its sum so far is in sub)
-    uint32_t cur_first = 0, cur_key = 0;
-    bool cur_seg_head = false;
-    int64_t pos = i0;                    // next sorted position to look at
-    while (true) {
-        // lane l looks at sorted position pos - 1 + l: lane 0 is the position before, lanes 1..62 are
-        // handled in this round, lane 63 is only looked at as "what follows lane 62"
-        const int64_t q = pos - 1 + lane;
-        const bool in = q >= 0 && q < n;
-        const uint32_t key = in ? keys[q] : 0xffffffffu, val = in ? vals[q] : 0u;
-        const uint32_t ex = val / (uint32_t)Tn;
-        const uint32_t pkey = (uint32_t)__shfl_up((int)key, 1), pex = (uint32_t)__shfl_up((int)ex, 1);
-        const bool valid = key < (uint32_t)V;
-        const uint64_t m_valid = __ballot(valid);
-        const uint64_t m_head = __ballot(valid && lane >= 1 && (key != pkey || ex != pex));     // starts a run
-        const uint64_t m_seg = __ballot(valid && lane >= 1 && key != pkey);                     // starts a segment
-        // the lanes this wave handles now: from the first run head of its chunk (or lane 1 if a run is
-        // open) up to the lane before the first head that belongs to a later chunk, an invalid key, or 63
-        const int64_t chunk_end = i0 + kChunk;
-        int l = 1;
-        if (!in_run) {
-            const uint64_t h = m_head & ~(uint64_t)1;
-            if (!h) {
-                // no run starts in this round; rows seen belong to a run of an earlier chunk
-                if (!(m_valid >> 62 & 1) || pos - 1 + 62 >= chunk_end) return;
-                pos += 62;
-                continue;
+    for (int k = 0; k < 8; ++k) sub[k] = tot[k] = 0.f;
+    uint32_t first = 0, cur_key = 0, first_idx = 0, id_first = 0;
+    bool run_head = false, seg_head = false;
+    // kRows rows in flight: the loads carry no condition (a row past the end repeats the last one and is
+    // dropped afterwards), so that all are issued before the first is waited for
+    for (int r = l; r < e; r += kRows) {
+        Row8<T> raw[kVec ? kRows : 1];
+        float part[kVec ? 1 : kRows][8];
+        if constexpr (kVec) {
+#pragma unroll
+            for (int u = 0; u < kRows; ++u) {
+                const int t = r + u < e ? r + u : e - 1;
+                raw[u] = load_row8(g, (int64_t)lane_value(val, t), D, c_load);
             }
-            l = __builtin_ctzll(h);
-            if (pos - 1 + l >= chunk_end) return;
-        }
-        // end: first lane >= l that is invalid, or a head at a position >= chunk_end
-        int e = l;
-        while (e <= 62) {
-            if (!(m_valid >> e & 1)) break;
-            if ((m_head >> e & 1) && pos - 1 + e >= chunk_end) break;
-            ++e;
-        }
-        // rows l .. e-1, eight in flight: the loads carry no condition (a row past the end repeats the last
-        // one and is dropped afterwards), so that all eight are issued before the first is waited for
-        for (int r = l; r < e; r += 8) {
-            float part[8][8];
+        } else {                                                 // ragged or unaligned columns: element loads
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < kRows; ++u) {
 #pragma unroll
                 for (int k = 0; k < 8; ++k) part[u][k] = 0.f;
-            if (vec) {                                           // lanes whose eight columns are a whole vector
-                Row8<T> raw[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int t = r + u < e ? r + u : e - 1;
-                    raw[u] = load_row8(g, (int64_t)lane_value(val, t), D, c0);
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) unpack_row8(raw[u], part[u]);
-            } else if (has_cols) {                               // ragged or unaligned columns: element loads
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (r + u < e) add_row(g, (int64_t)lane_value(val, r + u), D, c0, false, part[u]);
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int t = r + u;
-                if (t >= e) break;
-                if (m_head >> t & 1) {                           // this row opens a run
-                    in_run = true;
-                    cur_first = lane_value(val, t);
-                    cur_key = lane_value(key, t);
-                    cur_seg_head = (m_seg >> t & 1) != 0;
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) sub[k] = 0.f;
-                }
-#pragma unroll
-                for (int k = 0; k < 8; ++k) sub[k] += part[u][k];
-                // the run ends here if the next position is invalid or opens another run; lane 63's
-                // successor is unknown, which is why lane 62 is the last one handled in a round
-                const bool next_valid = (m_valid >> (t + 1) & 1) != 0;
-                if (next_valid && !(m_head >> (t + 1) & 1)) continue;
-                const uint32_t next_key = next_valid ? lane_value(key, t + 1) : 0xffffffffu;
-                float sq = 0.f;
-#pragma unroll
-                for (int k = 0; k < 8; ++k) sq = fmaf(sub[k], sub[k], sq);
-                sq = wave_sum(sq);
-                if (lane == 0) contrib[(int64_t)cb * n + cur_first] = sq;
-                if (cur_seg_head && next_key != cur_key) {      // the id's only run: this is the row of w'
-                    float wsq = has_cols ? put_row(w + (int64_t)cur_key * D + c0, sub, c0, D, accumulate != 0) : 0.f;
-                    if (!accumulate) {
-                        wsq = wave_sum(wsq);
-                        if (lane == 0) bigpart[(int64_t)cb * n + cur_first] = wsq;
-                    }
-                } else if (has_cols) {
-                    put_row(runsum + (int64_t)cur_first * D + c0, sub, c0, D, false);
-                }
-                in_run = false;
+                if (has_cols && r + u < e) add_row(g, (int64_t)lane_value(val, r + u), D, c0, false, part[u]);
             }
         }
-        if (e <= 62) return;              // stopped at an invalid key or at a later chunk's run
-        pos += 62;                        // lane 62 was the last handled: it becomes lane 0 of the next round
+        auto row = [&](int u, float (&f)[8]) {
+            if constexpr (kVec) {
+                unpack_row8(raw[u], f);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) f[k] = part[u][k];
+            }
+        };
+        const int rows = e - r < kRows ? e - r : kRows;
+        const uint32_t in_batch = (1u << rows) - 1u;
+        if (!((uint32_t)(b_opens | b_short_run_ends | b_piece_ends) & in_batch)) {
+#pragma unroll
+            for (int u = 0; u < kRows; ++u)
+                if (u < rows) {
+                    float f[8];
+                    row(u, f);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) sub[k] += f[k];
+                }
+            b_opens_id >>= kRows; b_opens >>= kRows; b_run_head >>= kRows; b_short_run_ends >>= kRows;
+            b_piece_ends >>= kRows; b_run_ends >>= kRows; b_seg_ends >>= kRows;
+            continue;
+        }
+        // Something opens or closes in this batch: one row at a time, in a loop that is not unrolled (its body,
+        // sixteen times over, would not fit the instruction cache); bit 0 of every mask is the row in hand.
+#pragma nounroll
+        for (int u = 0; u < rows; ++u) {
+            const int t = r + u;
+            float f[8];
+            if constexpr (kVec) {
+                unpack_row8(pick_row(raw, u), f);
+            } else {
+                pick_floats(part, u, f);
+            }
+            if (b_opens_id & 1) {                                // this row opens an id
+                id_first = lane_value(val, t);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) tot[k] = 0.f;
+            }
+            if (b_opens & 1) {                                   // ... a piece of a long id, or a run
+                first = lane_value(val, t);
+                first_idx = (uint32_t)(i0 - kShort - 1 + t);
+                cur_key = lane_value(key, t);
+                run_head = (b_run_head & 1) != 0;
+                seg_head = (b_opens_id & 1) != 0;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) sub[k] = 0.f;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) sub[k] += f[k];
+            const bool short_run_ends = (b_short_run_ends & 1) != 0, piece_ends = (b_piece_ends & 1) != 0;
+            if (short_run_ends || piece_ends) {
+                const bool seg_end_here = (b_seg_ends & 1) != 0, run_end_here = (b_run_ends & 1) != 0;
+                // a short id's run: its share of s[b] now, the row of w' when the id is complete.  A long id's
+                // piece: the share of s[b] if it is a whole run, the row of w' if it is the id's only piece,
+                // parked otherwise.
+                const bool whole_run = short_run_ends || (run_head && run_end_here);
+                const bool to_w = short_run_ends ? seg_end_here : (whole_run && seg_head && seg_end_here);
+                const bool park = piece_ends && !to_w;
+                float sq = 0.f, wsq = 0.f, out[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    sq = fmaf(sub[k], sub[k], sq);
+                    if (short_run_ends) tot[k] += sub[k];
+                    out[k] = short_run_ends ? tot[k] : sub[k];
+                }
+                if (!has_cols) sq = 0.f;                         // such lanes hold a copy of lane 0's columns
+                if (has_cols && (to_w || park)) {
+                    float *dst = to_w ? w + (int64_t)cur_key * D + c0 : runsum + (int64_t)first * D + c0;
+                    wsq = put_row(dst, out, c0, D, to_w && accumulate != 0, to_w);
+                }
+                if (whole_run) {
+                    wave_sum2(sq, wsq);                          // one exchange for both
+                    if (lane == 0) {
+                        contrib[(int64_t)cb * n + first] = sq;
+                        if (to_w && !accumulate) bigpart[(int64_t)cb * n + (short_run_ends ? id_first : first)] = wsq;
+                    }
+                }
+                if (park && cb == 0 && lane == 0) {
+                    if (seg_head) multi[first_idx] = 1u;
+                    if (run_head && !run_end_here) multi_run[first_idx] = 1u;
+                }
+            }
+            b_opens_id >>= 1; b_opens >>= 1; b_run_head >>= 1; b_short_run_ends >>= 1;
+            b_piece_ends >>= 1; b_run_ends >>= 1; b_seg_ends >>= 1;
+        }
     }
+    }   // chunks
 }
 
-// Kernel B.  A wave looks after the segments (ids) whose first row is among its kChunk sorted positions and
-// that have more than one run: the row of w' is the sum of the runs' parked sums, in example order.
-__global__ __launch_bounds__(64 * kWavesPerBlock) void emb_ids_kernel(
-    const uint32_t *keys, const uint32_t *vals, float *w, const float *runsum, float *bigpart, int64_t n, int Tn,
-    int D, int V, int accumulate)
+// First index in [lo, n) whose (id, position) pair is not below (v, target); every lane searches for its own
+// target, the loop runs until the slowest lane is done (about log2(n) dependent loads).
+__device__ __forceinline__ int64_t lower_bound_pair(const uint32_t *keys, const uint32_t *vals, int64_t lo, int64_t n,
+                                                    uint32_t v, uint32_t target)
 {
+    int64_t len = n - lo;
+    while (__any(len > 0)) {
+        const int64_t half = len >> 1, m = lo + half;
+        bool below = false;
+        if (len > 0) {
+            const uint32_t k = keys[m], p = vals[m];
+            below = k < v || (k == v && p < target);
+        }
+        lo = below ? m + 1 : lo;
+        len = below ? len - half - 1 : half;
+    }
+    return lo;
+}
+
+// Kernel B, two launches.  First per run (kIds = false): a wave looks after the runs of long ids whose first
+// sorted position is among its kChunk positions and that kernel A marked as having several pieces; it adds
+// the run's parked piece sums in sorted order, squares the result (the run's share of s[b]) and parks it in
+// place of the run's first piece.  Then per id (kIds = true): a wave looks after the long ids whose first
+// sorted position is among its positions and adds the parked run sums in example order: the row of w'.
+// Neither walks the positions: the sorted list is searched.  A run's pieces start at its first position and
+// at every multiple of kPiece below the run's end, which one search finds; an id's runs start where the
+// searches for (id, b*T), one example per lane, land on that id and example.  The cost is logarithmic in
+// the number of positions however long the id is.  Parked sums are loaded sixteen at a time.
+template <bool kIds>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void emb_sums_kernel(
+    const uint32_t *keys, const uint32_t *vals, float *w, float *runsum, float *contrib, float *bigpart,
+    const uint32_t *marks_at, int64_t n, int Tn, int D, int V, int accumulate)
+{
+    constexpr int kBatch = 16;                                   // parked sums in flight
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t i0 = (int64_t)blockIdx.x * kChunk;
@@ -301,56 +464,106 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void emb_ids_kernel(
     if (cb * kColBlock >= D) return;
     const bool has_cols = c0 < D;
     const bool runsum_vec = c0 + 8 <= D && D % 4 == 0 && (reinterpret_cast<uintptr_t>(runsum) & 15u) == 0;
-    for (int64_t i = i0; i < i0 + kChunk && i < n; ++i) {
-        const uint32_t v = keys[i];
-        if (v >= (uint32_t)V) break;
-        if (i > 0 && keys[i - 1] == v) continue;                // not the head of a segment
-        float tot[8];
+    const int Bn = (int)(n / Tn);
+    uint64_t marks = __ballot(lane < kChunk && i0 + lane < n && marks_at[i0 + lane < n ? i0 + lane : 0] != 0u);
+    while (marks) {
+        const int64_t i = i0 + __builtin_ctzll(marks);
+        marks &= marks - 1;
+        const uint32_t v = keys[i], p0 = vals[i], ex0 = p0 / (uint32_t)Tn;
+        float acc[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) tot[k] = 0.f;
-        // first the number of runs (positions only); an id with one run was finished by kernel A
-        int runs = 0;
-        for (int pass = 0; pass < 2; ++pass) {
-            if (pass == 1 && runs < 2) break;
-            int64_t j = i;
-            uint32_t prev_ex = 0xffffffffu;                      // example of the position before the window
-            int len;
-            do {
-                const Window win = window_at(keys, vals, j, n, Tn, lane);
-                len = leading(win.key == v);
-                // a position heads a run if the one before it belongs to another example
-                uint32_t before = (uint32_t)__shfl_up((int)win.ex, 1);
-                if (lane == 0) before = prev_ex;
-                uint64_t heads = __ballot(lane < len && win.ex != before);
-                if (pass == 0) {
-                    runs += __popcll(heads);
-                } else {
-                    while (heads) {                              // parked sums, in example order
-                        const int r = __builtin_ctzll(heads);
-                        heads &= heads - 1;
-                        if (has_cols) add_row(runsum, (int64_t)lane_value(win.val, r), D, c0, runsum_vec, tot);
+        for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+        // the parked sums at the positions held by the lanes of `take`, in lane order
+        auto add_parked = [&](uint64_t take, uint32_t pos) {
+            while (take) {
+                uint32_t ent[kBatch];                            // all loads first, then the additions in order
+                int cnt = 0;
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    if (take) {
+                        ent[u] = lane_value(pos, __builtin_ctzll(take));
+                        take &= take - 1;
+                        ++cnt;
+                    } else {
+                        ent[u] = ent[u > 0 ? u - 1 : 0];
                     }
                 }
-                if (len > 0) prev_ex = lane_value(win.ex, len - 1);
-                j += len;
-            } while (len == 64);
-        }
-        if (runs < 2) continue;
-        float wsq = has_cols ? put_row(w + (int64_t)v * D + c0, tot, c0, D, accumulate != 0) : 0.f;
-        if (!accumulate) {
-            wsq = wave_sum(wsq);
-            if (lane == 0) bigpart[(int64_t)cb * n + vals[i]] = wsq;
+                float add[kBatch][8];
+                if (runsum_vec) {
+                    Row8<float> raw[kBatch];
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) raw[u] = load_row8(runsum, (int64_t)ent[u], D, c0);
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) unpack_row8(raw[u], add[u]);
+                } else {
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) {
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) add[u][k] = 0.f;
+                        if (has_cols && u < cnt) add_row(runsum, (int64_t)ent[u], D, c0, false, add[u]);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u)
+                    if (u < cnt) {
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) acc[k] += add[u][k];
+                    }
+            }
+        };
+        if constexpr (kIds) {
+            for (int b0 = 0; b0 < Bn; b0 += 64) {
+                const int b = b0 + lane;
+                const uint32_t target = (uint32_t)(b < Bn ? b : 0) * (uint32_t)Tn;
+                const int64_t at = lower_bound_pair(keys, vals, i, n, v, target);
+                const uint32_t k = at < n ? keys[at] : 0xffffffffu, pos = at < n ? vals[at] : 0u;
+                add_parked(__ballot(b < Bn && k == v && pos - target < (uint32_t)Tn), pos);
+            }
+            float wsq = has_cols ? put_row(w + (int64_t)v * D + c0, acc, c0, D, accumulate != 0, true) : 0.f;
+            if (!accumulate) {
+                wsq = wave_sum(wsq);
+                if (lane == 0) bigpart[(int64_t)cb * n + p0] = wsq;
+            }
+        } else {
+            const int64_t end = lower_bound_pair(keys, vals, i, n, v, (ex0 + 1u) * (uint32_t)Tn);
+            const int64_t h1 = (i / kPiece + 1) * kPiece;        // the run's second piece, if it gets that far
+            const int64_t npieces = 1 + (end > h1 ? (end - h1 + kPiece - 1) / kPiece : 0);
+            for (int64_t u0 = 0; u0 < npieces; u0 += 64) {
+                const int64_t u = u0 + lane, at = u == 0 ? i : h1 + (u - 1) * kPiece;
+                const bool ok = u < npieces;
+                add_parked(__ballot(ok), ok ? vals[at] : 0u);
+            }
+            float sq = has_cols ? put_row(runsum + (int64_t)p0 * D + c0, acc, c0, D, false) : 0.f;
+            sq = wave_sum(sq);
+            if (lane == 0) contrib[(int64_t)cb * n + p0] = sq;
         }
     }
 }
 
-// partial sums of squares of w (accumulate mode: every row counts, not only those touched)
+// partial sums of squares of w (accumulate mode: every row counts, not only those touched).  Four 16-byte
+// loads in flight per thread; every thread's own order of additions is fixed.
 __global__ __launch_bounds__(256) void emb_wnorm_kernel(const float *w, int64_t n, double *part)
 {
     __shared__ double slots[4];
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     double t = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
-        t += (double)w[i] * (double)w[i];
+    if ((reinterpret_cast<uintptr_t>(w) & 15u) == 0) {
+        const float4 *w4 = reinterpret_cast<const float4 *>(w);
+        const int64_t n4 = n / 4;
+        double t1 = 0.0, t2 = 0.0, t3 = 0.0;
+        auto sq4 = [](const float4 &v) {
+            return (double)v.x * v.x + (double)v.y * v.y + (double)v.z * v.z + (double)v.w * v.w;
+        };
+        for (; i + 3 * stride < n4; i += 4 * stride) {
+            const float4 a = w4[i], b = w4[i + stride], c = w4[i + 2 * stride], d = w4[i + 3 * stride];
+            t += sq4(a); t1 += sq4(b); t2 += sq4(c); t3 += sq4(d);
+        }
+        for (; i < n4; i += stride) t += sq4(w4[i]);
+        t = (t + t1) + (t2 + t3);
+        i = n4 * 4 + (int64_t)blockIdx.x * 256 + threadIdx.x;
+    }
+    for (; i < n; i += stride) t += (double)w[i] * (double)w[i];
     t = block_sum_f64(t, slots);
     if (threadIdx.x == 0) part[blockIdx.x] = t;
 }
@@ -372,17 +585,18 @@ __global__ __launch_bounds__(1024) void emb_final_kernel(const float *contrib, c
         if (wpart) {
             for (int i = threadIdx.x; i < nwpart; i += 1024) t += wpart[i];
         } else {
-            double t1 = 0.0, t2 = 0.0, t3 = 0.0;               // four loads in flight; the order stays fixed
+            double part[16];                                     // sixteen loads in flight; the order stays fixed
+#pragma unroll
+            for (int u = 0; u < 16; ++u) part[u] = 0.0;
             const int64_t m = (int64_t)ncb * n;
             int64_t i = threadIdx.x;
-            for (; i + 3072 < m; i += 4096) {
-                t += (double)bigpart[i];
-                t1 += (double)bigpart[i + 1024];
-                t2 += (double)bigpart[i + 2048];
-                t3 += (double)bigpart[i + 3072];
+            for (; i + 15 * 1024 < m; i += 16 * 1024) {
+#pragma unroll
+                for (int u = 0; u < 16; ++u) part[u] += (double)bigpart[i + u * 1024];
             }
-            for (; i < m; i += 1024) t += (double)bigpart[i];
-            t = (t + t1) + (t2 + t3);
+            for (; i < m; i += 1024) part[0] += (double)bigpart[i];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) t += part[u];
         }
         t = block_sum_f64(t, slots);
         if (threadIdx.x == 0) big_sq[0] = (float)t;
@@ -390,6 +604,40 @@ __global__ __launch_bounds__(1024) void emb_final_kernel(const float *contrib, c
 }
 
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+
+// The zero fill of w' (bandwidth bound) has nothing to do with the sort (a dozen tiny launches): it runs on a
+// side stream of the library's own, forked from and joined to the caller's stream with events, so the two
+// overlap.  One side stream and event pair per device, made at the first call there and kept; calls that
+// share a device share them (the events order each call's fill with that call's own work).
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+};
+constexpr int kMaxDevices = 64;
+SideStream g_side[kMaxDevices];
+std::mutex g_side_mutex;
+
+SideStream *side_stream()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_side_mutex);
+    SideStream &s = g_side[dev];
+    if (!s.stream) {
+        hipStream_t st = nullptr;
+        hipEvent_t a = nullptr, b = nullptr;
+        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return nullptr;   // default priority
+        if (hipEventCreateWithFlags(&a, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&b, hipEventDisableTiming) != hipSuccess) {
+            (void)hipStreamDestroy(st);
+            if (a) (void)hipEventDestroy(a);
+            return nullptr;
+        }
+        s.stream = st; s.fork = a; s.join = b;
+    }
+    return &s;
+}
 
 int key_bits(int V)
 {
@@ -401,7 +649,7 @@ int key_bits(int V)
 struct EmbPlan {
     int64_t n;
     int ncb;
-    size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_contrib, off_bigpart, off_wpart, off_temp, off_runsum;
+    size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_contrib, off_bigpart, off_multi, off_multi_run, off_wpart, off_temp, off_runsum;
     size_t temp_bytes, bytes;
 };
 
@@ -426,8 +674,10 @@ hipError_t make_emb_plan(int B, int T, int D, int V, EmbPlan &p)
     p.off_vals_in = p.off_keys_out + arr;
     p.off_vals_out = p.off_vals_in + arr;
     p.off_contrib = p.off_vals_out + arr;
-    p.off_bigpart = p.off_contrib + f;            // directly behind contrib: one fill clears both
-    p.off_wpart = p.off_bigpart + f;
+    p.off_bigpart = p.off_contrib + f;            // directly behind contrib, the marks behind that: one fill
+    p.off_multi = p.off_bigpart + f;              // clears all three
+    p.off_multi_run = p.off_multi + arr;
+    p.off_wpart = p.off_multi_run + arr;
     p.off_temp = p.off_wpart + align256(kNormBlocks * sizeof(double));
     p.temp_bytes = temp;
     p.off_runsum = p.off_temp + align256(temp);
@@ -468,8 +718,25 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
     uint32_t *vals_out = reinterpret_cast<uint32_t *>(ws + p.off_vals_out);
     float *contrib = reinterpret_cast<float *>(ws + p.off_contrib);
     float *bigpart = reinterpret_cast<float *>(ws + p.off_bigpart);
+    uint32_t *multi = reinterpret_cast<uint32_t *>(ws + p.off_multi);
+    uint32_t *multi_run = reinterpret_cast<uint32_t *>(ws + p.off_multi_run);
     double *wpart = reinterpret_cast<double *>(ws + p.off_wpart);
     const int64_t nscratch = (int64_t)((p.off_wpart - p.off_contrib) / sizeof(float));
+    // fork: the fill starts now on the side stream (on the caller's stream if there is none)
+    SideStream *side = accumulate ? nullptr : side_stream();
+    if (!accumulate) {
+        hipStream_t fs = st;
+        if (side) {
+            if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
+                return LNPEGN_EHIP;
+            fs = side->stream;
+        }
+        const int64_t nw = (int64_t)V * D;
+        const unsigned fb = (unsigned)(nw / 256 / 8 + 1 < 65536 ? nw / 256 / 8 + 1 : 65536);
+        emb_fill_kernel<<<dim3(fb), dim3(256), 0, fs>>>(w, nw);
+        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        if (side && hipEventRecord(side->join, fs) != hipSuccess) return LNPEGN_EHIP;
+    }
     const unsigned nblk = (unsigned)((p.n + 255) / 256);
     emb_prepare_kernel<<<dim3(nblk), dim3(256), 0, st>>>(ids, ids_are_int64, keys_in, vals_in, contrib, p.n, nscratch, V);
     if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
@@ -477,28 +744,32 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
     if (rocprim::radix_sort_pairs(ws + p.off_temp, temp, keys_in, keys_out, vals_in, vals_out, (size_t)p.n, 0,
                                   key_bits(V), st) != hipSuccess)
         return LNPEGN_EHIP;
-    if (!accumulate) {
-        const int64_t nw = (int64_t)V * D;
-        const unsigned fb = (unsigned)(nw / 256 / 8 + 1 < 65536 ? nw / 256 / 8 + 1 : 65536);
-        emb_fill_kernel<<<dim3(fb), dim3(256), 0, st>>>(w, nw);
-        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
-    }
+    // join: the rows of w' are written from here on
+    if (side && hipStreamWaitEvent(st, side->join, 0) != hipSuccess) return LNPEGN_EHIP;
     const int esz = dt == LNPEGN_BF16 ? 2 : 4;
     // 8 columns per lane: 16 bytes of bf16, 32 bytes of fp32; rows must keep that alignment
     const int vec_ok = ((reinterpret_cast<uintptr_t>(g) & 15u) == 0 && ((int64_t)D * esz) % 16 == 0) ? 1 : 0;
     const dim3 grid((unsigned)((p.n + kChunk - 1) / kChunk), (unsigned)((p.ncb + kWavesPerBlock - 1) / kWavesPerBlock));
+    const dim3 grid_runs(grid.x < (unsigned)g_emb_run_blocks ? grid.x : (unsigned)g_emb_run_blocks, grid.y);
     float *runsum = reinterpret_cast<float *>(ws + p.off_runsum);
-    if (dt == LNPEGN_BF16)
-        emb_runs_kernel<bf16_t><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(
-            static_cast<const bf16_t *>(g), keys_out, vals_out, w, runsum, contrib, bigpart, p.n, T, D, V, accumulate,
-            vec_ok);
-    else
-        emb_runs_kernel<float><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(
-            static_cast<const float *>(g), keys_out, vals_out, w, runsum, contrib, bigpart, p.n, T, D, V, accumulate,
-            vec_ok);
+    const bool vec = vec_ok && D % 8 == 0;
+    auto runs = [&](auto kernel, auto *gp) {
+        kernel<<<grid_runs, dim3(64 * kWavesPerBlock), 0, st>>>(gp, keys_out, vals_out, w, runsum, contrib, bigpart, multi,
+                                                                multi_run, p.n, T, D, V, accumulate);
+    };
+    if (dt == LNPEGN_BF16) {
+        if (vec) runs(emb_runs_kernel<bf16_t, true>, static_cast<const bf16_t *>(g));
+        else runs(emb_runs_kernel<bf16_t, false>, static_cast<const bf16_t *>(g));
+    } else {
+        if (vec) runs(emb_runs_kernel<float, true>, static_cast<const float *>(g));
+        else runs(emb_runs_kernel<float, false>, static_cast<const float *>(g));
+    }
     if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
-    emb_ids_kernel<<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(keys_out, vals_out, w, runsum, bigpart, p.n, T, D, V,
-                                                              accumulate);
+    emb_sums_kernel<false><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(keys_out, vals_out, w, runsum, contrib, bigpart,
+                                                                      multi_run, p.n, T, D, V, accumulate);
+    if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    emb_sums_kernel<true><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(keys_out, vals_out, w, runsum, contrib, bigpart,
+                                                                     multi, p.n, T, D, V, accumulate);
     if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
     const bool wnorm = accumulate && big_sq;
     if (wnorm) {

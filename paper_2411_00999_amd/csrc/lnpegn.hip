@@ -11,6 +11,7 @@
 #include "lnpegn_rows.h"
 
 namespace lnpegn {
+extern int g_emb_run_blocks;   // embedding_pegn.hip: workgroups of its run kernel per column group
 namespace {
 
 // launch-shape overrides (0 = automatic)
@@ -580,6 +581,10 @@ int lnpegn_set_tuning(int key, int value)
         case 5:
             if (value > 4) return LNPEGN_EINVAL;
             g_vpt_max = value;
+            return LNPEGN_OK;
+        case 6:
+            if (value < 1 || value > 65535) return LNPEGN_EINVAL;
+            g_emb_run_blocks = value;
             return LNPEGN_OK;
         default: return LNPEGN_EINVAL;
     }

@@ -756,6 +756,23 @@ def test_embedding_pegn_special_cases():
     _check_gns(est, oracle.gns_estimate(ref["s"], [np.sum(ref["w"] ** 2)], float(B)), B)
 
 
+@pytest.mark.parametrize("dtype,D", [("bf16", 512), ("f32", 264), ("bf16", 100)])
+def test_embedding_pegn_long_runs(dtype, D):
+    """Runs longer than one piece: an id that fills one example and occurs nowhere else (one run, several
+    pieces), an id that fills most of every example, and ordinary ids between them."""
+    B, T, V = 5, 150, 400
+    rng = np.random.default_rng(workloads.BASE_SEED + 83)
+    _, g = workloads.make_embedding_inputs(83, B, T, D, V, dtype)
+    ids = rng.integers(10, V, (B, T))
+    ids[1, :] = 3                                   # one run of 150 rows, the id's only one
+    ids[:, 20:131] = np.where(ids[:, 20:131] == 3, 4, 7)   # 111-row runs of id 7 in every example ...
+    ids[1, 20:131] = 3                              # ... but example 1 stays id 3 throughout
+    ids[2, 5:70:2] = 9                              # an id scattered inside one example: one run of 33 rows
+    _check_embedding(ids, g, V, _run_embedding(ids, g, V, dtype))
+    w0 = rng.normal(0, 1e-2, (V, D))
+    _check_embedding(ids, g, V, _run_embedding(ids, g, V, dtype, w0=w0), w0=w0)
+
+
 def test_embedding_pegn_argument_errors():
     import torch
     from paper_2411_00999_amd import binding
