@@ -246,6 +246,10 @@ int linear_pegn(const void *x, const void *g, float *w, float *s, float *big_sq,
  * reproducible).  workspace: embedding_pegn_workspace_bytes(...) bytes (0 if the shape is invalid or
  * no device is present: the sort's scratch is sized for the current device), 256-byte aligned,
  * caller-owned, contents scratch.  B*T < 2^31, V < 2^30.  Enqueued on stream, never synchronises.
+ * Without LNPEGN_ACCUMULATE the zero fill of w runs on a side stream that the library creates once per
+ * device (default priority, kept until the process ends), forked from and joined back to `stream` with
+ * events inside this call: to the caller the call is still one piece of work on `stream`; calls issued
+ * from several streams of one device share the side stream and may serialise on it.
  */
 size_t embedding_pegn_workspace_bytes(int B, int T, int D, int V);
 int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, float *s, float *big_sq, int B, int T,
@@ -258,7 +262,9 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
  * (0 = automatic, else 1..16); key 3: rows between the sweep starts of consecutive examples,
  * plus one (0 = automatic); key 4: neighbouring chunks on one XCD (0 automatic, 1 never, 2 always);
  * key 5: cap on 16-byte vectors per lane and array of the row kernel (0 = automatic, else 1..4: fewer
- * means more waves share a row).
+ * means more waves share a row); key 6: workgroups (per group of four column blocks) of
+ * embedding_pegn's run kernel, 1..65535 (default 4096; with fewer than one per 16 positions each
+ * workgroup loops).
  * Returns LNPEGN_EINVAL for an unknown key or a value out of range.  Not thread-safe against concurrent launches.
  */
 int lnpegn_set_tuning(int key, int value);
