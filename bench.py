@@ -31,6 +31,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # stream probe of known size); see profiles/ln_bwd_rows_workload3_rocprofv3.md.  Re-measure after any
 # change to the row kernel or its launch shape.  Workloads without a measurement report null.
 MEASURED_TRAFFIC_BYTES = {3: 411_200_000}
+# The same for one whole call of linear_pegn / embedding_pegn on the named shapes (all kernels of the call;
+# profiles/linear_pegn_gpt1p3b_up_rocprofv3.md, profiles/embedding_pegn_gpt1p3b_wte_rocprofv3.md).
+MEASURED_CALL_TRAFFIC_BYTES = {"gpt1p3b_up": 3_134_000_000, "gpt1p3b_wte": 675_000_000}
 
 
 # ----------------------------------------------------------------------------- HIP events
@@ -177,7 +180,8 @@ def linear_leg(shape_name, steps, warmup, log):
         "ms_per_call": round(ms, 4),
         "roofline": {"kernel": "linear_pegn_kernel + linear_final_kernel (whole call)", "bound": "mfma",
                      "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": MEASURED_CALL_TRAFFIC_BYTES.get(shape_name),
                      "algorithmic_flops_per_call": flops},
         "library_plain_gemm": {"what": "torch.mm(x^T, g) in bf16: the weight gradient alone, no per-example norms",
                                "ms_per_call": round(ms_gemm, 4), "TFLOPs": round(flops / ms_gemm / 1e9, 1)},
@@ -226,9 +230,10 @@ def embedding_leg(shape_name, steps, warmup, log):
         "workload": f"{shape_name}: ids [B={B},T={T}] Zipf over V={V} ({len(np.unique(ids_h))} distinct), g [B,T,D={D}] bf16 "
                     f"-> w' [V,D] fp32, s [B], ||w'||^2",
         "ms_per_call": round(ms, 4),
-        "roofline": {"kernel": "embedding_pegn (whole call: sort, fill, runs, ids, final)", "bound": "hbm",
+        "roofline": {"kernel": "embedding_pegn (whole call: sort and fill side by side, runs, sums, final)", "bound": "hbm",
                      "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_bytes_per_call": alg},
+                     "frac": round(gbs / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_CALL_TRAFFIC_BYTES.get(shape_name), "algorithmic_bytes_per_call": alg},
         "library_plain_backward": {"what": "aten.embedding_dense_backward in bf16: the weight gradient alone (bf16 "
                                            "result), no per-example norms", "ms_per_call": round(ms_lib, 4)},
     }
