@@ -282,7 +282,9 @@ int lnpegn_set_profile_events(void *start_event, void *stop_event);
  * Benchmarking aid: a plain streaming kernel of known traffic, the yardstick for the row
  * kernels (empirical bandwidth ceiling of the machine, and the scale of hardware byte
  * counters).  mode 0: out = a (one read, one write); mode 1: out = a XOR b (two reads, one
- * write -- the access mix of the LayerNorm backward).  `bytes` is the size of EACH array and
+ * write -- the access mix of the LayerNorm backward), four vectors per lane, ordinary loads and
+ * stores; mode 2: the same two reads and one write as one-shot workgroups of one vector per lane with
+ * streaming loads and stores (the fastest plain form found).  `bytes` is the size of EACH array and
  * must be a multiple of 16; a, b, out are 16-byte aligned device pointers (b is ignored in
  * mode 0).  Honours lnpegn_set_profile_events like the backward calls.
  */

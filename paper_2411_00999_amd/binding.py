@@ -226,7 +226,8 @@ def set_profile_events(start_event, stop_event) -> None:
 
 
 def stream_probe(a, b, out, mode: int, stream=None) -> None:
-    """Streaming yardstick kernel: out = a (mode 0) or a XOR b (mode 1) over equal-sized buffers."""
+    """Streaming yardstick kernel: out = a (mode 0) or a XOR b (modes 1, 2: 2 = one-shot workgroups, streaming
+    loads and stores) over equal-sized buffers."""
     nbytes = out.numel() * out.element_size()
     rc = load().lnpegn_stream_probe(_ptr(a), _ptr(b), _ptr(out), nbytes, mode, _stream(stream))
     if rc:

@@ -795,3 +795,24 @@ def test_embedding_pegn_argument_errors():
     assert lib.embedding_pegn(*args(wsb=64)) == 3
     assert lib.embedding_pegn_workspace_bytes(2, 8, 16, 0) == 0
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ the streaming yardstick is a real copy / xor
+def test_stream_probe_modes():
+    import torch
+    from paper_2411_00999_amd import binding
+    lib = binding.load()
+    n = 4096 * 5 + 4 * 37                      # int32 words: whole workgroups and a ragged tail of 16-byte vectors
+    g = torch.Generator(device="cpu").manual_seed(7)
+    a = torch.randint(-2**31, 2**31 - 1, (n,), dtype=torch.int32, generator=g).cuda()
+    b = torch.randint(-2**31, 2**31 - 1, (n,), dtype=torch.int32, generator=g).cuda()
+    for mode, want in ((0, a), (1, a ^ b), (2, a ^ b)):
+        out = torch.full_like(a, 12345)
+        binding.stream_probe(a, b, out, mode)
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"mode {mode}"
+    out = torch.zeros_like(a)
+    assert lib.lnpegn_stream_probe(a.data_ptr(), b.data_ptr(), out.data_ptr(), n * 4, 3, None) == 1
+    assert lib.lnpegn_stream_probe(a.data_ptr(), None, out.data_ptr(), n * 4, 2, None) == 1
+    assert lib.lnpegn_stream_probe(a.data_ptr(), b.data_ptr(), out.data_ptr(), n * 4 - 8, 2, None) == 1
+    torch.cuda.synchronize()
