@@ -260,6 +260,8 @@ def main():
     ap.add_argument("--linear-shape", default="gpt1p3b_up", help="a key of workloads.LINEAR_SHAPES")
     ap.add_argument("--embedding-only", action="store_true", help="run only the embedding-layer leg")
     ap.add_argument("--embedding-shape", default="gpt1p3b_wte", help="a key of workloads.EMBEDDING_SHAPES")
+    ap.add_argument("--tuning", default="", help="launch-shape overrides, key=value[,key=value...] "
+                                                 "(lnpegn_set_tuning; for experiments, the reported defaults use none)")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
 
@@ -272,6 +274,12 @@ def main():
     def log0(msg):
         if not args.quiet:
             print(msg, file=sys.stderr, flush=True)
+
+    if args.tuning:
+        from paper_2411_00999_amd import binding as _binding
+        for kv in filter(None, args.tuning.split(",")):
+            k, v = kv.split("=")
+            _binding.set_tuning(int(k), int(v))
 
     if args.linear_only:
         if args.gpus != 1:

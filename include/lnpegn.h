@@ -52,6 +52,9 @@ size_t lnpegn_workspace_bytes(int B, int T, int D, lnpegn_dtype dt);
 
 /* Short English text for a status code (host pointer to a static string). */
 const char *lnpegn_status_string(int status);
+/* The hipError_t (as an int) behind the calling thread's most recent LNPEGN_EHIP from a backward call's row
+ * kernel launch, 0 if there was none: what to look up when a launch is refused. */
+int lnpegn_last_hip_error(void);
 
 /*
  * LayerNorm row statistics, the part of the forward pass the backward needs.

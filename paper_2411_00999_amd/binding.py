@@ -16,7 +16,7 @@ from . import build as _build
 F32, BF16 = 0, 1
 STATUS = {0: "LNPEGN_OK", 1: "LNPEGN_EINVAL", 2: "LNPEGN_EUNSUPPORTED", 3: "LNPEGN_EWORKSPACE",
           4: "LNPEGN_EHIP"}
-EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "ln_fwd_stats", "ln_bwd",
+EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "lnpegn_last_hip_error", "ln_fwd_stats", "ln_bwd",
            "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning", "lnpegn_set_profile_events",
            "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred",
            "ln_fwd", "ln_bwd_ex", "rms_fwd", "rms_bwd_ex",
@@ -30,7 +30,13 @@ _lib = None
 class LnpegnError(RuntimeError):
     def __init__(self, fn: str, status: int):
         self.status = status
-        super().__init__(f"{fn} returned {STATUS.get(status, status)}")
+        detail = ""
+        if status == 4 and _lib is not None:          # LNPEGN_EHIP: say which HIP error, if the library kept it
+            try:
+                detail = f" (hipError_t {_lib.lnpegn_last_hip_error()})"
+            except AttributeError:
+                pass
+        super().__init__(f"{fn} returned {STATUS.get(status, status)}{detail}")
 
 
 def lib_path() -> str:
@@ -43,6 +49,10 @@ def load() -> ctypes.CDLL:
     if _lib is not None:
         return _lib
     path = _build.ensure_built()
+    # torch ships a HIP runtime of its own; it must be in the process before this library is loaded, so that
+    # both bind to that one copy (loaded first, this library would pull in the system's copy beside torch's,
+    # and kernel launches then fail with hipErrorNoDevice)
+    import torch  # noqa: F401
     lib = ctypes.CDLL(path)
     vp, fp, i, f, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
     lib.lnpegn_workspace_bytes.argtypes = [i, i, i, i]

@@ -702,6 +702,7 @@ size_t embedding_pegn_workspace_bytes(int B, int T, int D, int V)
 int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, float *s, float *big_sq, int B, int T,
                    int D, int V, lnpegn_dtype dt, void *workspace, size_t workspace_bytes, unsigned flags, void *stream)
 {
+    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!emb_shape_ok(B, T, D, V) || !ids || !g || !w || !s || !workspace) return LNPEGN_EINVAL;
     if (flags & ~(unsigned)LNPEGN_ACCUMULATE) return LNPEGN_EINVAL;
     if (dt != LNPEGN_F32 && dt != LNPEGN_BF16) return LNPEGN_EUNSUPPORTED;

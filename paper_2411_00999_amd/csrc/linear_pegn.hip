@@ -502,6 +502,7 @@ size_t linear_pegn_workspace_bytes(int B, int T, int K, int L, lnpegn_dtype dt)
 int linear_pegn(const void *x, const void *g, float *w, float *s, float *big_sq, int B, int T, int K, int L,
                 lnpegn_dtype dt, void *workspace, size_t workspace_bytes, unsigned flags, void *stream)
 {
+    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!lin_shape_ok(B, T, K, L) || !x || !g || !w || !s || !workspace) return LNPEGN_EINVAL;
     if (flags & ~(unsigned)LNPEGN_ACCUMULATE) return LNPEGN_EINVAL;
     if (dt != LNPEGN_F32 && dt != LNPEGN_BF16) return LNPEGN_EUNSUPPORTED;

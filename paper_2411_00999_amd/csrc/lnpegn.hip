@@ -11,6 +11,7 @@
 #include "lnpegn_rows.h"
 
 namespace lnpegn {
+thread_local int g_last_hip_error = 0;   // hipError_t behind this thread's latest LNPEGN_EHIP from a row kernel launch
 extern int g_emb_run_blocks;   // embedding_pegn.hip: workgroups of its run kernel per column group
 namespace {
 
@@ -82,7 +83,7 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         const int elems = p.vpt * E;                 // per lane
         waves_per_simd = elems > 8 ? 2 : 4;          // measured: more waves of 16-element lanes only add contention
         // launch bound of the instantiation that will run: 256 threads for S = 1, 2, 4; 512 else
-        const int max_waves = (p.S == 1 || p.S == 2 || p.S == 4) ? 4 : 8;
+        const int max_waves = (p.S == 1 || p.S == 2 || (p.S == 4 && elems > 8)) ? 4 : 8;
         int R = g_waves > 0 ? g_waves / p.S : (p.S >= 4 ? 1 : 4 / p.S);
         if (R < 1) R = 1;
         while (R > 1 && R * p.S > max_waves) --R;
@@ -98,7 +99,13 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
     // one full round of resident workgroups unless told otherwise
     int target = pegn ? g_chunks_pegn : g_chunks_plain;
     if (target <= 0) {
-        const int per_cu = (waves_per_simd * 4) / nwaves > 0 ? (waves_per_simd * 4) / nwaves : 1;
+        int per_cu = (waves_per_simd * 4) / nwaves > 0 ? (waves_per_simd * 4) / nwaves : 1;
+        // Per-example sweeps with wide lanes: one workgroup per CU.  Half as many chunks per example keep each
+        // example's moving window of memory half as wide, which is worth more than the second workgroup's
+        // latency hiding (measured on B=16 T=2048: D=2048 bf16 72.0 -> 69.3 us, D=4096 bf16 152 -> 148 us,
+        // D=1024 fp32 75.9 -> 71.5 us; within 2 % either way on the other shapes tried; the plain backward,
+        // one sweep over the whole tensor, prefers two).
+        if (pegn && p.fast && waves_per_simd == 2 && per_cu > 1) per_cu /= 2;
         target = kCUs * per_cu;
     }
     const int rows_min = p.fast ? 2 * p.R : 1;       // keep every row group busy
@@ -216,6 +223,7 @@ int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, con
             float *pe_beta_sq, float *big_sq, int B, int T, int D, int dt, int gamma_dt, float eps,
             void *workspace, size_t workspace_bytes, void *stream)
 {
+    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
     if (!dtype_ok(dt) || !dtype_ok(gamma_dt)) return LNPEGN_EUNSUPPORTED;
     if (!x || !dy || !gamma || !dx || !dgamma || (!rms && !dbeta)) return LNPEGN_EINVAL;
@@ -256,7 +264,10 @@ int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, con
         e = saved ? launch_rows<bf16_t, true>(p, a, rl) : launch_rows<bf16_t, false>(p, a, rl);
     else
         e = saved ? launch_rows<float, true>(p, a, rl) : launch_rows<float, false>(p, a, rl);
-    if (e != hipSuccess) return LNPEGN_EHIP;
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return LNPEGN_EHIP;
+    }
     if (defer) return LNPEGN_OK;   // lnpegn_reduce_deferred finishes the job
 
     // ---- the levels above the chunks (fixed-order sums) ----
@@ -391,6 +402,8 @@ size_t lnpegn_workspace_bytes(int B, int T, int D, lnpegn_dtype dt)
     return need;
 }
 
+int lnpegn_last_hip_error(void) { return g_last_hip_error; }
+
 const char *lnpegn_status_string(int status)
 {
     switch (status) {
@@ -406,6 +419,7 @@ const char *lnpegn_status_string(int status)
 int ln_fwd_stats(const void *x, float *mean, float *rstd, int B, int T, int D, lnpegn_dtype dt,
                  float eps, void *stream)
 {
+    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
     if (!dtype_ok(dt)) return LNPEGN_EUNSUPPORTED;
     if (!x || !mean || !rstd) return LNPEGN_EINVAL;
@@ -421,6 +435,7 @@ int ln_fwd_stats(const void *x, float *mean, float *rstd, int B, int T, int D, l
 int ln_fwd(const void *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd, int B,
            int T, int D, lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *stream)
 {
+    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
     if (!dtype_ok(dt) || !dtype_ok(gamma_dt)) return LNPEGN_EUNSUPPORTED;
     if (!x || !gamma || !beta || !y) return LNPEGN_EINVAL;
@@ -487,6 +502,7 @@ int ln_bwd_ex(const void *x, const void *dy, const void *gamma, const float *mea
 int rms_fwd(const void *x, const void *gamma, void *y, float *rstd, int B, int T, int D, lnpegn_dtype dt,
             lnpegn_dtype gamma_dt, float eps, void *stream)
 {
+    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
     if (!dtype_ok(dt) || !dtype_ok(gamma_dt)) return LNPEGN_EUNSUPPORTED;
     if (!x || !gamma || !y) return LNPEGN_EINVAL;
@@ -515,6 +531,7 @@ int rms_bwd_ex(const void *x, const void *dy, const void *gamma, const float *rs
 int lnpegn_reduce_deferred(void *const *workspaces, int n, int B, int T, int D, lnpegn_dtype dt,
                            void *stream)
 {
+    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!workspaces || n <= 0 || !shape_ok(B, T, D)) return LNPEGN_EINVAL;
     if (!dtype_ok(dt)) return LNPEGN_EUNSUPPORTED;
     for (int i = 0; i < n; ++i)
@@ -540,6 +557,7 @@ int lnpegn_reduce_deferred(void *const *workspaces, int n, int B, int T, int D, 
 int gns_estimate(const float *pe_sq, const float *big_sq, int n_groups, int B, float pe_scale,
                  float *out, void *stream)
 {
+    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!pe_sq || !big_sq || !out || n_groups <= 0 || B <= 1) return LNPEGN_EINVAL;
     gns_estimate_kernel<<<dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
         pe_sq, big_sq, n_groups, B, pe_scale, out);
@@ -548,6 +566,7 @@ int gns_estimate(const float *pe_sq, const float *big_sq, int n_groups, int B, f
 
 int gns_ema_update(double *state, const float *records, int n, double alpha, float *smoothed, void *stream)
 {
+    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!state || !records || n <= 0 || !(alpha >= 0.0 && alpha < 1.0)) return LNPEGN_EINVAL;
     gns_ema_update_kernel<<<dim3((n + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
         state, records, n, alpha, smoothed);
@@ -556,6 +575,7 @@ int gns_ema_update(double *state, const float *records, int n, double alpha, flo
 
 int gns_offline(const float *records, int64_t n, float *out, void *stream)
 {
+    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!records || !out || n < 2) return LNPEGN_EINVAL;
     gns_offline_kernel<<<dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(records, n, out);
     return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
@@ -607,6 +627,7 @@ int lnpegn_set_tuning(int key, int value)
 
 int lnpegn_stream_probe(const void *a, const void *b, void *out, size_t bytes, int mode, void *stream)
 {
+    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!a || !out || (mode >= 1 && !b) || bytes == 0 || bytes % 16) return LNPEGN_EINVAL;
     if (mode < 0 || mode > 2) return LNPEGN_EINVAL;
     if (!aligned16(a) || !aligned16(out) || (mode >= 1 && !aligned16(b))) return LNPEGN_EINVAL;

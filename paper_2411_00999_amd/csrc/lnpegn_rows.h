@@ -97,10 +97,20 @@ __device__ __forceinline__ int wave_valid_elems(int ws, int S, int nvec)
 // workgroup takes part in every barrier, also a group that has run out of rows).  0: the same
 // with S read at run time (3, 5, 6, 7 waves).
 // kFull: every lane owns kVpt valid vectors (nvec == 64*S*kVpt), so no padding logic is compiled.
-constexpr int rows_kernel_max_threads(int kS) { return (kS == 0 || kS == 8) ? 512 : 256; }
+// Four waves per row with one vector per lane may also run as two row groups (512 threads).
+constexpr bool rows_kernel_narrow4(int kS, int elems) { return kS == 4 && elems <= 8; }
+constexpr int rows_kernel_max_threads(int kS, int elems)
+{
+    return (kS == 0 || kS == 8 || rows_kernel_narrow4(kS, elems)) ? 512 : 256;
+}
+constexpr int rows_kernel_min_blocks(int kS, int elems)
+{
+    return rows_kernel_narrow4(kS, elems) ? 2 : elems > 8 ? 3 : 4;
+}
 
 template <typename T, int kVpt, bool kSaved, int kS, bool kFull>
-__global__ __launch_bounds__(rows_kernel_max_threads(kS), (kVpt * Vec<T>::kElems > 8 ? 3 : 4))
+__global__ __launch_bounds__(rows_kernel_max_threads(kS, kVpt * Vec<T>::kElems),
+                             rows_kernel_min_blocks(kS, kVpt * Vec<T>::kElems))
 void ln_bwd_rows_kernel(RowArgs a)
 {
     using V = Vec<T>;
@@ -108,7 +118,7 @@ void ln_bwd_rows_kernel(RowArgs a)
     constexpr int E = V::kElems;
     constexpr bool kSync = kS != 1;
     // x and dy are read once: the streaming hint pays for narrow rows and costs on wide ones (measured)
-    constexpr bool kStreamLoads = kS == 1 || kS == 2;
+    constexpr bool kStreamLoads = kS == 1 || kS == 2 || rows_kernel_narrow4(kS, kVpt * E);
     constexpr int NF = 2 * kVpt * E;  // accumulator floats per lane
     constexpr int KL = kVpt - 1;      // only a lane's last vector slot can be padding
     extern __shared__ __align__(16) float lds[];
