@@ -3,14 +3,14 @@
 //   s[b]     = sum_{v,d} w_b[v,d]^2               (step 3)
 //   w'[v,d]  = sum_b w_b[v,d]                     (step 4)
 // The positions p = b*T + t are sorted by id (stable, so positions ascend inside an id and the rows of one
-// example are adjacent): a "run" is the rows of one id in one example, a "segment" all runs of one id, a
+// example are adjacent): a "segment" is all positions of one id, a "run" those of one id in one example, a
 // "piece" at most kPiece consecutive sorted positions of one run (a run is cut wherever the sorted index is a
-// multiple of kPiece).  Kernel A gives every piece to a wave (columns spread over its lanes).  A piece that
-// is a whole run yields that example's share of step 3 at once, and the row of w' too if the run is the id's
-// only one.  Every other sum is parked in the workspace and kernel B, one wave per id that has more than one
-// piece, adds the parked sums in sorted order: pieces into runs (squared: step 3), runs into the row of w'.
-// Every row of g is read once, no wave reads more than kChunk + kPiece rows however skewed the ids are, and
-// nothing is atomic: results are bitwise reproducible.
+// multiple of kPiece).  Kernel A reads g, every row once.  An id with at most kShort positions is finished
+// there by one wave (each run's share of step 3, the row of w').  A longer id is handed out piece by piece:
+// a piece that is a whole run yields that run's share at once, the piece sums are parked in the workspace,
+// and kernel B (two launches: per run, then per id) adds the parked sums in sorted order, finding them by
+// binary search of the sorted list rather than by walking it.  No wave reads more than kChunk + kPiece rows
+// however skewed the ids are, and nothing is atomic: results are bitwise reproducible.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -231,11 +231,12 @@ __device__ __forceinline__ void pick_floats(const float (&a)[N][8], int u, float
 // whose positions hold the pieces' first rows; a piece that is a whole run yields that run's share of s[b],
 // every sum is parked (unless the piece is the id's only one) and the id is marked for kernel B.
 // A wave sees kShort positions back (to tell whether a piece in its chunk belongs to a short segment that an
-// earlier wave owns) and far enough ahead for anything that starts in its chunk; rows are streamed eight at
-// a time.  contrib [ncb][n]: a run's share of s[b], at the run's first position, zero elsewhere.
+// earlier wave owns) and far enough ahead for anything that starts in its chunk; rows are streamed sixteen
+// (fp32: eight) at a time.  contrib [ncb][n]: a run's share of s[b], at the run's first position, zero elsewhere.
 // runsum [n][D]: parked sums, at the piece's first position.  multi [n]: set at the sorted index of the first
-// position of a long id that has parked sums; multi_run [n]: of a run that has several pieces.  bigpart [ncb][n]: squared norm of a finished row of w', at the segment's first
-// position (not when accumulating).
+// position of a long id that has parked sums; multi_run [n]: of a run that has several pieces.
+// bigpart [ncb][n]: squared norm of a finished row of w', at the segment's first position (not when
+// accumulating).
 constexpr int kShort = 12;
 static_assert(kShort + kChunk + kPiece < 63 && kShort + kChunk + kShort < 63, "one 64-lane window must cover a wave's work");
 
