@@ -614,6 +614,8 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 struct SideStream {
     hipStream_t stream = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
+    std::mutex in_use;   // held by a call from its fork to its join: the two events are recorded and waited
+                         // on as pairs, which another thread's call on the same device must not interleave
 };
 constexpr int kMaxDevices = 64;
 SideStream g_side[kMaxDevices];
@@ -726,6 +728,8 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
     const int64_t nscratch = (int64_t)((p.off_wpart - p.off_contrib) / sizeof(float));
     // fork: the fill starts now on the side stream (on the caller's stream if there is none)
     SideStream *side = accumulate ? nullptr : side_stream();
+    std::unique_lock<std::mutex> side_lock;
+    if (side) side_lock = std::unique_lock<std::mutex>(side->in_use);
     if (!accumulate) {
         hipStream_t fs = st;
         if (side) {
@@ -748,6 +752,7 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
         return LNPEGN_EHIP;
     // join: the rows of w' are written from here on
     if (side && hipStreamWaitEvent(st, side->join, 0) != hipSuccess) return LNPEGN_EHIP;
+    if (side) side_lock.unlock();
     const int esz = dt == LNPEGN_BF16 ? 2 : 4;
     // 8 columns per lane: 16 bytes of bf16, 32 bytes of fp32; rows must keep that alignment
     const int vec_ok = ((reinterpret_cast<uintptr_t>(g) & 15u) == 0 && ((int64_t)D * esz) % 16 == 0) ? 1 : 0;

@@ -773,6 +773,46 @@ def test_embedding_pegn_long_runs(dtype, D):
     _check_embedding(ids, g, V, _run_embedding(ids, g, V, dtype, w0=w0), w0=w0)
 
 
+def test_embedding_pegn_two_threads_two_streams():
+    """Calls from two host threads on two streams of one device share the library's side stream: every call must
+    still give the single-call result bit for bit."""
+    import threading
+    import torch
+    from paper_2411_00999_amd import binding
+    B, T, D, V = 4, 256, 512, 3000
+    cases = []
+    for seed in (91, 92):
+        ids, g = workloads.make_embedding_inputs(seed, B, T, D, V, "bf16")
+        idd, gd = torch.from_numpy(ids).cuda(), pu.to_device(g, "bf16")
+        ref = binding.embedding_pegn(idd, gd, V)
+        torch.cuda.synchronize()
+        cases.append((idd, gd, ref))
+    results, errors = [None, None], []
+
+    def work(k):
+        try:
+            st = torch.cuda.Stream()
+            idd, gd, _ = cases[k]
+            outs = []
+            with torch.cuda.stream(st):
+                for _ in range(20):
+                    outs.append(binding.embedding_pegn(idd, gd, V, stream=st))
+            st.synchronize()
+            results[k] = outs
+        except Exception as e:                      # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for k in range(2):
+        for out in results[k]:
+            assert all(torch.equal(a, b) for a, b in zip(out, cases[k][2]))
+
+
 def test_embedding_pegn_argument_errors():
     import torch
     from paper_2411_00999_amd import binding
