@@ -368,6 +368,23 @@ def main():
         fused_step()     # leave the outputs of the mode being reported in place
         torch.cuda.synchronize()
 
+    # ---- the same fused step captured into a HIP graph and replayed: what the GPU does when the host's launch
+    #      cost is out of the way (it only matters where a layer's kernel is shorter than a launch: workload 2)
+    graph_replay = None
+    if not args.only_fused and args.reduce == "deferred":
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            fused_step()
+            with torch.cuda.graph(graph, stream=side):
+                fused_step()
+        torch.cuda.current_stream().wait_stream(side)
+        t_graph = timed(graph.replay, args.warmup, args.steps)
+        graph_replay = {"ms_per_step": round(t_graph * 1e3, 4), "GBps": round(bytes_per_step / t_graph / 1e9, 2)}
+        log(f"fused step replayed from a graph: {t_graph * 1e3:.3f} ms/step  {bytes_per_step / t_graph / 1e9:.1f} GB/s")
+        del graph
+
     # ---- forward + backward with gradient accumulation (the workload of the paper's timing figure
     #      in Section 5.1): ln_fwd saves the statistics, ln_bwd_ex(PER_EXAMPLE|ACCUMULATE|DEFER) reuses them
     fwd_bwd = None
@@ -528,6 +545,7 @@ def main():
         f"{other}_reduction": {"fused_ms_per_step": round(t_fused_o * 1e3, 4),
                                "plain_ms_per_step": round(t_plain_o * 1e3, 4),
                                "fused_GBps": round(bytes_per_step / t_fused_o / 1e9, 2)},
+        "graph_replay": graph_replay,
         "fwd_bwd_accumulate": fwd_bwd,
         "gns": {"g_small_sq": gns[0], "g_big_sq": gns[1], "G2": gns[2], "S": gns[3], "B_simple": gns[4]},
         "roofline": {
