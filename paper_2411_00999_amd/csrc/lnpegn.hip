@@ -371,7 +371,10 @@ hipError_t launch_fwd(FwdArgs a, bool vector_ok, hipStream_t s)
     } else {
         const int waves = ceil_div(a.nvec, 64 * (16 / E));
         const int vpt = ceil_div(a.nvec, 64 * waves);
-        const dim3 grid((unsigned)(N < 4096 ? N : 4096)), block(64 * waves);
+        // measured (B*T = 32768 rows, bf16): 16 resident waves per CU for rows of 2 and 4 waves (D=2048: 47.8 us
+        // against 52.6 with twice as many; D=4096: 92.3 against 95.2), the full 32 for rows of 8 (D=8192: 181 against 190)
+        const int64_t cap = waves <= 4 ? 4096 / waves : 4096;
+        const dim3 grid((unsigned)(N < cap ? N : cap)), block(64 * waves);
         switch (vpt) {
             case 1: ln_fwd_kernel<T, 1, true, kWriteY><<<grid, block, 0, s>>>(a); break;
             case 2: ln_fwd_kernel<T, 2, true, kWriteY><<<grid, block, 0, s>>>(a); break;

@@ -546,7 +546,7 @@ __global__ void ln_fwd_kernel(FwdArgs a)
 #pragma unroll
         for (int k = 0; k < kVpt; ++k) {
             Raw raw = V::zero();
-            if (ok[k]) raw = xv[r * a.nvec + vidx[k]];
+            if (ok[k]) raw = V::load_stream(xv + r * a.nvec + vidx[k]);   // x is not read again by this kernel
             V::unpack(raw, xf[k]);
 #pragma unroll
             for (int e = 0; e < E; ++e) s += xf[k][e];
