@@ -485,26 +485,35 @@ def main():
         g64 = host_inputs[0].gamma.astype(np.float64)
         oracle.ln_bwd_pegn(host_inputs[0].x[:1].astype(np.float64), host_inputs[0].dy[:1].astype(np.float64),
                            g64, eps)           # load + warm the library
-        t_cpu, ref0 = 0.0, None
-        for inp in host_inputs:
+        # every sampled layer is passed `reps` times, so that the sample is about 1 s of wall time on all the
+        # threads (10-30 s of CPU work) however fast the host is
+        t_cpu, ref0, reps, passes = 0.0, None, 1, 0
+        n_s = len(host_inputs)
+        for li, inp in enumerate(host_inputs):
             x64, dy64 = inp.x.astype(np.float64), inp.dy.astype(np.float64)     # exact, not timed
-            t0 = time.perf_counter()
-            ref = oracle.ln_bwd_pegn(x64, dy64, inp.gamma.astype(np.float64), eps, want_dx=True,
-                                     want_pe=False, nthreads=threads)
-            t_cpu += time.perf_counter() - t0
+            rep = 0
+            while rep < reps:
+                t0 = time.perf_counter()
+                ref = oracle.ln_bwd_pegn(x64, dy64, inp.gamma.astype(np.float64), eps, want_dx=True,
+                                         want_pe=False, nthreads=threads)
+                dt_call = time.perf_counter() - t0
+                t_cpu += dt_call
+                passes += 1
+                rep += 1
+                if li == 0 and rep == 1:
+                    reps = int(min(40, max(1, round(1.0 / max(dt_call * n_s, 1e-3)))))
             ref0 = ref0 or ref
             del x64, dy64
-        n_s = len(host_inputs)
         cpu_baseline = {
-            "value": round(n_s * bytes_per_layer / t_cpu / 1e9, 4), "unit": "GB/s", "cores": threads,
+            "value": round(passes * bytes_per_layer / t_cpu / 1e9, 4), "unit": "GB/s", "cores": threads,
             "kind": "oracle",
-            "sample": f"layers 0..{n_s - 1} of {n_layers} (each B={B} T={T} D={D}: dx, dgamma, dbeta and "
-                      f"per-example norms by one separate fp64 backward per example), {t_cpu:.2f} s wall on "
-                      f"{threads} threads of {os.cpu_count()} host cpus; bytes counted as for the GPU "
-                      f"({esz} B/element)",
+            "sample": f"layers 0..{n_s - 1} of {n_layers}, each passed {reps} times (each B={B} T={T} D={D}: dx, dgamma, "
+                      f"dbeta and per-example norms by one separate fp64 backward per example), {t_cpu:.2f} s wall on "
+                      f"{threads} threads of {os.cpu_count()} host cpus = {t_cpu * threads:.0f} s of CPU work; bytes "
+                      f"counted as for the GPU ({esz} B/element)",
             "seconds": round(t_cpu, 3),
         }
-        log(f"oracle: {t_cpu:.2f} s for {n_s} layers on {threads} threads")
+        log(f"oracle: {t_cpu:.2f} s for {passes} layer passes on {threads} threads")
         # spot parity of layer 0 against the oracle output just computed
         L0 = layers[0]
         dg = L0["dgamma"].cpu().numpy().astype(np.float64)
