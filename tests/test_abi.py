@@ -162,3 +162,26 @@ def test_linear_accum_steps_host_function_matches_oracle():
     for bad in [(-1, 10, 2), (1, -10, 2), (1, 10, 0)]:
         with pytest.raises(binding.LnpegnError):
             binding.gns_linear_accum_steps(*bad)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only: any other --gpus ends with a message and a non-zero status, before
+    anything touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr or "one GPU" in r.stderr
+
+
+def test_product_path_does_not_import_the_oracle():
+    """The oracle is test infrastructure: nothing under the package may import it."""
+    pkg = os.path.join(ROOT, "paper_2411_00999_amd")
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            text = open(os.path.join(pkg, name)).read()
+            assert "import oracle" not in text and "from oracle" not in text, name
+    for name in os.listdir(os.path.join(pkg, "csrc")):
+        text = open(os.path.join(pkg, "csrc", name)).read()
+        assert "oracle/" not in text, name
