@@ -83,8 +83,12 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         const int elems = p.vpt * E;                 // per lane
         waves_per_simd = elems > 8 ? 2 : 4;          // measured: more waves of 16-element lanes only add contention
         // launch bound of the instantiation that will run: 256 threads for S = 1, 2, 4; 512 else
-        const int max_waves = (p.S == 1 || p.S == 2 || (p.S == 4 && elems > 8)) ? 4 : 8;
-        int R = g_waves > 0 ? g_waves / p.S : (p.S >= 4 ? 1 : 4 / p.S);
+        const int max_waves = (elems <= 8 && p.S <= 2) ? 4 : 8;
+        // row groups per workgroup.  Wide lanes: six waves per workgroup, one workgroup per CU (measured, B*T =
+        // 32768 rows: bf16 D=2048 69.2 -> 66.9 us per-example and 69.0 -> 65.4 plain against four waves; fp32
+        // D=2048 151.7 -> 145.6 and 133 -> 131; eight waves are slower than six; no difference where a row
+        // already takes four or eight waves)
+        int R = g_waves > 0 ? g_waves / p.S : elems > 8 ? (p.S <= 2 ? 6 / p.S : 1) : (p.S >= 4 ? 1 : 4 / p.S);
         if (R < 1) R = 1;
         while (R > 1 && R * p.S > max_waves) --R;
         p.R = R;

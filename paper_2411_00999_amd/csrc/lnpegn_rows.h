@@ -97,15 +97,17 @@ __device__ __forceinline__ int wave_valid_elems(int ws, int S, int nvec)
 // workgroup takes part in every barrier, also a group that has run out of rows).  0: the same
 // with S read at run time (3, 5, 6, 7 waves).
 // kFull: every lane owns kVpt valid vectors (nvec == 64*S*kVpt), so no padding logic is compiled.
-// Four waves per row with one vector per lane may also run as two row groups (512 threads).
+// Launch bounds.  Lanes that own more than 8 elements (two or more 16-byte vectors of bf16) run as one workgroup
+// of up to 8 waves per CU, whatever the number of waves per row; lanes with one vector run as several small
+// workgroups per CU, except that four waves per row may also pair up as two row groups.
 constexpr bool rows_kernel_narrow4(int kS, int elems) { return kS == 4 && elems <= 8; }
 constexpr int rows_kernel_max_threads(int kS, int elems)
 {
-    return (kS == 0 || kS == 8 || rows_kernel_narrow4(kS, elems)) ? 512 : 256;
+    return (kS == 0 || kS == 8 || elems > 8 || rows_kernel_narrow4(kS, elems)) ? 512 : 256;
 }
 constexpr int rows_kernel_min_blocks(int kS, int elems)
 {
-    return rows_kernel_narrow4(kS, elems) ? 2 : elems > 8 ? 3 : 4;
+    return elems > 8 ? 1 : rows_kernel_narrow4(kS, elems) ? 2 : 4;
 }
 
 template <typename T, int kVpt, bool kSaved, int kS, bool kFull>
