@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per row-kernel launch counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the
 # stream probe of known size); see profiles/ln_bwd_rows_workload3_rocprofv3.md.  Re-measure after any
 # change to the row kernel or its launch shape.  Workloads without a measurement report null.
-MEASURED_TRAFFIC_BYTES = {3: 408_800_000}
+MEASURED_TRAFFIC_BYTES = {3: 407_050_000}
 # The same for one whole call of linear_pegn / embedding_pegn on the named shapes (all kernels of the call;
 # profiles/linear_pegn_gpt1p3b_up_rocprofv3.md, profiles/embedding_pegn_gpt1p3b_wte_rocprofv3.md).
 MEASURED_CALL_TRAFFIC_BYTES = {"gpt1p3b_up": 3_134_000_000, "gpt1p3b_wte": 675_000_000}
