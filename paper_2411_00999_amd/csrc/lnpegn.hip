@@ -87,8 +87,10 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         // row groups per workgroup.  Wide lanes: six waves per workgroup, one workgroup per CU (measured, B*T =
         // 32768 rows: bf16 D=2048 69.2 -> 66.9 us per-example and 69.0 -> 65.4 plain against four waves; fp32
         // D=2048 151.7 -> 145.6 and 133 -> 131; eight waves are slower than six; no difference where a row
-        // already takes four or eight waves)
-        int R = g_waves > 0 ? g_waves / p.S : elems > 8 ? (p.S <= 2 ? 6 / p.S : 1) : (p.S >= 4 ? 1 : 4 / p.S);
+        // already takes four or eight waves).
+        // (rows that one wave covers stay at four row groups: six made the short kernels of B=8 T=1024 D=768 and
+        // B=512 T=64 D=1024 3-10 % slower)
+        int R = g_waves > 0 ? g_waves / p.S : (elems > 8 && p.S == 2) ? 3 : (p.S >= 4 ? 1 : 4 / p.S);
         if (R < 1) R = 1;
         while (R > 1 && R * p.S > max_waves) --R;
         p.R = R;
@@ -109,7 +111,9 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         // latency hiding (measured on B=16 T=2048: D=2048 bf16 72.0 -> 69.3 us, D=4096 bf16 152 -> 148 us,
         // D=1024 fp32 75.9 -> 71.5 us; within 2 % either way on the other shapes tried; the plain backward,
         // one sweep over the whole tensor, prefers two).
-        if (pegn && p.fast && waves_per_simd == 2 && per_cu > 1) per_cu /= 2;
+        // ... as long as a chunk keeps a hundred rows or so: short launches (B=8 T=1024 D=768: 13 us) want the
+        // parallelism more.
+        if (pegn && p.fast && waves_per_simd == 2 && per_cu > 1 && N / ((int64_t)kCUs * (per_cu / 2)) >= 96) per_cu /= 2;
         target = kCUs * per_cu;
     }
     const int rows_min = p.fast ? 2 * p.R : 1;       // keep every row group busy
