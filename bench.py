@@ -260,6 +260,8 @@ def main():
     ap.add_argument("--linear-shape", default="gpt1p3b_up", help="a key of workloads.LINEAR_SHAPES")
     ap.add_argument("--embedding-only", action="store_true", help="run only the embedding-layer leg")
     ap.add_argument("--embedding-shape", default="gpt1p3b_wte", help="a key of workloads.EMBEDDING_SHAPES")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="streams the independent layers of a step are spread over (deferred reduction only)")
     ap.add_argument("--tuning", default="", help="launch-shape overrides, key=value[,key=value...] "
                                                  "(lnpegn_set_tuning; for experiments, the reported defaults use none)")
     ap.add_argument("--quiet", action="store_true")
@@ -322,22 +324,41 @@ def main():
 
     all_ws = [L["ws"] for L in layers]
 
+    # The layers are independent, so the caller may spread them over streams: with two, one layer's kernel
+    # ramps up while the other's drains.  Deferred mode only (the immediate calls share one workspace).
+    lanes = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else []
+
+    def over_layers(call, deferred):
+        if not (lanes and deferred):
+            for L in layers:
+                call(L, None)
+            return
+        cur = torch.cuda.current_stream()
+        fork = torch.cuda.Event()
+        fork.record(cur)
+        for st in lanes:
+            st.wait_event(fork)
+        for i, L in enumerate(layers):
+            call(L, lanes[i % len(lanes)])
+        for st in lanes:
+            join = torch.cuda.Event()
+            join.record(st)
+            cur.wait_event(join)
+
     def make_steps(deferred):
         def fused_step():
-            for L in layers:
-                binding.ln_bwd_pegn(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"],
-                                    dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"],
-                                    pe_gamma_sq=L["pe_g"], pe_beta_sq=L["pe_b"], big_sq=L["big"],
-                                    workspace=L["ws"] if deferred else sh["ws"], deferred=deferred)
+            over_layers(lambda L, st: binding.ln_bwd_pegn(
+                L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"], dx=L["dx"], dgamma=L["dgamma"],
+                dbeta=L["dbeta"], pe_gamma_sq=L["pe_g"], pe_beta_sq=L["pe_b"], big_sq=L["big"],
+                workspace=L["ws"] if deferred else sh["ws"], deferred=deferred, stream=st), deferred)
             if deferred:
                 binding.reduce_deferred(all_ws, B, T, D, sh["dt_code"])
             binding.gns_estimate(sh["pe_all"], sh["big_all"], float(B), out=sh["gns"])
 
         def plain_step():
-            for L in layers:
-                binding.ln_bwd(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"],
-                               dx=L["dx"], dgamma=L["dgamma"], dbeta=L["dbeta"],
-                               workspace=L["ws"] if deferred else sh["ws"], deferred=deferred)
+            over_layers(lambda L, st: binding.ln_bwd(
+                L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"], dx=L["dx"], dgamma=L["dgamma"],
+                dbeta=L["dbeta"], workspace=L["ws"] if deferred else sh["ws"], deferred=deferred, stream=st), deferred)
             if deferred:
                 binding.reduce_deferred(all_ws, B, T, D, sh["dt_code"])
         return fused_step, plain_step
@@ -543,8 +564,10 @@ def main():
         "config": {
             "workload": f"configs[{cfg - 1}]: {n_layers} LayerNorm layers back-to-back, B={B} T={T} D={D} "
                         f"{dtype}, ln_bwd_pegn per layer + one gns_estimate; row stats {args.stats}; "
-                        f"{args.reduce} reduction",
+                        f"{args.reduce} reduction; layers spread over {max(1, len(lanes)) if args.reduce == 'deferred' else 1} "
+                        f"stream(s)",
             "B": B, "T": T, "D": D, "layers": n_layers, "stats": args.stats, "reduce": args.reduce,
+            "streams": max(1, len(lanes)) if args.reduce == "deferred" else 1,
         },
         "pct_hbm_peak": round(100.0 * bytes_per_step / t_fused / 1e9 / HBM_PEAK_GBS, 2),
         "tokens_per_s": round(n_layers * N / t_fused, 1),
