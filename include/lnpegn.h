@@ -10,11 +10,14 @@
  *
  * Conventions shared by every entry point
  *   - Every pointer is a DEVICE pointer unless it says "host".  The caller owns
- *     every buffer, the workspace included.  The library allocates nothing,
- *     frees nothing, keeps no state between calls and never synchronises.
+ *     every buffer, the workspace included.  The library allocates no memory,
+ *     frees none and never synchronises.  The only state it keeps is named where
+ *     it arises: the benchmarking overrides (lnpegn_set_tuning,
+ *     lnpegn_set_profile_events) and the side stream of embedding_pegn.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     All work is enqueued on it and the call returns before it completes.
- *   - Outputs are overwritten, never accumulated into.
+ *     All work is enqueued on it and the call returns before it completes; a
+ *     call may therefore be captured into a HIP graph.
+ *   - Outputs are overwritten, unless a flag of the call says they accumulate.
  *   - The return value is a lnpegn_status.  On any status other than LNPEGN_OK
  *     nothing was launched and no output was touched.
  *   - Results are bitwise reproducible from call to call for a fixed shape:
