@@ -1,18 +1,17 @@
 """TEST INFRASTRUCTURE -- NOT PART OF THE PRODUCT PATH.
 
-Slow fp64 definition of the embedding-layer simultaneous per-example gradient-norm computation
-(Appendix B, embedding-layer algorithm): for token ids x [B,T] in [0,V) and gradients g [B,T,D] of the
-loss with respect to the embedding outputs,
+Slow fp64 definition of what the embedding-layer per-example gradient-norm computation of Appendix B
+(embedding-layer algorithm) must produce.  An embedding layer copies row ids[b,t] of its table to
+output position (b,t); the gradient of example b's loss with respect to the table is therefore the
+scatter-add of that example's output gradients by id,
 
-    step 1   o = onehot(x, V)                               [B,T,V]
-    step 2   w_b[v,d] = sum_t o[b,t,v] * g[b,t,d]           (per-example weight gradient [V,D])
-    step 3   s_w[b]   = sum_{v,d} w_b[v,d]^2
-    step 4   w'[v,d]  = sum_b w_b[v,d]
+    w_b[v,:] = sum over the positions t of example b with ids[b,t] == v of g[b,t,:]      [V,D]
 
-Step 5 (mean over b, times B^2) is the estimator's business (gns_estimate with pe_scale = B): s_w is
-returned raw.  The one-hot tensor and the per-example [V,D] gradient are formed on purpose -- that is
-the definition; one matrix product per example is the only library step.  Nothing here is imported by
-the HIP package.
+and the quantities wanted are  s[b] = ||w_b||_F^2  (raw: the mean over b and the B^2 factor belong to
+the estimator, gns_estimate with pe_scale = B)  and  w' = sum_b w_b.  The code below is that sentence:
+a loop over (b,t) adding one row at a time into example b's own [V,D] array, which is formed on
+purpose.  No one-hot tensor, no matrix product, no library step.  Nothing here is imported by the HIP
+package.
 """
 from __future__ import annotations
 
@@ -32,11 +31,11 @@ def embedding_pegn(ids, g, V: int, want_pe: bool = False) -> dict:
     s = np.zeros(B)
     pe = np.zeros((B, V, D)) if want_pe else None
     for b in range(B):
-        onehot = np.zeros((T, V))
-        onehot[np.arange(T), ids[b]] = 1.0          # step 1 for this example
-        w_b = onehot.T @ g[b]                        # step 2
-        s[b] = np.sum(w_b * w_b)                     # step 3
-        w += w_b                                     # step 4
+        w_b = np.zeros((V, D))                       # example b's own table gradient
+        for t in range(T):
+            w_b[int(ids[b, t])] += g[b, t]           # the row that position (b,t) read
+        s[b] = np.sum(w_b * w_b)
+        w += w_b
         if want_pe:
             pe[b] = w_b
     return dict(w=w, s=s, pe=pe)

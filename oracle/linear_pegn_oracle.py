@@ -1,17 +1,18 @@
 """TEST INFRASTRUCTURE -- NOT PART OF THE PRODUCT PATH.
 
-Slow fp64 definition of the linear-layer simultaneous per-example gradient-norm computation
-(Section 3, Algorithm 1): for activations x [B,T,K] entering a linear layer and gradients g [B,T,L]
-of the loss with respect to its outputs,
+Slow fp64 definition of what the linear-layer per-example gradient-norm computation of Section 3
+(Algorithm 1) must produce.  A linear layer maps x[b,t,:] (K features) to x[b,t,:] @ W (L features);
+with g [B,T,L] the gradient of the loss with respect to its outputs, the gradient of example b's loss
+with respect to W is the sum over that example's positions of the outer products of input and output
+gradient,
 
-    step 1   w_b[k,l] = sum_t x[b,t,k] * g[b,t,l]        (every middle dimension is flattened into t)
-    step 2   s_w[b]   = sum_{k,l} w_b[k,l]^2
-    step 3   w'[k,l]  = sum_b w_b[k,l]
+    w_b = sum_t outer(x[b,t,:], g[b,t,:]) = x_b^T g_b                                     [K,L]
 
-Step 4 (mean over b, times B^2) is the estimator's business (gns_estimate with pe_scale = B), as
-for the LayerNorm path: s_w is returned raw.  The per-example tensor is materialised here on
-purpose -- that is the definition; one matrix product per example is the only library step.
-Nothing here is imported by the HIP package.
+(every middle dimension is flattened into t), and the quantities wanted are  s[b] = ||w_b||_F^2  (raw:
+the mean over b and the B^2 factor belong to the estimator, gns_estimate with pe_scale = B, as for the
+LayerNorm path)  and  w' = sum_b w_b.  The per-example matrix is formed on purpose -- that is the
+definition; one matrix product per example is the only library step, and linear_pegn_entries and
+gram_sq_norm below reach the same numbers without it.  Nothing here is imported by the HIP package.
 """
 from __future__ import annotations
 
@@ -30,16 +31,16 @@ def linear_pegn(x, g, want_pe: bool = False) -> dict:
     s = np.zeros(B)
     pe = np.zeros((B, K, L)) if want_pe else None
     for b in range(B):
-        w_b = x[b].T @ g[b]                 # step 1 for this example
-        s[b] = np.sum(w_b * w_b)            # step 2
-        w += w_b                            # step 3
+        w_b = x[b].T @ g[b]                 # example b's own weight gradient
+        s[b] = np.sum(w_b * w_b)
+        w += w_b
         if want_pe:
             pe[b] = w_b
     return dict(w=w, s=s, pe=pe)
 
 
 def linear_pegn_entries(x, g, ks, ls) -> np.ndarray:
-    """Selected entries of step 3, one by one: w'[k,l] = sum_b sum_t x[b,t,k] * g[b,t,l] for each pair
+    """Selected entries of the batch gradient, one by one: w'[k,l] = sum_b sum_t x[b,t,k] * g[b,t,l] for each pair
     (ks[i], ls[i]).  For shapes whose full [K,L] result is out of the oracle's reach."""
     x = np.asarray(x)
     g = np.asarray(g)
@@ -50,7 +51,7 @@ def linear_pegn_entries(x, g, ks, ls) -> np.ndarray:
 
 
 def gram_sq_norm(x_b, g_b) -> float:
-    """Step 2 for ONE example without forming w_b: the three-dimensional form of Section 2.2,
+    """||w_b||_F^2 for ONE example without forming w_b: the three-dimensional form of Section 2.2,
     n_b^2 = <X_b X_b^T, G_b G_b^T>_F  (X_b [T,K], G_b [T,L]; O(T^2) memory)."""
     x_b = np.asarray(x_b, dtype=np.float64)
     g_b = np.asarray(g_b, dtype=np.float64)

@@ -94,10 +94,12 @@ def test_symmetries(o=emb):
 MUTATIONS = [
     ("norm of rows summed without grouping by id", "s[b] = np.sum(w_b * w_b)", "s[b] = np.sum(g[b] * g[b])"),
     ("everything summed before squaring", "s[b] = np.sum(w_b * w_b)", "s[b] = np.sum(g[b].sum(0) ** 2)"),
-    ("one-hot off by one", "onehot[np.arange(T), ids[b]] = 1.0", "onehot[np.arange(T), (ids[b] + 1) % V] = 1.0"),
-    ("ids of example 0 used for all", "onehot[np.arange(T), ids[b]] = 1.0", "onehot[np.arange(T), ids[0]] = 1.0"),
-    ("mean over b in the weight gradient", "w += w_b ", "w += w_b / B "),
-    ("counts instead of sums", "w_b = onehot.T @ g[b]", "w_b = (onehot.T @ g[b]) / np.maximum(onehot.sum(0), 1)[:, None]"),
+    ("row index off by one", "w_b[int(ids[b, t])] += g[b, t]", "w_b[(int(ids[b, t]) + 1) % V] += g[b, t]"),
+    ("ids of example 0 used for all", "w_b[int(ids[b, t])] += g[b, t]", "w_b[int(ids[0, t])] += g[b, t]"),
+    ("mean over b in the weight gradient", "        w += w_b\n", "        w += w_b / B\n"),
+    ("a repeated id overwrites instead of adding", "w_b[int(ids[b, t])] += g[b, t]", "w_b[int(ids[b, t])] = g[b, t]"),
+    ("per-example gradient not cleared between examples", "w_b = np.zeros((V, D))                       # example",
+     "w_b = w if b else np.zeros((V, D))           # example"),
 ]
 
 

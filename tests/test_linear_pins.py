@@ -120,7 +120,7 @@ MUTATIONS = [
     ("x not transposed (outer sum of rows)", "w_b = x[b].T @ g[b]", "w_b = np.outer(x[b].sum(0), g[b].sum(0))"),
     ("norm is a sum of abs", "s[b] = np.sum(w_b * w_b)", "s[b] = np.sum(np.abs(w_b))"),
     ("norm of the running total", "s[b] = np.sum(w_b * w_b)", "s[b] = np.sum((w + w_b) * (w + w_b))"),
-    ("mean over b in the weight gradient", "w += w_b ", "w += w_b / B "),
+    ("mean over b in the weight gradient", "        w += w_b\n", "        w += w_b / B\n"),
     ("square root taken", "s[b] = np.sum(w_b * w_b)", "s[b] = np.sqrt(np.sum(w_b * w_b))"),
 ]
 
