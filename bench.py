@@ -79,9 +79,6 @@ def build_layers(cfg, n_layers, stats_mode, log):
     import torch
     from paper_2411_00999_amd import binding, workloads
 
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    import parity_util as pu
-
     B, T, D, dtype, _ = workloads.SHAPES[cfg]
     workers = max(1, min(16, os.cpu_count() or 1, n_layers))
     layers, host_inputs = [], []
@@ -91,8 +88,8 @@ def build_layers(cfg, n_layers, stats_mode, log):
         for l, fut in enumerate(futs):
             inp = fut.result()
             f32 = dict(dtype=torch.float32, device="cuda")
-            L = dict(x=pu.to_device(inp.x, dtype), dy=pu.to_device(inp.dy, dtype),
-                     gamma=pu.to_device(inp.gamma, dtype))
+            L = dict(x=workloads.to_device(inp.x, dtype), dy=workloads.to_device(inp.dy, dtype),
+                     gamma=workloads.to_device(inp.gamma, dtype))
             L["dx"] = torch.empty_like(L["x"])
             L["dgamma"] = torch.empty(D, **f32)
             L["dbeta"] = torch.empty(D, **f32)

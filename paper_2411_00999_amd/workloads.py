@@ -208,3 +208,21 @@ def make_embedding_inputs(seed: int, B: int, T: int, D: int, V: int, dtype: str 
     if dtype == "bf16":
         g = round_to_bf16(g)
     return ids, g
+
+
+# ------------------------------------------------------------------ host <-> device plumbing
+def to_device(arr32: np.ndarray, dtype: str):
+    """float32 host values -> device tensor of the workload's storage type (exact)."""
+    import torch
+    if dtype == "bf16":
+        bits = bf16_bits(arr32)
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(arr32, dtype=np.float32)).cuda()
+
+
+def to_host64(t) -> np.ndarray:
+    """device tensor (fp32 or bf16) -> float64 numpy (exact)."""
+    import torch
+    if t.dtype == torch.bfloat16:
+        return t.float().cpu().numpy().astype(np.float64)
+    return t.cpu().numpy().astype(np.float64)

@@ -2,42 +2,33 @@
 
 Comparison rule (written out here because "relative 1e-5 / 2e-3" needs a definition where a
 zero-mean sum cancels and where the output itself is rounded to bf16):
-  for every output tensor, with ref the fp64 oracle value and rms = sqrt(mean(ref^2)),
-    (1)  ||out - ref||_2 / ||ref||_2                       <= tol
-    (2)  |out - ref| <= tol * (|ref| + rms) [+ half a bf16 ulp of ref for bf16 outputs]
-  For dx, rms in (2) is never taken smaller than the rms of the un-cancelled term rstd*dy*gamma:
+  for every output tensor, with ref the fp64 oracle value, rms = sqrt(mean(ref^2)) and
+  scale = max(rms, floor_rms):
+    (1)  ||out - ref||_2 <= tol * scale * sqrt(size)      (= tol * ||ref||_2 when no floor applies)
+    (2)  |out - ref| <= tol * (|ref| + scale) [+ half a bf16 ulp of ref for bf16 outputs]
+  BOTH are applied to every tensor with a non-zero reference or a non-zero floor.
+  For dx, floor_rms is the rms of the un-cancelled term rstd*dy*gamma:
   dx = rstd*(dyh - mean(dyh) - xhat*mean(dyh*xhat)) is a difference, and where it cancels
-  completely (D = 1: dx == 0 exactly) rounding errors scale with the terms, not the result.
-  tol = 1e-5 for fp32 inputs, 2e-3 for bf16 inputs.  Outputs that are fp32 sums (dgamma,
-  dbeta, per-example squared norms, big_sq) are held to 1e-5 for both input types, because
-  both sides read identical inputs and differ only in accumulation order.
+  (completely for D = 1: dx == 0 exactly) rounding errors scale with the terms, not the result.
+  tol = 1e-5 for fp32 inputs, 2e-3 for bf16 inputs.  A bf16 output carries its own rounding: the
+  correctly rounded oracle value is already ||rne_bf16(ref) - ref||_2 =: q away from ref (about
+  1.7e-3 * ||ref||_2 for bell-shaped data, so (1) leaves the arithmetic about 3e-4), and on a
+  small or oddly distributed tensor q alone can pass tol; the bound of (1) is therefore never
+  taken below q + 3e-4 * scale * sqrt(size).  Outputs that are fp32 sums (dgamma, dbeta,
+  per-example squared norms, big_sq) are held to 1e-5 for both input types, because both
+  sides read identical inputs and differ only in accumulation order.
 """
 from __future__ import annotations
 
 import numpy as np
 
+from paper_2411_00999_amd.workloads import to_device, to_host64  # noqa: F401  (used by the tests)
+
 TOL_F32 = 1e-5
 TOL_BF16 = 2e-3
 TOL_SUMS = 1e-5
 TOL_GNS = 1e-4
-
-
-def to_device(arr32: np.ndarray, dtype: str):
-    """float32 host values -> device tensor of the workload's storage type (exact)."""
-    import torch
-    from paper_2411_00999_amd import workloads
-    if dtype == "bf16":
-        bits = workloads.bf16_bits(arr32)
-        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(arr32, dtype=np.float32)).cuda()
-
-
-def to_host64(t) -> np.ndarray:
-    """device tensor (fp32 or bf16) -> float64 numpy (exact)."""
-    import torch
-    if t.dtype == torch.bfloat16:
-        return t.float().cpu().numpy().astype(np.float64)
-    return t.cpu().numpy().astype(np.float64)
+BF16_L2_SLACK = 3e-4
 
 
 def bf16_half_ulp(ref: np.ndarray) -> np.ndarray:
@@ -47,25 +38,37 @@ def bf16_half_ulp(ref: np.ndarray) -> np.ndarray:
     return 0.5 * 2.0 ** (e - 7)
 
 
+def rne_bf16(ref: np.ndarray) -> np.ndarray:
+    """float64 values rounded to the nearest bf16 number, ties to even (normal range)."""
+    q = 2.0 * bf16_half_ulp(ref)
+    return np.rint(ref / q) * q
+
+
 def check_close(name, out, ref, tol, bf16_output=False, floor_rms=0.0):
     out = np.asarray(out, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert out.shape == ref.shape, f"{name}: shape {out.shape} vs {ref.shape}"
     assert np.all(np.isfinite(out)), f"{name}: non-finite output"
     diff = np.abs(out - ref)
+    root_n = np.sqrt(max(ref.size, 1))
     nref = np.linalg.norm(ref.ravel())
-    rms = max(nref / np.sqrt(max(ref.size, 1)), floor_rms)
-    bound = tol * (np.abs(ref) + rms)
+    scale = max(nref / root_n, floor_rms)
+    # (2) elementwise
+    bound = tol * (np.abs(ref) + scale)
     if bf16_output:
         bound = bound + bf16_half_ulp(ref)
     worst = int(np.argmax(diff - bound))
     assert np.all(diff <= bound), (
         f"{name}: |out-ref|={diff.ravel()[worst]:.3e} > bound {bound.ravel()[worst]:.3e} "
         f"at flat index {worst} (ref {ref.ravel()[worst]:.6e}, out {out.ravel()[worst]:.6e})")
-    if nref > 0 and nref / np.sqrt(ref.size) >= floor_rms:
-        rel = np.linalg.norm((out - ref).ravel()) / nref
-        # the L2 bound gets the same output-rounding allowance as the elementwise one
-        allow = tol + (np.linalg.norm(bf16_half_ulp(ref).ravel()) / nref if bf16_output else 0.0)
+    # (1) L2, relative to the larger of ||ref|| and the floor
+    denom = scale * root_n
+    if denom > 0:
+        rel = np.linalg.norm((out - ref).ravel()) / denom
+        allow = tol
+        if bf16_output:
+            q = np.linalg.norm((rne_bf16(ref) - ref).ravel()) / denom
+            allow = max(tol, q + BF16_L2_SLACK)
         assert rel <= allow, f"{name}: L2 relative error {rel:.3e} > {allow:.3e}"
 
 
