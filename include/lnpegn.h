@@ -18,19 +18,28 @@
  *     All work is enqueued on it and the call returns before it completes; a
  *     call may therefore be captured into a HIP graph.
  *   - Outputs are overwritten, unless a flag of the call says they accumulate.
- *   - The return value is a lnpegn_status.  On any status other than LNPEGN_OK
- *     nothing was launched and no output was touched.
+ *   - The return value is a lnpegn_status.  Arguments are validated on the host before
+ *     anything is enqueued: LNPEGN_EINVAL, LNPEGN_EUNSUPPORTED and LNPEGN_EWORKSPACE mean that
+ *     nothing was launched and no output was touched.  LNPEGN_EHIP means that the HIP runtime
+ *     refused a launch (or an event call); a call is several launches, so those that went out
+ *     before the refused one stay enqueued and the outputs are then unspecified.
  *   - Results are bitwise reproducible from call to call for a fixed shape:
  *     no floating-point atomics are used anywhere.
  *   - Index arithmetic is 64-bit; B*T*D may exceed 2^31.
  *   - Any D >= 1 is computed correctly.  The bandwidth-tuned kernels need
  *     D % 8 == 0 (bf16) or D % 4 == 0 (fp32), D <= 8192
  *     and 16-byte aligned x, dy, dx; other cases take a slower generic kernel.
+ *   - Loading.  The library links against the HIP runtime (libamdhip64) by its soname.  A
+ *     process must hold ONE copy of that runtime: a host program that also loads another
+ *     package which ships a HIP runtime of its own (PyTorch-ROCm does) must load that package
+ *     first, so that this library binds to the copy already in the process; with two copies
+ *     every launch fails with hipErrorNoDevice (reported as LNPEGN_EHIP).
  */
 #ifndef LNPEGN_H
 #define LNPEGN_H
 
 #include <stddef.h>
+#include <stdint.h>
 
 #ifdef __cplusplus
 extern "C" {
@@ -159,8 +168,8 @@ int ln_bwd_ex(const void *x, const void *dy, const void *gamma, const float *mea
               size_t workspace_bytes, unsigned flags, void *stream);
 
 /*
- * RMSNorm variant (Appendix B: the per-example algorithm is "practically identical", the gradient
- * being with respect to the affine parameter):  rstd = 1/sqrt(mean_d x^2 + eps),  xhat = x*rstd,
+ * RMSNorm variant (Appendix B remarks that the per-example algorithm carries over unchanged, the
+ * gradient being with respect to the affine parameter):  rstd = 1/sqrt(mean_d x^2 + eps),  xhat = x*rstd,
  * y = gamma*xhat; there is no beta.
  *   rms_fwd     y [B,T,D] in dt; rstd [N] fp32 or NULL
  *   rms_bwd_ex  dx = rstd*(dyh - xhat*mean_d(dyh*xhat));  dgamma [D] = sum dy*xhat;

@@ -98,6 +98,9 @@ __device__ __forceinline__ void reduce_groups_body(const ReduceArgs &a, int g, i
         v1 += wsum[w][4 + comp][src_lane];
     }
     const bool single = a.G1 == 1;
+    // With a single group the sums go straight to dgamma / dbeta, on top of what they hold when
+    // accumulating; the group's OWN sums (own0, own1) are what an example's norm is taken from.
+    const float own0 = (float)v0, own1 = (float)v1;
     if (single && a.accumulate && col < a.D) {
         v0 += (double)a.dgamma[col];
         if (a.dbeta) v1 += (double)a.dbeta[col];
@@ -116,10 +119,17 @@ __device__ __forceinline__ void reduce_groups_body(const ReduceArgs &a, int g, i
         // squares of the values as stored (fp32), summed in fp64
         const double q0 = block_sum_f64(col < a.D ? (double)f0 * f0 : 0.0, slots[0]);
         const double q1 = block_sum_f64(col < a.D ? (double)f1 * f1 : 0.0, slots[1]);
+        double e0 = q0, e1 = q1;
+        if (a.pe_from_groups && single && a.accumulate) {
+            // one example per micro-batch: its norm is that of this call's sums (Appendix B steps 2
+            // and 6), not of the gradient accumulated so far
+            e0 = block_sum_f64(col < a.D ? (double)own0 * own0 : 0.0, slots[0]);
+            e1 = block_sum_f64(col < a.D ? (double)own1 * own1 : 0.0, slots[1]);
+        }
         if (tid == 0) {
             if (a.pe_from_groups) {
-                a.part_s[((int64_t)g * a.ntile + tile) * 2] = q0;
-                a.part_s[((int64_t)g * a.ntile + tile) * 2 + 1] = q1;
+                a.part_s[((int64_t)g * a.ntile + tile) * 2] = e0;
+                a.part_s[((int64_t)g * a.ntile + tile) * 2 + 1] = e1;
             }
             if (single) {
                 a.part_big[tile * 2] = q0;

@@ -185,3 +185,38 @@ def test_product_path_does_not_import_the_oracle():
     for name in os.listdir(os.path.join(pkg, "csrc")):
         text = open(os.path.join(pkg, "csrc", name)).read()
         assert "oracle/" not in text, name
+
+
+def test_header_compiles_alone_as_c():
+    """The public header is self-contained C: a translation unit that includes nothing else."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    for std in ("c99", "c11"):
+        r = subprocess.run([gcc, f"-std={std}", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                            HEADER], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+
+
+def test_c_program_calls_the_library(tmp_path):
+    """tests/c_caller/abi_caller.c, built with gcc against the header and liblnpegn.so, runs the host-only
+    entry points and the argument-validation paths from plain C."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    binding.load()
+    lib = binding.lib_path()
+    exe = str(tmp_path / "abi_caller")
+    src = os.path.join(ROOT, "tests", "c_caller", "abi_caller.c")
+    libdir = os.path.dirname(lib)
+    r = subprocess.run([gcc, "-std=c11", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"), src,
+                        "-o", exe, "-L", libdir, "-l:liblnpegn.so", f"-Wl,-rpath,{libdir}",
+                        "-Wl,-rpath-link,/opt/rocm/lib"], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "all checks passed" in r.stdout

@@ -178,7 +178,7 @@ def test_misaligned_pointers_take_the_generic_kernel():
 def test_bitwise_reproducible():
     inp = workloads.make_inputs(3, B=4, T=64, D=2048)
     a = pu.run_gpu(inp)
-    for _ in range(5):
+    for _ in range(10):
         b = pu.run_gpu(inp)
         for k in ("dx", "dgamma", "dbeta", "s_gamma", "s_beta", "big_sq"):
             np.testing.assert_array_equal(a[k], b[k], err_msg=k)
@@ -268,7 +268,11 @@ def test_forward_against_oracle(cfg, B, T, D):
 
 
 @pytest.mark.parametrize("cfg,B,T,D,defer", [(3, 4, 40, 2048, False), (2, 3, 21, 768, False),
-                                            (4, 300, 2, 1024, False), (3, 4, 40, 2048, True), (1, 2, 9, 257, True)])
+                                            (4, 300, 2, 1024, False), (3, 4, 40, 2048, True), (1, 2, 9, 257, True),
+                                            # one example per micro-batch (Section 5.1's setting), spanning several
+                                            # chunks: vector kernel and generic kernel, immediate and deferred
+                                            (3, 1, 200, 2048, False), (3, 1, 200, 2048, True),
+                                            (1, 1, 50, 257, False), (1, 1, 50, 257, True)])
 def test_gradient_accumulation_over_micro_batches(cfg, B, T, D, defer):
     """A micro-batches through LNPEGN_ACCUMULATE == the oracle on the concatenated batch."""
     import torch
