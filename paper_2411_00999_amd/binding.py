@@ -16,8 +16,9 @@ from . import build as _build
 F32, BF16 = 0, 1
 STATUS = {0: "LNPEGN_OK", 1: "LNPEGN_EINVAL", 2: "LNPEGN_EUNSUPPORTED", 3: "LNPEGN_EWORKSPACE",
           4: "LNPEGN_EHIP"}
+STATIC_SCRATCH_BYTES = 32 << 20     # LNPEGN_STATIC_SCRATCH_BYTES of the header
 EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "lnpegn_last_hip_error", "ln_fwd_stats", "ln_bwd",
-           "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning", "lnpegn_set_profile_events",
+           "ln_bwd_pegn", "ln_bwd_pegn_static", "gns_estimate", "lnpegn_set_tuning", "lnpegn_set_profile_events",
            "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred",
            "ln_fwd", "ln_bwd_ex", "rms_fwd", "rms_bwd_ex",
            "gns_ema_update", "gns_offline", "gns_linear_accum_steps",
@@ -62,6 +63,7 @@ def load() -> ctypes.CDLL:
     lib.ln_fwd_stats.argtypes = [vp, fp, fp, i, i, i, i, f, vp]
     lib.ln_bwd.argtypes = [vp, vp, vp, fp, fp, vp, fp, fp, i, i, i, i, i, f, vp, sz, vp]
     lib.ln_bwd_pegn.argtypes = [vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, i, i, i, i, i, f, vp, sz, vp]
+    lib.ln_bwd_pegn_static.argtypes = [vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, i, i, i, i, i, f, vp]
     lib.ln_bwd_deferred.argtypes = lib.ln_bwd.argtypes
     lib.ln_bwd_pegn_deferred.argtypes = lib.ln_bwd_pegn.argtypes
     lib.lnpegn_reduce_deferred.argtypes = [ctypes.POINTER(ctypes.c_void_p), i, i, i, i, i, vp]
@@ -83,7 +85,7 @@ def load() -> ctypes.CDLL:
     lib.lnpegn_set_tuning.argtypes = [i, i]
     lib.lnpegn_set_profile_events.argtypes = [vp, vp]
     lib.lnpegn_stream_probe.argtypes = [vp, vp, vp, sz, i, vp]
-    for name in ("ln_fwd_stats", "ln_bwd", "ln_bwd_pegn", "gns_estimate", "lnpegn_set_tuning",
+    for name in ("ln_fwd_stats", "ln_bwd", "ln_bwd_pegn", "ln_bwd_pegn_static", "gns_estimate", "lnpegn_set_tuning",
                  "lnpegn_set_profile_events", "lnpegn_stream_probe", "ln_bwd_deferred",
                  "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred", "ln_fwd", "ln_bwd_ex",
                  "rms_fwd", "rms_bwd_ex", "gns_ema_update", "gns_offline", "gns_linear_accum_steps",
@@ -367,6 +369,21 @@ def ln_bwd_pegn(x, dy, gamma, eps: float, mean=None, rstd=None, dx=None, dgamma=
             workspace.numel(), _stream(stream))
     if rc:
         raise LnpegnError("ln_bwd_pegn", rc)
+    return dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq
+
+
+def ln_bwd_pegn_static(x, dy, gamma, eps: float, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq=None,
+                       mean=None, rstd=None, stream=None):
+    """ln_bwd_pegn without a workspace: the library's own fixed scratch is used and nothing is
+    allocated, here or in the library -- every output buffer is the caller's.  Shapes whose workspace
+    would exceed STATIC_SCRATCH_BYTES raise LnpegnError(LNPEGN_EWORKSPACE)."""
+    B, T, D = _check3(x)
+    _check3(dy)
+    rc = load().ln_bwd_pegn_static(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(dx), _ptr(dgamma),
+                                   _ptr(dbeta), _ptr(pe_gamma_sq), _ptr(pe_beta_sq), _ptr(big_sq), B, T, D,
+                                   _dt(x), _dt(gamma), eps, _stream(stream))
+    if rc:
+        raise LnpegnError("ln_bwd_pegn_static", rc)
     return dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq
 
 

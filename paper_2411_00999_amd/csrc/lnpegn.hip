@@ -1,14 +1,23 @@
 // C ABI of the lnpegn library (declared in include/lnpegn.h): argument validation, launch
 // planning and kernel launches.  No allocation, no synchronisation, no state between calls
-// apart from the process-wide launch-shape overrides of lnpegn_set_tuning().
+// apart from the process-wide launch-shape overrides of lnpegn_set_tuning() and the per-device
+// address of the fixed scratch of ln_bwd_pegn_static.
 #include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <mutex>
 
 #include "../../include/lnpegn.h"
 #include "lnpegn_finalize.h"
 #include "lnpegn_tracker.h"
 #include "lnpegn_rows.h"
+
+// Scratch of ln_bwd_pegn_static: the workspace of a backward call, held by the library itself so that the
+// call allocates nothing.  One copy per GPU the library runs on, kept until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress; kernels are given the address it returns.
+constexpr size_t kStaticScratchBytes = LNPEGN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace lnpegn {
 thread_local int g_last_hip_error = 0;   // hipError_t behind this thread's latest LNPEGN_EHIP from a row kernel launch
@@ -163,6 +172,29 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
 }
 
 bool shape_ok(int B, int T, int D) { return B > 0 && T > 0 && D > 0; }
+
+// Device address of `scratch` on the current device, looked up once per device and kept.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr || reinterpret_cast<uintptr_t>(ptr) % kAlign) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 bool dtype_ok(int dt) { return dt == LNPEGN_F32 || dt == LNPEGN_BF16; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -477,6 +509,24 @@ int ln_bwd_pegn(const void *x, const void *dy, const void *gamma, const float *m
 {
     return run_bwd(true, false, false, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq,
                    B, T, D, dt, gamma_dt, eps, workspace, workspace_bytes, stream);
+}
+
+int ln_bwd_pegn_static(const void *x, const void *dy, const void *gamma, const float *mean, const float *rstd,
+                       void *dx, float *dgamma, float *dbeta, float *pe_gamma_sq, float *pe_beta_sq, float *big_sq,
+                       int B, int T, int D, lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *stream)
+{
+    // validate the shape against the fixed scratch before touching the device
+    if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
+    if (!dtype_ok(dt) || !dtype_ok(gamma_dt)) return LNPEGN_EUNSUPPORTED;
+    if (lnpegn_workspace_bytes(B, T, D, dt) > kStaticScratchBytes) return LNPEGN_EWORKSPACE;
+    void *ws = nullptr;
+    const hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return LNPEGN_EHIP;
+    }
+    return run_bwd(true, false, false, false, x, dy, gamma, mean, rstd, dx, dgamma, dbeta, pe_gamma_sq, pe_beta_sq, big_sq,
+                   B, T, D, dt, gamma_dt, eps, ws, kStaticScratchBytes, stream);
 }
 
 int ln_bwd_deferred(const void *x, const void *dy, const void *gamma, const float *mean,
