@@ -118,6 +118,12 @@ def build_layers(cfg, n_layers, stats_mode, log):
     return layers, shared, host_inputs
 
 
+def workloads_shape_bytes(cfg, dtype=""):
+    from paper_2411_00999_amd import workloads
+    B, T, D, dt0, _ = workloads.SHAPES[cfg]
+    return B * T * D * (2 if (dtype or dt0) == "bf16" else 4)
+
+
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -236,6 +242,120 @@ def embedding_leg(shape_name, steps, warmup, log):
     }
 
 
+def quantiles(values):
+    """median, 10th and 90th percentile of a list of timings."""
+    v = sorted(values)
+    n = len(v)
+    pick = lambda q: v[min(n - 1, max(0, int(round(q * (n - 1)))))]
+    return {"median": round(pick(0.5), 3), "p10": round(pick(0.1), 3), "p90": round(pick(0.9), 3)}
+
+
+ROTATE_BYTES = 512 << 20     # bytes touched between two uses of a buffer set in the cache-cold legs
+# HBM bytes per row-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (fused kernel), per workload;
+# the profiles/ summary of each workload has the command and the copy-kernel scale.  null = not measured.
+MEASURED_ROW_TRAFFIC = {}
+
+
+def config_leg(cfg, iters, log, sets=None, dtype=None, stats_mode="recompute"):
+    """One workload of the benchmark's configs, one layer: ln_bwd_pegn and the plain ln_bwd interleaved on one
+    stream, every call with HIP events on its row kernel's own dispatch and a second pair around the whole call
+    (row kernel + reduction launches).  Cache-cold: the calls rotate over enough buffer sets that at least
+    ROTATE_BYTES are touched before a set is used again (the 256 MB memory-side cache cannot hold them); the
+    hot figures repeat the measurement on one set."""
+    import torch
+    from paper_2411_00999_amd import binding, workloads
+    B, T, D, dt0, _ = workloads.SHAPES[cfg]
+    dtype = dtype or dt0
+    esz = 2 if dtype == "bf16" else 4
+    N = B * T
+    alg = 3 * N * D * esz
+    n_sets = sets or max(2, -(-ROTATE_BYTES // alg) + 1)
+    dt_code = binding.BF16 if dtype == "bf16" else binding.F32
+    f32 = dict(dtype=torch.float32, device="cuda")
+    S = []
+    for k in range(n_sets):
+        x, dy, gamma = workloads.make_inputs_device(cfg, k, dtype)
+        L = dict(x=x, dy=dy, gamma=gamma, dx=torch.empty_like(x), mean=None, rstd=None)
+        if stats_mode == "saved":
+            L["mean"], L["rstd"] = binding.ln_fwd_stats(x, workloads.EPS)
+        S.append(L)
+    out = dict(dgamma=torch.empty(D, **f32), dbeta=torch.empty(D, **f32), pe_g=torch.empty(B, **f32),
+               pe_b=torch.empty(B, **f32), big=torch.empty(2, **f32))
+    ws = binding.alloc_workspace(B, T, D, dt_code)
+    hip = HipEvents()
+    eps = workloads.EPS
+
+    def call(L, plain, ev):
+        if ev is not None:
+            binding.set_profile_events(ev[0], ev[1])
+        if plain:
+            binding.ln_bwd(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"], dx=L["dx"],
+                           dgamma=out["dgamma"], dbeta=out["dbeta"], workspace=ws)
+        else:
+            binding.ln_bwd_pegn(L["x"], L["dy"], L["gamma"], eps, mean=L["mean"], rstd=L["rstd"], dx=L["dx"],
+                                dgamma=out["dgamma"], dbeta=out["dbeta"], pe_gamma_sq=out["pe_g"],
+                                pe_beta_sq=out["pe_b"], big_sq=out["big"], workspace=ws)
+
+    def measure(rotate):
+        n_warm = max(4, 2 * n_sets) if rotate else 6
+        pairs = [(hip.create(), hip.create()) for _ in range(2 * iters)]
+        outer = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(2 * iters)]
+        c = 0
+        for _ in range(n_warm):
+            call(S[c % n_sets if rotate else 0], c & 1, None)
+            c += 1
+        torch.cuda.synchronize()
+        for i in range(2 * iters):            # even i: fused, odd i: plain
+            L = S[c % n_sets if rotate else 0]
+            c += 1
+            outer[i][0].record()
+            call(L, i & 1, pairs[i])
+            outer[i][1].record()
+        torch.cuda.synchronize()
+        res = {}
+        for which, off in (("fused", 0), ("plain", 1)):
+            k_us = [hip.elapsed_ms(*pairs[i]) * 1e3 for i in range(off, 2 * iters, 2)]
+            c_us = [outer[i][0].elapsed_time(outer[i][1]) * 1e3 for i in range(off, 2 * iters, 2)]
+            kq, cq = quantiles(k_us), quantiles(c_us)
+            res[which] = {"row_kernel_us": kq, "call_us": cq,
+                          "row_kernel_GBps": round(alg / kq["median"] / 1e3, 1),
+                          "row_kernel_frac_of_peak": round(alg / kq["median"] / 1e3 / HBM_PEAK_GBS, 4),
+                          "call_GBps": round(alg / cq["median"] / 1e3, 1)}
+        res["overhead_row_kernel_pct"] = round(100.0 * (res["fused"]["row_kernel_us"]["median"] /
+                                                        res["plain"]["row_kernel_us"]["median"] - 1.0), 2)
+        res["overhead_call_pct"] = round(100.0 * (res["fused"]["call_us"]["median"] /
+                                                  res["plain"]["call_us"]["median"] - 1.0), 2)
+        for a, b in pairs:
+            hip.destroy(a)
+            hip.destroy(b)
+        return res
+
+    cold = measure(True)
+    hot = measure(False)
+    log(f"workload {cfg} {dtype} B={B} T={T} D={D}: cold row kernel fused {cold['fused']['row_kernel_us']['median']:.1f} us "
+        f"({cold['fused']['row_kernel_GBps']:.0f} GB/s) plain {cold['plain']['row_kernel_us']['median']:.1f} us, "
+        f"overhead {cold['overhead_row_kernel_pct']:+.1f} %; calls {cold['fused']['call_us']['median']:.1f} / "
+        f"{cold['plain']['call_us']['median']:.1f} us; hot {hot['fused']['row_kernel_us']['median']:.1f} / "
+        f"{hot['plain']['row_kernel_us']['median']:.1f} us")
+    small = alg < (64 << 20)
+    return {
+        "workload": f"configs[{cfg - 1}]: B={B} T={T} D={D} {dtype}, one layer, ln_bwd_pegn vs ln_bwd interleaved, "
+                    f"row stats {stats_mode}, immediate reduction",
+        "algorithmic_bytes_per_launch": alg,
+        "regime": ("launch-bound: the call is shorter than its launches' latency; not a bandwidth point" if small
+                   else "bandwidth-bound"),
+        "iterations": iters,
+        "cold": dict(cold, cache=f"cold: {n_sets} buffer sets rotated, >= {(n_sets - 1) * alg >> 20} MiB touched "
+                                 f"between two uses of a set"),
+        "hot": dict(hot, cache="hot: one buffer set reused (fits the 256 MB memory-side cache)" if alg < (256 << 20)
+                    else "one buffer set reused (larger than the 256 MB memory-side cache)"),
+        "roofline": {"kernel": "ln_bwd_rows_kernel (fused call), cold", "bound": "hbm",
+                     "achieved": cold["fused"]["row_kernel_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": cold["fused"]["row_kernel_frac_of_peak"],
+                     "traffic": MEASURED_ROW_TRAFFIC.get((cfg, dtype))},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -250,6 +370,14 @@ def main():
     ap.add_argument("--only-fused", action="store_true",
                     help="profiling aid: skip the plain ln_bwd, the other reduction mode and the probe, so "
                          "that a kernel trace of this run holds fused dispatches only")
+    ap.add_argument("--only-plain", action="store_true",
+                    help="profiling aid: run only the plain ln_bwd step, so that a kernel trace of this run holds "
+                         "plain dispatches only")
+    ap.add_argument("--configs", default="1,2,4,5",
+                    help="workloads measured one layer at a time next to the headline (comma list, '' for none)")
+    ap.add_argument("--configs-only", action="store_true", help="run only the per-workload legs and print them")
+    ap.add_argument("--config-iters", type=int, default=0, help="timed fused/plain pairs per workload (0 = automatic)")
+    ap.add_argument("--config-dtype", default="", help="override the storage type of the per-workload legs (f32/bf16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-linear", action="store_true", help="skip the linear-layer per-example-norm leg")
     ap.add_argument("--linear-only", action="store_true",
@@ -294,6 +422,26 @@ def main():
     def log(msg):
         if not args.quiet:
             print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    def per_config_legs():
+        import torch
+        legs = {}
+        for c in [int(v) for v in args.configs.split(",") if v]:
+            alg = 3 * workloads_shape_bytes(c, args.config_dtype)
+            iters = args.config_iters or (50 if alg > (1 << 30) else 200)
+            legs[f"workload{c}"] = config_leg(c, iters, log, dtype=args.config_dtype or None, stats_mode=args.stats)
+            torch.cuda.empty_cache()
+        return legs
+
+    if args.configs_only:
+        import torch
+        from paper_2411_00999_amd import binding
+        if not torch.cuda.is_available():
+            sys.exit("bench.py: no GPU visible")
+        torch.cuda.set_device(0)
+        binding.load()
+        print(json.dumps(per_config_legs()), flush=True)
+        return
 
     import numpy as np
     import torch

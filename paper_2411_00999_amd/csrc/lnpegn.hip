@@ -11,6 +11,7 @@
 #include "../../include/lnpegn.h"
 #include "lnpegn_finalize.h"
 #include "lnpegn_tracker.h"
+#include "lnpegn_launch.h"
 #include "lnpegn_rows.h"
 
 // Scratch of ln_bwd_pegn_static: the workspace of a backward call, held by the library itself so that the
@@ -30,6 +31,10 @@ int g_chunks_plain = 0;
 int g_waves = 0;
 int g_vpt_max = 0;          // cap on 16-byte vectors per lane and array (0: automatic)
 int g_xcd = -1;        // hand neighbouring chunks to the same XCD: 0 never, 1 always, -1 automatic
+int g_dx_cached = -1;  // dx stores write-back instead of streaming: 0 never, 1 always, -1 automatic
+int g_exp = 0;
+int g_lds_pad = 0;
+long long *g_trace = nullptr;
 int g_stagger = -1;   // rows between the sweep starts of consecutive examples (-1 = automatic)
 // one-shot profiling events around the row kernel (null = disarmed)
 hipEvent_t g_ev_start = nullptr;
@@ -47,6 +52,7 @@ inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 struct Plan {
     // row kernel
+    bool plain;       // no per-example outputs: the plain backward's kernel
     bool fast;        // vectorised kernels usable (shape-wise; pointer alignment checked apart)
     bool sync;        // several waves per row
     int vpt;          // 16-byte vectors per lane
@@ -73,6 +79,7 @@ constexpr size_t kHeaderBytes = 256;
 Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
 {
     Plan p{};
+    p.plain = !pegn;
     const int E = dt == LNPEGN_BF16 ? 8 : 4;
     const int64_t N = (int64_t)B * T;
     int vpt_max = 16 / E;                            // at most 16 elements per lane
@@ -109,7 +116,7 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
     {
         const size_t xchg = (size_t)((8 * nwaves + 2 * p.S + 3) & ~3) * sizeof(float);
         const size_t merge = p.fast && p.R > 1 ? (size_t)nwaves * 2 * p.vpt * E * kWave * sizeof(float) : 0;
-        p.lds_bytes = xchg + (merge > 512 ? merge : 512);
+        p.lds_bytes = xchg + (merge > 512 ? merge : 512) + (size_t)g_lds_pad * 1024;
     }
     // one full round of resident workgroups unless told otherwise
     int target = pegn ? g_chunks_pegn : g_chunks_plain;
@@ -198,66 +205,6 @@ hipError_t static_scratch(void **out)
 bool dtype_ok(int dt) { return dt == LNPEGN_F32 || dt == LNPEGN_BF16; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// ------------------------------------------------------------------------------------------
-// row kernel dispatch
-// ------------------------------------------------------------------------------------------
-// One launch of a row kernel.  When profiling events are armed they are attached to this very
-// dispatch, so their elapsed time is the kernel's own execution time.
-struct RowLaunch {
-    hipStream_t stream;
-    hipEvent_t ev_start, ev_stop;
-};
-
-template <typename K>
-hipError_t launch_row_kernel(K kernel, dim3 grid, dim3 block, size_t lds, const RowLaunch &rl,
-                             const RowArgs &a)
-{
-    if (rl.ev_start) {
-        RowArgs copy = a;
-        void *args[] = {&copy};
-        return hipExtLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, args, lds,
-                                  rl.stream, rl.ev_start, rl.ev_stop, 0);
-    }
-    kernel<<<grid, block, lds, rl.stream>>>(a);
-    return hipGetLastError();
-}
-
-template <typename T, int kVpt, bool kSaved>
-hipError_t launch_rows_vpt(const Plan &p, const RowArgs &a, const RowLaunch &rl)
-{
-    const dim3 grid((unsigned)p.n_slots), block(64 * p.R * p.S);
-    const bool full = p.nvec == 64 * p.S * kVpt;
-    auto go = [&](auto kernel) { return launch_row_kernel(kernel, grid, block, p.lds_bytes, rl, a); };
-    switch (p.S) {
-        case 1: return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, 1, true>)
-                            : go(ln_bwd_rows_kernel<T, kVpt, kSaved, 1, false>);
-        case 2: return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, 2, true>)
-                            : go(ln_bwd_rows_kernel<T, kVpt, kSaved, 2, false>);
-        case 4: return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, 4, true>)
-                            : go(ln_bwd_rows_kernel<T, kVpt, kSaved, 4, false>);
-        case 8: return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, 8, true>)
-                            : go(ln_bwd_rows_kernel<T, kVpt, kSaved, 8, false>);
-        default: return full ? go(ln_bwd_rows_kernel<T, kVpt, kSaved, 0, true>)
-                             : go(ln_bwd_rows_kernel<T, kVpt, kSaved, 0, false>);
-    }
-}
-
-template <typename T, bool kSaved>
-hipError_t launch_rows(const Plan &p, const RowArgs &a, const RowLaunch &rl)
-{
-    if (!p.fast)
-        return launch_row_kernel(ln_bwd_rows_generic_kernel<T, kSaved>, dim3((unsigned)p.n_slots),
-                                 dim3(256), 0, rl, a);
-    // at most 16 elements per lane: 2 vectors of 8 bf16, 4 vectors of 4 fp32
-    if constexpr (Vec<T>::kElems == 4) {
-        if (p.vpt == 3) return launch_rows_vpt<T, 3, kSaved>(p, a, rl);
-        if (p.vpt == 4) return launch_rows_vpt<T, 4, kSaved>(p, a, rl);
-    }
-    if (p.vpt == 1) return launch_rows_vpt<T, 1, kSaved>(p, a, rl);
-    if (p.vpt == 2) return launch_rows_vpt<T, 2, kSaved>(p, a, rl);
-    return hipErrorInvalidValue;
-}
-
 int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, const void *dy, const void *gamma, const float *mean,
             const float *rstd, void *dx, float *dgamma, float *dbeta, float *pe_gamma_sq,
             float *pe_beta_sq, float *big_sq, int B, int T, int D, int dt, int gamma_dt, float eps,
@@ -289,21 +236,24 @@ int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, con
     const bool xcd = g_xcd >= 0 ? g_xcd != 0 : p.S >= 4;
     a.xcd_chunks = (xcd && p.fast && p.n_slots % 8 == 0) ? (int)(p.n_slots / 8) : 0;
     a.S = p.S; a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.emit_pe = p.emit_pe; a.rms = rms;
-    a.eps = eps; a.inv_D = 1.0f / (float)D;
+    a.eps = eps; a.inv_D = 1.0f / (float)D; a.exp = g_exp; a.trace = g_trace;
     if (defer) {
         a.defer = reinterpret_cast<DeferHeader *>(ws);
         a.hdr = DeferHeader{dgamma, dbeta, pe_gamma_sq, pe_beta_sq, pegn ? big_sq : nullptr,
                             (int)p.n_slots, p.gs, p.G1, p.pe_from_groups ? 1 : 0, accumulate ? 1 : 0};
     }
 
-    hipError_t e;
     const bool saved = rstd != nullptr;
     const RowLaunch rl{s, g_ev_start, g_ev_stop};
     g_ev_start = g_ev_stop = nullptr;
-    if (dt == LNPEGN_BF16)
-        e = saved ? launch_rows<bf16_t, true>(p, a, rl) : launch_rows<bf16_t, false>(p, a, rl);
-    else
-        e = saved ? launch_rows<float, true>(p, a, rl) : launch_rows<float, false>(p, a, rl);
+    RowShape rs{};
+    rs.plain = p.plain; rs.fast = p.fast; rs.vpt = p.vpt; rs.S = p.S; rs.R = p.R; rs.nvec = p.nvec;
+    rs.n_slots = p.n_slots; rs.lds_bytes = p.lds_bytes;
+    // measured: write-back stores of dx help while dx fits the memory-side cache next to the reads
+    rs.dx_cached = g_dx_cached >= 0 ? g_dx_cached != 0
+                                    : (int64_t)B * T * D * (dt == LNPEGN_BF16 ? 2 : 4) <= ((int64_t)96 << 20);
+    const hipError_t e = dt == LNPEGN_BF16 ? (saved ? launch_rows_bf16_saved(rs, a, rl) : launch_rows_bf16_recompute(rs, a, rl))
+                                           : (saved ? launch_rows_f32_saved(rs, a, rl) : launch_rows_f32_recompute(rs, a, rl));
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;
         return LNPEGN_EHIP;
@@ -682,9 +632,19 @@ int lnpegn_set_tuning(int key, int value)
             if (value < 1 || value > 65535) return LNPEGN_EINVAL;
             g_emb_run_blocks = value;
             return LNPEGN_OK;
+        case 7: g_exp = value; return LNPEGN_OK;
+        case 8: g_lds_pad = value; return LNPEGN_OK;
+        case 9:
+            if (value > 2) return LNPEGN_EINVAL;
+            g_dx_cached = value - 1;
+            return LNPEGN_OK;
         default: return LNPEGN_EINVAL;
     }
 }
+
+#ifdef LNPEGN_TRACE
+int lnpegn_set_trace(void *p) { g_trace = static_cast<long long *>(p); return 0; }
+#endif
 
 int lnpegn_stream_probe(const void *a, const void *b, void *out, size_t bytes, int mode, void *stream)
 {

@@ -8,6 +8,13 @@ namespace lnpegn {
 
 constexpr int kWave = 64;
 
+// What a deferred backward call leaves at the start of its workspace for the batched reduction
+// (written by the row kernel, read by the reduction kernels).
+struct DeferHeader {
+    float *dgamma, *dbeta, *pe_gamma_sq, *pe_beta_sq, *big_sq;
+    int n_slots, gs, G1, pe_from_groups, accumulate;
+};
+
 // ---------------------------------------------------------------------------------------
 // Wave64 all-lanes sum on the DPP cross-lane network (no LDS traffic).  The order of the
 // additions is fixed, so the result is reproducible.  Every lane of the wave must be active.
@@ -94,6 +101,32 @@ struct bf16_t {
     uint16_t bits;
 };
 
+// ---------------------------------------------------------------------------------------
+// Buffer addressing.  A row is described by a buffer resource (base address, size in bytes); a
+// lane whose byte offset lies beyond the size reads zeros and its stores are dropped by the
+// hardware, so rows that do not fill every lane need no branch around their memory accesses.
+// kAux selects the cache policy of the access: 0 = default (cached, write-back), 1 = sc0,
+// 2 = nt (streaming), 16 = sc1, and their sums.
+// ---------------------------------------------------------------------------------------
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, int bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+
+template <int kAux>
+__device__ __forceinline__ u32x4_t buffer_load16(rsrc_t r, int byte_offset)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, kAux);
+}
+
+template <int kAux>
+__device__ __forceinline__ void buffer_store16(rsrc_t r, int byte_offset, u32x4_t v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_offset, 0, kAux);
+}
+
 template <typename T>
 struct Vec;
 
@@ -111,6 +144,18 @@ struct Vec<float> {
     {
         const f32x4_t t = {v.x, v.y, v.z, v.w};
         __builtin_nontemporal_store(t, reinterpret_cast<f32x4_t *>(p));
+    }
+    template <int kAux>
+    __device__ static __forceinline__ Raw load_buf(rsrc_t r, int byte_offset)
+    {
+        const f32x4_t t = __builtin_bit_cast(f32x4_t, buffer_load16<kAux>(r, byte_offset));
+        return make_float4(t.x, t.y, t.z, t.w);
+    }
+    template <int kAux>
+    __device__ static __forceinline__ void store_buf(rsrc_t r, int byte_offset, const Raw &v)
+    {
+        const f32x4_t t = {v.x, v.y, v.z, v.w};
+        buffer_store16<kAux>(r, byte_offset, __builtin_bit_cast(u32x4_t, t));
     }
     __device__ static __forceinline__ void unpack(const Raw &r, float (&f)[4])
     {
@@ -146,6 +191,18 @@ struct Vec<bf16_t> {
     {
         const u32x4_t t = {v.x, v.y, v.z, v.w};
         __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t *>(p));
+    }
+    template <int kAux>
+    __device__ static __forceinline__ Raw load_buf(rsrc_t r, int byte_offset)
+    {
+        const u32x4_t t = buffer_load16<kAux>(r, byte_offset);
+        return make_uint4(t.x, t.y, t.z, t.w);
+    }
+    template <int kAux>
+    __device__ static __forceinline__ void store_buf(rsrc_t r, int byte_offset, const Raw &v)
+    {
+        const u32x4_t t = {v.x, v.y, v.z, v.w};
+        buffer_store16<kAux>(r, byte_offset, t);
     }
     __device__ static __forceinline__ void unpack(const Raw &r, float (&f)[8])
     {

@@ -30,12 +30,6 @@ struct ReduceArgs {
     int accumulate;        // dgamma, dbeta: add to what is there (gradient accumulation) instead of overwrite
 };
 
-// What a deferred backward call leaves at the start of its workspace for the batched reduction.
-struct DeferHeader {
-    float *dgamma, *dbeta, *pe_gamma_sq, *pe_beta_sq, *big_sq;
-    int n_slots, gs, G1, pe_from_groups, accumulate;
-};
-
 // These kernels are a handful of dependent memory round trips long, so every level issues its
 // loads in batches of eight before it adds them (in index order: the sums are reproducible).
 

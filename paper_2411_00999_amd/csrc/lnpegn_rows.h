@@ -17,7 +17,6 @@
 #include <type_traits>
 
 #include "lnpegn_device.h"
-#include "lnpegn_finalize.h"
 
 namespace lnpegn {
 
@@ -46,6 +45,8 @@ struct RowArgs {
                          //      (i % 8) * xcd_chunks + i / 8, so neighbouring chunks share an L2
     float eps;
     float inv_D;
+    int exp;             // EXPERIMENT bits
+    long long *trace;    // EXPERIMENT
 };
 
 // gamma for one 16-byte row vector, as fp32 (gamma may be stored in either type)
@@ -110,10 +111,11 @@ constexpr int rows_kernel_min_blocks(int kS, int elems)
     return elems > 8 ? 1 : rows_kernel_narrow4(kS, elems) ? 2 : 4;
 }
 
-template <typename T, int kVpt, bool kSaved, int kS, bool kFull>
-__global__ __launch_bounds__(rows_kernel_max_threads(kS, kVpt * Vec<T>::kElems),
-                             rows_kernel_min_blocks(kS, kVpt * Vec<T>::kElems))
-void ln_bwd_rows_kernel(RowArgs a)
+// kPlain: the plain backward (one partition "example" spanning the whole tensor, never any
+// per-example output); it is a kernel of its own name so that a kernel trace tells the two apart.
+// kDxCached: dx is stored write-back (cached) instead of streaming.
+template <typename T, int kVpt, bool kSaved, int kS, bool kFull, bool kPlain, bool kDxCached>
+__device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
 {
     using V = Vec<T>;
     using Raw = typename V::Raw;
@@ -121,9 +123,28 @@ void ln_bwd_rows_kernel(RowArgs a)
     constexpr bool kSync = kS != 1;
     // x and dy are read once: the streaming hint pays for narrow rows and costs on wide ones (measured)
     constexpr bool kStreamLoads = kS == 1 || kS == 2 || rows_kernel_narrow4(kS, kVpt * E);
+#ifndef LNPEGN_LD_AUX
+#define LNPEGN_LD_AUX (kStreamLoads ? 2 : 0)
+#endif
+#ifndef LNPEGN_ST_AUX
+#define LNPEGN_ST_AUX 2
+#endif
+#ifndef LNPEGN_ST_AUX_SMALL
+#define LNPEGN_ST_AUX_SMALL 0
+#endif
+    constexpr int kLoadAux = LNPEGN_LD_AUX;
     constexpr int NF = 2 * kVpt * E;  // accumulator floats per lane
     constexpr int KL = kVpt - 1;      // only a lane's last vector slot can be padding
     extern __shared__ __align__(16) float lds[];
+#ifdef LNPEGN_TRACE
+    int tr_n = 0;
+    const bool tr_on = a.trace && (threadIdx.x == 0) && (blockIdx.x % 37 == 0) && blockIdx.x / 37 < 8;
+    long long *tr = a.trace + (blockIdx.x / 37) * 256;
+#define TR() do { if (tr_on && tr_n < 255) tr[1 + tr_n++] = clock64(); } while (0)
+#else
+#define TR() do {} while (0)
+#endif
+    TR();
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -148,12 +169,15 @@ void ln_bwd_rows_kernel(RowArgs a)
 #pragma unroll
     for (int k = 0; k < kVpt; ++k) vidx[k] = (k * S + ws) * kWave + lane;
     const bool ok_last = kFull ? true : vidx[KL] < a.nvec;
-    const int v_last = ok_last ? vidx[KL] : 0;     // padded lanes load a valid vector and drop it
+    const int v_last = ok_last ? vidx[KL] : 0;     // gamma of a padded lane: a valid vector, then zeroed
     const int n_w = wave_valid_elems<kVpt, E>(ws, S, a.nvec);
 
-    const Raw *xv = static_cast<const Raw *>(a.x);
-    const Raw *dyv = static_cast<const Raw *>(a.dy);
-    Raw *dxv = static_cast<Raw *>(a.dx);
+    // Rows are addressed as buffers of one row each: a padded lane (vector index >= nvec) reads
+    // zeros and its store is dropped, with no branch around the access.
+    const int row_bytes = a.nvec * (int)sizeof(Raw);
+    const char *xbase = static_cast<const char *>(a.x);
+    const char *dybase = static_cast<const char *>(a.dy);
+    char *dxbase = static_cast<char *>(a.dx);
 
     auto row_of = [&](int m) {   // m-th row of the chunk -> global row index (wave-uniform)
         int u = j + m * a.C + t_rot;
@@ -168,19 +192,13 @@ void ln_bwd_rows_kernel(RowArgs a)
             st_mean = a.rms ? 0.f : a.mean[rr];
             st_rstd = a.rstd[rr];
         }
-        const int64_t off = (int64_t)rr * a.nvec;
-        const Raw *xrow = xv + off;
-        const Raw *drow = dyv + off;
+        const int64_t off = (int64_t)rr * row_bytes;
+        const rsrc_t rx = make_rsrc(xbase + off, row_bytes);
+        const rsrc_t rd = make_rsrc(dybase + off, row_bytes);
 #pragma unroll
         for (int k = 0; k < kVpt; ++k) {
-            const int v = k < KL ? vidx[k] : v_last;
-            if constexpr (kStreamLoads) {
-                xr[k] = V::load_stream(xrow + v);
-                dr[k] = V::load_stream(drow + v);
-            } else {
-                xr[k] = xrow[v];
-                dr[k] = drow[v];
-            }
+            xr[k] = V::template load_buf<kLoadAux>(rx, vidx[k] * (int)sizeof(Raw));
+            dr[k] = V::template load_buf<kLoadAux>(rd, vidx[k] * (int)sizeof(Raw));
         }
     };
 
@@ -234,17 +252,11 @@ void ln_bwd_rows_kernel(RowArgs a)
             r = row_of(mm);
 #pragma unroll
             for (int k = 0; k < kVpt; ++k) {
-                V::unpack(xr[k], xf[k]);
+                V::unpack(xr[k], xf[k]);   // padded lanes hold zeros: the buffer load returned them
                 V::unpack(dr[k], df[k]);
-                if (!kFull && k == KL) {
-#pragma unroll
-                    for (int e = 0; e < E; ++e) {
-                        xf[k][e] = ok_last ? xf[k][e] : 0.f;
-                        df[k][e] = ok_last ? df[k][e] : 0.f;
-                    }
-                }
             }
             const float saved_mean = st_mean, saved_rstd = st_rstd;   // this row's, before the prefetch
+            TR();
             if (mm + R < n_rows) load_row(mm + R, xr, dr);
             // pass 1: pivot = the wave's own mean (or the saved row mean)
             if constexpr (kSaved) {
@@ -282,6 +294,7 @@ void ln_bwd_rows_kernel(RowArgs a)
                 if (lane == 0) xchg[ws] = make_float4(s_dyh, s_dyx, s_x, m2);
             }
         }
+        TR();
         if constexpr (kSync) __syncthreads();
         if (act) {
             float rstd, shift_r = 0.f;   // shift_r = (pivot - mean) * rstd
@@ -330,7 +343,8 @@ void ln_bwd_rows_kernel(RowArgs a)
             // pass 3: dx = rstd*(dyh - c2 - xhat*c1), c1 = rstd*mean_d(dyh*(x-mean)), c2 = mean_d(dyh)
             const float k1 = -rstd * rstd * s_dyx * a.inv_D;
             const float k2 = a.rms ? 0.f : -rstd * s_dyh * a.inv_D;   // RMSNorm has no mean(dyh) term
-            Raw *orow = dxv + (int64_t)r * a.nvec;
+            const rsrc_t ro = make_rsrc(dxbase + (int64_t)r * row_bytes, row_bytes);
+            Raw packed[kVpt];
 #pragma unroll
             for (int k = 0; k < kVpt; ++k) {
                 float o[E];
@@ -341,20 +355,39 @@ void ln_bwd_rows_kernel(RowArgs a)
                     acc_g[k][e] += df[k][e] * xhat;
                     acc_b[k][e] += df[k][e];
                 }
-                if (k < KL || ok_last) V::store_stream(orow + vidx[k], V::pack(o));
+                packed[k] = V::pack(o);
             }
+            // dx is written once and not read back here.  Streaming stores for tensors that no cache
+            // holds, write-back stores where the memory-side cache can take them: a compile-time choice,
+            // because a branch around a store makes the compiler wait for every store at the loop head
+#pragma unroll
+            for (int k = 0; k < kVpt; ++k)
+                V::template store_buf<kDxCached ? LNPEGN_ST_AUX_SMALL : LNPEGN_ST_AUX>(
+                    ro, vidx[k] * (int)sizeof(Raw), packed[k]);
         }
         parity ^= 1;
+        TR();
     };
 
     using Full = std::integral_constant<bool, false>;
     using Tail = std::integral_constant<bool, true>;
-    for (int it = 0; it < n_full; ++it) {
+    // The first row is taken outside the loop so that the loop is entered in the state it
+    // repeats: next row's loads issued, then this row's stores.  The wait for a row's data can
+    // then leave the younger stores outstanding (vmcnt counts loads and stores in issue order);
+    // entered straight from the prologue, the compiler has to wait for everything at the loop
+    // head, i.e. for the previous row's stores to be acknowledged by memory, once per row.
+    if (n_full > 0) {
+        process(Full{}, m);
+        m += R;
+    }
+    for (int it = 1; it < n_full; ++it) {
         process(Full{}, m);
         m += R;
     }
     if (has_tail) process(Tail{}, m);
 
+    TR();
+    if (a.exp & 2) return;
     // ---- hand the chunk's column sums to the workspace ----
     float *out_g = a.part + (int64_t)chunk * 2 * a.D;
     float *out_b = out_g + a.D;
@@ -413,7 +446,8 @@ void ln_bwd_rows_kernel(RowArgs a)
             }
         }
     }
-    if (a.emit_pe) {
+    TR();
+    if (!kPlain && a.emit_pe && !(a.exp & 1)) {
         // Appendix B steps 2 and 6 for the example this workgroup owns entirely
         __syncthreads();   // the merge buffer is reused as the reduction scratch
         double *slots = reinterpret_cast<double *>(merge);
@@ -424,6 +458,26 @@ void ln_bwd_rows_kernel(RowArgs a)
             if (a.pe_beta_sq) a.pe_beta_sq[b] = (float)tb;
         }
     }
+    TR();
+#ifdef LNPEGN_TRACE
+    if (tr_on) tr[0] = tr_n;
+#endif
+}
+
+template <typename T, int kVpt, bool kSaved, int kS, bool kFull, bool kDxCached>
+__global__ __launch_bounds__(rows_kernel_max_threads(kS, kVpt * Vec<T>::kElems),
+                             rows_kernel_min_blocks(kS, kVpt * Vec<T>::kElems))
+void ln_bwd_rows_kernel(RowArgs a)
+{
+    ln_bwd_rows_body<T, kVpt, kSaved, kS, kFull, false, kDxCached>(a);
+}
+
+template <typename T, int kVpt, bool kSaved, int kS, bool kFull, bool kDxCached>
+__global__ __launch_bounds__(rows_kernel_max_threads(kS, kVpt * Vec<T>::kElems),
+                             rows_kernel_min_blocks(kS, kVpt * Vec<T>::kElems))
+void ln_bwd_plain_rows_kernel(RowArgs a)
+{
+    ln_bwd_rows_body<T, kVpt, kSaved, kS, kFull, true, kDxCached>(a);
 }
 
 // ---------------------------------------------------------------------------------------

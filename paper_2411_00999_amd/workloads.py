@@ -226,3 +226,40 @@ def to_host64(t) -> np.ndarray:
     if t.dtype == torch.bfloat16:
         return t.float().cpu().numpy().astype(np.float64)
     return t.cpu().numpy().astype(np.float64)
+
+
+def make_inputs_device(config: int, set_index: int = 0, dtype: Optional[str] = None):
+    """Workload ``config`` at full size drawn ON the GPU (torch generator, seeded by workload and set index):
+    (x, dy, gamma) device tensors with the workload's distributions.  For timing legs that rotate over many
+    buffer sets, where drawing gigabytes on the host would take longer than the measurement; the parity tests
+    use make_inputs, whose values the oracle reads too."""
+    import torch
+    B, T, D, dt0, _ = SHAPES[config]
+    dtype = dtype or dt0
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed_for(config, 0) * 4096 + set_index)
+
+    def normal(shape, std=1.0):
+        return torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * std
+
+    x = normal((B, T, D))
+    if config == 3:
+        x *= torch.exp(normal((B, T, 1), 0.5))
+    if config == 5:
+        n_out = max(1, int(round(0.01 * D)))
+        chans = torch.randperm(D, generator=gen, device="cuda")[:n_out]
+        x[:, :, chans] *= 20.0
+    x = x.to(tdt)
+    if config == 5:                       # Student-t(3) = normal / sqrt(chi2_3 / 3), example by example
+        dy = torch.empty((B, T, D), dtype=tdt, device="cuda")
+        for b in range(B):
+            chi2 = sum(normal((T, D)) ** 2 for _ in range(3))
+            dy[b] = (normal((T, D)) / torch.sqrt(chi2 / 3.0) * 1e-3).to(tdt)
+    else:
+        dy = normal((B, T, D), 1e-2 if config == 1 else 1e-3).to(tdt)
+    if config == 4 and B // 2 > 1:
+        x[1:B // 2] = x[0]
+        dy[1:B // 2] = dy[0]
+    gamma = (1.0 + normal((D,), 0.1 if config == 1 else 0.05)).to(tdt)
+    return x, dy, gamma
