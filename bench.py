@@ -118,6 +118,17 @@ def build_layers(cfg, n_layers, stats_mode, log):
     return layers, shared, host_inputs
 
 
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def workloads_shape_bytes(cfg, dtype=""):
     from paper_2411_00999_amd import workloads
     B, T, D, dt0, _ = workloads.SHAPES[cfg]
@@ -256,7 +267,35 @@ ROTATE_BYTES = 512 << 20     # bytes touched between two uses of a buffer set in
 MEASURED_ROW_TRAFFIC = {}
 
 
-def config_leg(cfg, iters, log, sets=None, dtype=None, stats_mode="recompute"):
+class ConfigBuffers:
+    """Device buffers of one workload for the per-workload legs: n_sets input sets (so that a cold measurement can
+    rotate over more bytes than the memory-side cache holds), one set of outputs, one workspace."""
+
+    def __init__(self, cfg, sets=None, dtype=None, stats_mode="recompute"):
+        import torch
+        from paper_2411_00999_amd import binding, workloads
+        B, T, D, dt0, _ = workloads.SHAPES[cfg]
+        self.cfg, self.B, self.T, self.D = cfg, B, T, D
+        self.dtype = dtype or dt0
+        self.stats_mode = stats_mode
+        esz = 2 if self.dtype == "bf16" else 4
+        self.alg = 3 * B * T * D * esz
+        self.n_sets = sets or max(2, -(-ROTATE_BYTES // self.alg) + 1)
+        dt_code = binding.BF16 if self.dtype == "bf16" else binding.F32
+        f32 = dict(dtype=torch.float32, device="cuda")
+        self.S = []
+        for k in range(self.n_sets):
+            x, dy, gamma = workloads.make_inputs_device(cfg, k, self.dtype)
+            L = dict(x=x, dy=dy, gamma=gamma, dx=torch.empty_like(x), mean=None, rstd=None)
+            if stats_mode == "saved":
+                L["mean"], L["rstd"] = binding.ln_fwd_stats(x, workloads.EPS)
+            self.S.append(L)
+        self.out = dict(dgamma=torch.empty(D, **f32), dbeta=torch.empty(D, **f32), pe_g=torch.empty(B, **f32),
+                        pe_b=torch.empty(B, **f32), big=torch.empty(2, **f32))
+        self.ws = binding.alloc_workspace(B, T, D, dt_code)
+
+
+def config_leg(cfg, iters, log, sets=None, dtype=None, stats_mode="recompute", buffers=None):
     """One workload of the benchmark's configs, one layer: ln_bwd_pegn and the plain ln_bwd interleaved on one
     stream, every call with HIP events on its row kernel's own dispatch and a second pair around the whole call
     (row kernel + reduction launches).  Cache-cold: the calls rotate over enough buffer sets that at least
@@ -264,24 +303,9 @@ def config_leg(cfg, iters, log, sets=None, dtype=None, stats_mode="recompute"):
     hot figures repeat the measurement on one set."""
     import torch
     from paper_2411_00999_amd import binding, workloads
-    B, T, D, dt0, _ = workloads.SHAPES[cfg]
-    dtype = dtype or dt0
-    esz = 2 if dtype == "bf16" else 4
-    N = B * T
-    alg = 3 * N * D * esz
-    n_sets = sets or max(2, -(-ROTATE_BYTES // alg) + 1)
-    dt_code = binding.BF16 if dtype == "bf16" else binding.F32
-    f32 = dict(dtype=torch.float32, device="cuda")
-    S = []
-    for k in range(n_sets):
-        x, dy, gamma = workloads.make_inputs_device(cfg, k, dtype)
-        L = dict(x=x, dy=dy, gamma=gamma, dx=torch.empty_like(x), mean=None, rstd=None)
-        if stats_mode == "saved":
-            L["mean"], L["rstd"] = binding.ln_fwd_stats(x, workloads.EPS)
-        S.append(L)
-    out = dict(dgamma=torch.empty(D, **f32), dbeta=torch.empty(D, **f32), pe_g=torch.empty(B, **f32),
-               pe_b=torch.empty(B, **f32), big=torch.empty(2, **f32))
-    ws = binding.alloc_workspace(B, T, D, dt_code)
+    buf = buffers or ConfigBuffers(cfg, sets, dtype, stats_mode)
+    B, T, D, dtype, alg, n_sets, S, out, ws = buf.B, buf.T, buf.D, buf.dtype, buf.alg, buf.n_sets, buf.S, buf.out, buf.ws
+    stats_mode = buf.stats_mode
     hip = HipEvents()
     eps = workloads.EPS
 
@@ -338,6 +362,7 @@ def config_leg(cfg, iters, log, sets=None, dtype=None, stats_mode="recompute"):
         f"{cold['plain']['call_us']['median']:.1f} us; hot {hot['fused']['row_kernel_us']['median']:.1f} / "
         f"{hot['plain']['row_kernel_us']['median']:.1f} us")
     small = alg < (64 << 20)
+    cfg = buf.cfg
     return {
         "workload": f"configs[{cfg - 1}]: B={B} T={T} D={D} {dtype}, one layer, ln_bwd_pegn vs ln_bwd interleaved, "
                     f"row stats {stats_mode}, immediate reduction",
@@ -473,8 +498,10 @@ def main():
     # ramps up while the other's drains.  Deferred mode only (the immediate calls share one workspace).
     lanes = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else []
 
+    use_lanes = [True]
+
     def over_layers(call, deferred):
-        if not (lanes and deferred):
+        if not (lanes and deferred and use_lanes[0]):
             for L in layers:
                 call(L, None)
             return
@@ -511,23 +538,51 @@ def main():
     fused_step, plain_step = make_steps(args.reduce == "deferred")
     other_fused, other_plain = make_steps(args.reduce != "deferred")
 
-    def timed(step, warmup, steps):
+    step_quantiles = {}
+
+    def timed(step, warmup, steps, tag=None):
+        """W untimed steps, then exactly K steps between two synchronisations: the wall time per step.  An event
+        after every step (on the launch stream, inside the timed region) also gives the steps' own durations."""
         for _ in range(warmup):
             step()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
+        marks[0].record()
+        for i in range(steps):
             step()
+            marks[i + 1].record()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
+        dt = (time.perf_counter() - t0) / steps
+        if tag:
+            step_quantiles[tag] = quantiles([marks[i].elapsed_time(marks[i + 1]) for i in range(steps)])
+        return dt
 
-    t_fused = timed(fused_step, args.warmup, args.steps)
+    if args.only_plain:       # profiling aid: plain dispatches only, no headline
+        t_p = timed(plain_step, args.warmup, args.steps, "plain")
+        print(json.dumps({"only_plain": True, "plain_ms_per_step": round(t_p * 1e3, 4),
+                          "plain_GBps": round(bytes_per_step / t_p / 1e9, 2), "steps": args.steps,
+                          "step_ms": step_quantiles.get("plain")}), flush=True)
+        return
+    t_fused = timed(fused_step, args.warmup, args.steps, "fused")
     log(f"fused : {t_fused * 1e3:.3f} ms/step  {bytes_per_step / t_fused / 1e9:.1f} GB/s")
     other = "immediate" if args.reduce == "deferred" else "deferred"
     t_plain = t_fused_o = t_plain_o = float("nan")
+    one_stream = None
     if not args.only_fused:
-        t_plain = timed(plain_step, args.warmup, args.steps)
+        t_plain = timed(plain_step, args.warmup, args.steps, "plain")
         log(f"plain : {t_plain * 1e3:.3f} ms/step  {bytes_per_step / t_plain / 1e9:.1f} GB/s")
+        one_stream = None
+        if lanes and args.reduce == "deferred":      # the same step with every layer on the launch stream
+            use_lanes[0] = False
+            t1f = timed(fused_step, 1, max(2, args.steps // 2))
+            t1p = timed(plain_step, 1, max(2, args.steps // 2))
+            use_lanes[0] = True
+            one_stream = {"fused_ms_per_step": round(t1f * 1e3, 4), "plain_ms_per_step": round(t1p * 1e3, 4),
+                          "fused_GBps": round(bytes_per_step / t1f / 1e9, 2),
+                          "pct_hbm_peak": round(100.0 * bytes_per_step / t1f / 1e9 / HBM_PEAK_GBS, 2)}
+            log(f"one stream: fused {t1f * 1e3:.3f} ms/step ({bytes_per_step / t1f / 1e9:.1f} GB/s), "
+                f"plain {t1p * 1e3:.3f} ms/step")
         t_fused_o = timed(other_fused, 1, max(2, args.steps // 2))
         t_plain_o = timed(other_plain, 1, max(2, args.steps // 2))
         log(f"({other} reduction: fused {t_fused_o * 1e3:.3f} ms/step, plain {t_plain_o * 1e3:.3f} ms/step)")
@@ -688,7 +743,18 @@ def main():
                       f"counted as for the GPU ({esz} B/element)",
             "seconds": round(t_cpu, 3),
         }
-        log(f"oracle: {t_cpu:.2f} s for {passes} layer passes on {threads} threads")
+        # the same oracle on ONE thread: one pass over layer 0
+        x64, dy64 = host_inputs[0].x.astype(np.float64), host_inputs[0].dy.astype(np.float64)
+        t0 = time.perf_counter()
+        oracle.ln_bwd_pegn(x64, dy64, g64, eps, want_dx=True, want_pe=False, nthreads=1)
+        t_one = time.perf_counter() - t0
+        del x64, dy64
+        cpu_baseline["one_thread"] = {"value": round(bytes_per_layer / t_one / 1e9, 4), "unit": "GB/s",
+                                      "seconds": round(t_one, 3), "sample": "layer 0, one pass"}
+        cpu_baseline["cpu_model"] = cpu_model()
+        cpu_baseline["host_cpus"] = os.cpu_count()
+        log(f"oracle: {t_cpu:.2f} s for {passes} layer passes on {threads} threads; one thread: {t_one:.2f} s per layer "
+            f"({cpu_baseline['cpu_model']})")
         # spot parity of layer 0 against the oracle output just computed
         L0 = layers[0]
         dg = L0["dgamma"].cpu().numpy().astype(np.float64)
@@ -698,7 +764,50 @@ def main():
         parity = {"layer0_dgamma_l2_rel": err_dg, "layer0_s_gamma_max_rel": err_sg,
                   "ok": bool(err_dg < 1e-5 and err_sg < 1e-5)}
 
+    # ---- a well-conditioned noise-scale estimate on the headline shape: the workload's own dy has zero mean
+    #      (true gradient 0: G2 is a difference of equal numbers and B_simple is noise), so the first layers are
+    #      drawn again with a [T,D] pattern shared by every example added to dy, run through the same calls, and
+    #      layer 0 is checked against the oracle
+    gns_signal = None
+    if not (args.only_fused or args.no_cpu_baseline):
+        import oracle
+        n_sig = min(2, n_layers)
+        sig = 2.5e-4
+        pe = torch.zeros((2 * n_sig, B), dtype=torch.float32, device="cuda")
+        bigs = torch.zeros(2 * n_sig, dtype=torch.float32, device="cuda")
+        ref_pe, ref_big = [], []
+        for l in range(n_sig):
+            inp = workloads.make_inputs(cfg, l, signal=sig)
+            binding.ln_bwd_pegn(workloads.to_device(inp.x, dtype), workloads.to_device(inp.dy, dtype),
+                                workloads.to_device(inp.gamma, dtype), eps, dx=layers[l]["dx"], dgamma=layers[l]["dgamma"],
+                                dbeta=layers[l]["dbeta"], pe_gamma_sq=pe[2 * l], pe_beta_sq=pe[2 * l + 1],
+                                big_sq=bigs[2 * l:2 * l + 2], workspace=sh["ws"])
+            if l == 0:
+                r = oracle.ln_bwd_pegn(inp.x, inp.dy, inp.gamma, eps, want_dx=False, want_pe=False)
+                ref_pe += [r["s_gamma"], r["s_beta"]]
+                ref_big += list(r["big_sq"])
+        est = binding.gns_estimate(pe, bigs, float(B)).cpu().numpy().astype(float)
+        est0 = binding.gns_estimate(pe[:2], bigs[:2], float(B)).cpu().numpy().astype(float)
+        want0 = oracle.gns_estimate(np.stack(ref_pe), np.array(ref_big), float(B))
+        gns_signal = {"what": f"layers 0..{n_sig - 1} drawn again with dy += m, m ~ N(0, {sig}) a [T,D] pattern shared by "
+                              f"all examples; ln_bwd_pegn + gns_estimate",
+                      "G2": est[2], "S": est[3], "B_simple": est[4],
+                      "layer0": {"B_simple": est0[4], "oracle_B_simple": want0["B_simple"],
+                                 "rel_err": abs(est0[4] / want0["B_simple"] - 1.0)}}
+        log(f"signal variant: B_simple {est[4]:.3f} (layer 0: {est0[4]:.4f}, oracle {want0['B_simple']:.4f})")
+        fused_step()
+        torch.cuda.synchronize()
+
     linear = embedding = None
+    workload_legs = None
+    if not args.only_fused and args.configs:
+        layers.clear()
+        sh.clear()
+        torch.cuda.empty_cache()
+        workload_legs = per_config_legs()
+        if cfg == 3 and not args.config_dtype:       # the headline shape with fp32 storage, one layer
+            workload_legs["workload3_f32"] = config_leg(3, 100, log, dtype="f32", stats_mode=args.stats)
+            torch.cuda.empty_cache()
     if not (args.no_linear or args.only_fused):
         layers.clear()
         sh.clear()
@@ -731,9 +840,13 @@ def main():
         f"{other}_reduction": {"fused_ms_per_step": round(t_fused_o * 1e3, 4),
                                "plain_ms_per_step": round(t_plain_o * 1e3, 4),
                                "fused_GBps": round(bytes_per_step / t_fused_o / 1e9, 2)},
+        "step_ms": step_quantiles,
+        "one_stream": one_stream,
         "graph_replay": graph_replay,
         "fwd_bwd_accumulate": fwd_bwd,
-        "gns": {"g_small_sq": gns[0], "g_big_sq": gns[1], "G2": gns[2], "S": gns[3], "B_simple": gns[4]},
+        "gns": {"g_small_sq": gns[0], "g_big_sq": gns[1], "G2": gns[2], "S": gns[3], "B_simple": gns[4],
+                "note": "zero-mean dy: the true gradient is 0, so G2 and B_simple are noise here; see gns_signal"},
+        "gns_signal": gns_signal,
         "roofline": {
             "kernel": "ln_bwd_rows_kernel (fused call)",
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -750,6 +863,7 @@ def main():
         },
         "cpu_baseline": cpu_baseline,
         "parity_spot_check": parity,
+        "workloads": workload_legs,
         "linear_pegn": linear,
         "embedding_pegn": embedding,
     }

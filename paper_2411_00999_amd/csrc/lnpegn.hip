@@ -32,9 +32,6 @@ int g_waves = 0;
 int g_vpt_max = 0;          // cap on 16-byte vectors per lane and array (0: automatic)
 int g_xcd = -1;        // hand neighbouring chunks to the same XCD: 0 never, 1 always, -1 automatic
 int g_dx_cached = -1;  // dx stores write-back instead of streaming: 0 never, 1 always, -1 automatic
-int g_exp = 0;
-int g_lds_pad = 0;
-long long *g_trace = nullptr;
 int g_stagger = -1;   // rows between the sweep starts of consecutive examples (-1 = automatic)
 // one-shot profiling events around the row kernel (null = disarmed)
 hipEvent_t g_ev_start = nullptr;
@@ -114,22 +111,26 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
     }
     const int nwaves = p.fast ? p.R * p.S : 4;
     {
-        const size_t xchg = (size_t)((8 * nwaves + 2 * p.S + 3) & ~3) * sizeof(float);
+        const size_t xchg = (size_t)((10 * nwaves + 2 * p.S + 3) & ~3) * sizeof(float);
         const size_t merge = p.fast && p.R > 1 ? (size_t)nwaves * 2 * p.vpt * E * kWave * sizeof(float) : 0;
-        p.lds_bytes = xchg + (merge > 512 ? merge : 512) + (size_t)g_lds_pad * 1024;
+        p.lds_bytes = xchg + (merge > 512 ? merge : 512);
     }
     // one full round of resident workgroups unless told otherwise
     int target = pegn ? g_chunks_pegn : g_chunks_plain;
     if (target <= 0) {
         int per_cu = (waves_per_simd * 4) / nwaves > 0 ? (waves_per_simd * 4) / nwaves : 1;
-        // Per-example sweeps with wide lanes: one workgroup per CU.  Half as many chunks per example keep each
-        // example's moving window of memory half as wide, which is worth more than the second workgroup's
-        // latency hiding (measured on B=16 T=2048: D=2048 bf16 72.0 -> 69.3 us, D=4096 bf16 152 -> 148 us,
-        // D=1024 fp32 75.9 -> 71.5 us; within 2 % either way on the other shapes tried; the plain backward,
-        // one sweep over the whole tensor, prefers two).
-        // ... as long as a chunk keeps a hundred rows or so: short launches (B=8 T=1024 D=768: 13 us) want the
-        // parallelism more.
-        if (pegn && p.fast && waves_per_simd == 2 && per_cu > 1 && N / ((int64_t)kCUs * (per_cu / 2)) >= 96) per_cu /= 2;
+        // Per-example sweeps, measured on B*T = 32768 rows (bf16, us per launch, fewer / more chunks):
+        //   rows of one wave   (D=768: 34.8 / 29.3, D=1024: 39.6 / 38.8)    two workgroups of four waves per CU
+        //   rows of two waves  (D=2048: six waves per workgroup)             one workgroup per CU
+        //   rows of four waves (D=4096: 138.9 / 147.8)                       one workgroup per CU: half as many
+        //       chunks per example keep each example's moving window of memory half as wide
+        //   rows of eight waves (D=8192: 279.6 / 268.0)                      two rounds of workgroups: the second
+        //       round starts where the first finishes, which evens out the CUs' unequal memory throughput
+        // ... as long as a chunk keeps a hundred rows or so (short launches want the parallelism more).
+        if (pegn && p.fast && p.S >= 2 && p.S <= 4 && waves_per_simd == 2 && per_cu > 1 &&
+            N / ((int64_t)kCUs * (per_cu / 2)) >= 96)
+            per_cu /= 2;
+        if (pegn && p.fast && p.S == 8 && N / ((int64_t)kCUs * 2) >= 32) per_cu = 2;
         target = kCUs * per_cu;
     }
     const int rows_min = p.fast ? 2 * p.R : 1;       // keep every row group busy
@@ -143,7 +144,7 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
     };
     if (pegn) {
         p.Tp = T;
-        int64_t c = B > kMaxPeGroups ? 1 : target / B;
+        int64_t c = (B > kMaxPeGroups && g_chunks_pegn <= 0) ? 1 : target / B;
         const int64_t cmax = T / rows_min > 1 ? T / rows_min : 1;
         if (c > cmax) c = cmax;
         if (c < 1) c = 1;
@@ -236,7 +237,7 @@ int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, con
     const bool xcd = g_xcd >= 0 ? g_xcd != 0 : p.S >= 4;
     a.xcd_chunks = (xcd && p.fast && p.n_slots % 8 == 0) ? (int)(p.n_slots / 8) : 0;
     a.S = p.S; a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.emit_pe = p.emit_pe; a.rms = rms;
-    a.eps = eps; a.inv_D = 1.0f / (float)D; a.exp = g_exp; a.trace = g_trace;
+    a.eps = eps; a.inv_D = 1.0f / (float)D;
     if (defer) {
         a.defer = reinterpret_cast<DeferHeader *>(ws);
         a.hdr = DeferHeader{dgamma, dbeta, pe_gamma_sq, pe_beta_sq, pegn ? big_sq : nullptr,
@@ -632,19 +633,13 @@ int lnpegn_set_tuning(int key, int value)
             if (value < 1 || value > 65535) return LNPEGN_EINVAL;
             g_emb_run_blocks = value;
             return LNPEGN_OK;
-        case 7: g_exp = value; return LNPEGN_OK;
-        case 8: g_lds_pad = value; return LNPEGN_OK;
-        case 9:
+        case 7:
             if (value > 2) return LNPEGN_EINVAL;
             g_dx_cached = value - 1;
             return LNPEGN_OK;
         default: return LNPEGN_EINVAL;
     }
 }
-
-#ifdef LNPEGN_TRACE
-int lnpegn_set_trace(void *p) { g_trace = static_cast<long long *>(p); return 0; }
-#endif
 
 int lnpegn_stream_probe(const void *a, const void *b, void *out, size_t bytes, int mode, void *stream)
 {

@@ -45,8 +45,6 @@ struct RowArgs {
                          //      (i % 8) * xcd_chunks + i / 8, so neighbouring chunks share an L2
     float eps;
     float inv_D;
-    int exp;             // EXPERIMENT bits
-    long long *trace;    // EXPERIMENT
 };
 
 // gamma for one 16-byte row vector, as fp32 (gamma may be stored in either type)
@@ -121,10 +119,10 @@ __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
     using Raw = typename V::Raw;
     constexpr int E = V::kElems;
     constexpr bool kSync = kS != 1;
-    // x and dy are read once: the streaming hint pays for narrow rows and costs on wide ones (measured)
-    constexpr bool kStreamLoads = kS == 1 || kS == 2 || rows_kernel_narrow4(kS, kVpt * E);
+    // x and dy are read once: streaming loads (measured faster than cached loads at every row width once
+    // the loop no longer waits for its stores; D=8192: 291 -> 276 us, D=4096: 145 -> 139 us)
 #ifndef LNPEGN_LD_AUX
-#define LNPEGN_LD_AUX (kStreamLoads ? 2 : 0)
+#define LNPEGN_LD_AUX 2
 #endif
 #ifndef LNPEGN_ST_AUX
 #define LNPEGN_ST_AUX 2
@@ -133,19 +131,10 @@ __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
 #define LNPEGN_ST_AUX_SMALL 0
 #endif
     constexpr int kLoadAux = LNPEGN_LD_AUX;
+    constexpr bool kDrainStores = kS == 2;
     constexpr int NF = 2 * kVpt * E;  // accumulator floats per lane
     constexpr int KL = kVpt - 1;      // only a lane's last vector slot can be padding
     extern __shared__ __align__(16) float lds[];
-#ifdef LNPEGN_TRACE
-    int tr_n = 0;
-    const bool tr_on = a.trace && (threadIdx.x == 0) && (blockIdx.x % 37 == 0) && blockIdx.x / 37 < 8;
-    long long *tr = a.trace + (blockIdx.x / 37) * 256;
-#define TR() do { if (tr_on && tr_n < 255) tr[1 + tr_n++] = clock64(); } while (0)
-#else
-#define TR() do {} while (0)
-#endif
-    TR();
-
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = blockDim.x >> 6;
@@ -224,10 +213,12 @@ __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
         for (int e = 0; e < E; ++e) acc_g[k][e] = acc_b[k][e] = 0.f;
 
     // LDS: [parity][R][S] exchange float4 {sum dyh, sum dyh*xc, sum x, M2}, then S floats n_w and
-    // S floats 1/n_w (rows with padding only), then the merge buffer.
+    // S floats 1/n_w (rows with padding only), two floats per wave for the per-example norms, then the
+    // merge buffer (16-byte aligned).
     float4 *xchg_base = reinterpret_cast<float4 *>(lds);
     float *nw_tab = lds + 8 * nwaves;
-    float *merge = lds + ((8 * nwaves + 2 * S + 3) & ~3);
+    float *pe_slots = nw_tab + 2 * S;     // 2 floats per wave: the waves' parts of an example's squared norms
+    float *merge = lds + ((10 * nwaves + 2 * S + 3) & ~3);
     if constexpr (kSync && !kFull) {
         if (lane == 0 && g == 0) {
             nw_tab[ws] = (float)n_w;
@@ -250,13 +241,16 @@ __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
         float4 *xchg = xchg_base + (parity * R + g) * S;
         if (act) {
             r = row_of(mm);
+            // Rows shared by two waves run faster when a row group lets its previous dx stores land before
+            // it asks for the next row (measured, B=16 T=2048 D=2048: 69.6 -> 67.0 us per-example,
+            // 66.0 -> 65.4 plain); every other row width is faster with the stores left in flight.
+            if constexpr (kDrainStores) __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0) only
 #pragma unroll
             for (int k = 0; k < kVpt; ++k) {
                 V::unpack(xr[k], xf[k]);   // padded lanes hold zeros: the buffer load returned them
                 V::unpack(dr[k], df[k]);
             }
             const float saved_mean = st_mean, saved_rstd = st_rstd;   // this row's, before the prefetch
-            TR();
             if (mm + R < n_rows) load_row(mm + R, xr, dr);
             // pass 1: pivot = the wave's own mean (or the saved row mean)
             if constexpr (kSaved) {
@@ -294,7 +288,6 @@ __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
                 if (lane == 0) xchg[ws] = make_float4(s_dyh, s_dyx, s_x, m2);
             }
         }
-        TR();
         if constexpr (kSync) __syncthreads();
         if (act) {
             float rstd, shift_r = 0.f;   // shift_r = (pivot - mean) * rstd
@@ -366,7 +359,6 @@ __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
                     ro, vidx[k] * (int)sizeof(Raw), packed[k]);
         }
         parity ^= 1;
-        TR();
     };
 
     using Full = std::integral_constant<bool, false>;
@@ -386,8 +378,6 @@ __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
     }
     if (has_tail) process(Tail{}, m);
 
-    TR();
-    if (a.exp & 2) return;
     // ---- hand the chunk's column sums to the workspace ----
     float *out_g = a.part + (int64_t)chunk * 2 * a.D;
     float *out_b = out_g + a.D;
@@ -413,55 +403,64 @@ __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
             }
         }
     } else {
-        // merge the row groups' sums through LDS, adding in group order (reproducible)
-        float *mine = merge + (int64_t)wave * NF * kWave;
+        // merge the row groups' sums through LDS, adding in group order (reproducible); a lane's 2*kVpt*E
+        // sums travel as NQ quads of four consecutive columns, one 16-byte LDS access each
+        constexpr int NQ = NF / 4;
+        float4 *merge4 = reinterpret_cast<float4 *>(merge);
+        float4 *mine = merge4 + (int64_t)wave * NQ * kWave + lane;
 #pragma unroll
         for (int k = 0; k < kVpt; ++k)
 #pragma unroll
-            for (int e = 0; e < E; ++e) {
-                mine[((0 * kVpt + k) * E + e) * kWave + lane] = acc_g[k][e];
-                mine[((1 * kVpt + k) * E + e) * kWave + lane] = acc_b[k][e];
+            for (int h = 0; h < E / 4; ++h) {
+                mine[((0 * kVpt + k) * (E / 4) + h) * kWave] =
+                    make_float4(acc_g[k][4 * h], acc_g[k][4 * h + 1], acc_g[k][4 * h + 2], acc_g[k][4 * h + 3]);
+                mine[((1 * kVpt + k) * (E / 4) + h) * kWave] =
+                    make_float4(acc_b[k][4 * h], acc_b[k][4 * h + 1], acc_b[k][4 * h + 2], acc_b[k][4 * h + 3]);
             }
         __syncthreads();
-        constexpr int NQ = NF / 4;  // groups of four consecutive columns per lane
         for (int q = g; q < NQ; q += R) {
             const int f0 = q * 4;
             const int arr = f0 / (kVpt * E);
             const int k = (f0 / E) % kVpt;
             const int e0 = f0 % E;
-            float s[4] = {0.f, 0.f, 0.f, 0.f};
+            float4 s4 = make_float4(0.f, 0.f, 0.f, 0.f);
             for (int gg = 0; gg < R; ++gg) {
-                const float *src = merge + ((int64_t)(gg * S + ws) * NF + f0) * kWave + lane;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) s[i] += src[i * kWave];
+                const float4 t = merge4[((int64_t)(gg * S + ws) * NQ + q) * kWave + lane];
+                s4.x += t.x; s4.y += t.y; s4.z += t.z; s4.w += t.w;
             }
             const int v = (k * S + ws) * kWave + lane;
             if (v < a.nvec) {
                 float *dst = (arr == 0 ? out_g : out_b) + (int64_t)v * E + e0;
-                *reinterpret_cast<float4 *>(dst) = make_float4(s[0], s[1], s[2], s[3]);
-                const double q2 = (double)s[0] * s[0] + (double)s[1] * s[1] + (double)s[2] * s[2] +
-                                  (double)s[3] * s[3];
+                *reinterpret_cast<float4 *>(dst) = s4;
+                const double q2 = (double)s4.x * s4.x + (double)s4.y * s4.y + (double)s4.z * s4.z +
+                                  (double)s4.w * s4.w;
                 if (arr == 0) sq_g += q2;
                 else sq_b += q2;
             }
         }
     }
-    TR();
-    if (!kPlain && a.emit_pe && !(a.exp & 1)) {
-        // Appendix B steps 2 and 6 for the example this workgroup owns entirely
-        __syncthreads();   // the merge buffer is reused as the reduction scratch
-        double *slots = reinterpret_cast<double *>(merge);
-        const double tg = block_sum_f64(sq_g, slots);
-        const double tb = block_sum_f64(sq_b, slots + 16);
+    if (!kPlain && a.emit_pe) {
+        // Appendix B steps 2 and 6 for the example this workgroup owns entirely.  A lane's squares are
+        // summed in fp64; the 64 lanes' sums then cross the wave as fp32 on the DPP network (positive
+        // terms, a tree of depth 6: relative error below 1e-6) and the waves' sums are added in wave
+        // order in fp64: one barrier in all.
+        float wg = (float)sq_g, wb = (float)sq_b;
+        wave_sum2(wg, wb);
+        if (lane == 0) {
+            pe_slots[2 * wave] = wg;
+            pe_slots[2 * wave + 1] = wb;
+        }
+        __syncthreads();
         if (threadIdx.x == 0) {
+            double tg = 0.0, tb = 0.0;
+            for (int w = 0; w < nwaves; ++w) {
+                tg += (double)pe_slots[2 * w];
+                tb += (double)pe_slots[2 * w + 1];
+            }
             a.pe_gamma_sq[b] = (float)tg;
             if (a.pe_beta_sq) a.pe_beta_sq[b] = (float)tb;
         }
     }
-    TR();
-#ifdef LNPEGN_TRACE
-    if (tr_on) tr[0] = tr_n;
-#endif
 }
 
 template <typename T, int kVpt, bool kSaved, int kS, bool kFull, bool kDxCached>
