@@ -27,7 +27,7 @@
  *     no floating-point atomics are used anywhere.
  *   - Index arithmetic is 64-bit; B*T*D may exceed 2^31.
  *   - Any D >= 1 is computed correctly.  The bandwidth-tuned kernels need
- *     D % 8 == 0 (bf16) or D % 4 == 0 (fp32), D <= 8192
+ *     D % 8 == 0 (bf16) or D % 4 == 0 (fp32), D <= 16384
  *     and 16-byte aligned x, dy, dx; other cases take a slower generic kernel.
  *   - Loading.  The library links against the HIP runtime (libamdhip64) by its soname.  A
  *     process must hold ONE copy of that runtime: a host program that also loads another

@@ -79,8 +79,10 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
     p.plain = !pegn;
     const int E = dt == LNPEGN_BF16 ? 8 : 4;
     const int64_t N = (int64_t)B * T;
-    int vpt_max = 16 / E;                            // at most 16 elements per lane
+    int vpt_max = 16 / E;                            // 16 elements per lane ...
     if (g_vpt_max > 0 && g_vpt_max < vpt_max) vpt_max = g_vpt_max;
+    // ... up to 32 for rows beyond eight waves of 16 (D > 8192): eight waves of 24 or 32 elements per lane
+    if (D % E == 0 && D / E > 64 * vpt_max * 8) vpt_max = 32 / E;
     p.fast = vector_ok && (D % E == 0) && (D / E <= 64 * vpt_max * 8);
     p.nvec = p.fast ? D / E : 0;
     p.sync = false;
@@ -90,7 +92,7 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
     p.max_threads = 256;
     int waves_per_simd = 4;                          // resident waves per SIMD to aim for
     if (p.fast) {
-        p.S = ceil_div(p.nvec, 64 * vpt_max);
+        p.S = vpt_max > 16 / E ? 8 : ceil_div(p.nvec, 64 * vpt_max);   // beyond 16 elements per lane: always eight waves
         p.vpt = ceil_div(p.nvec, 64 * p.S);
         p.sync = p.S > 1;
         const int elems = p.vpt * E;                 // per lane
@@ -103,7 +105,11 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         // already takes four or eight waves).
         // (rows that one wave covers stay at four row groups: six made the short kernels of B=8 T=1024 D=768 and
         // B=512 T=64 D=1024 3-10 % slower)
-        int R = g_waves > 0 ? g_waves / p.S : (elems > 8 && p.S == 2) ? 3 : (p.S >= 4 ? 1 : 4 / p.S);
+        // (fp32 rows of four waves: two row groups, measured with the per-example sweeps, 288.7 -> 273.8 us)
+        int R = g_waves > 0 ? g_waves / p.S
+                : (elems > 8 && p.S == 2) ? 3
+                : (pegn && E == 4 && p.S == 4 && p.vpt >= 3) ? 2
+                : (p.S >= 4 ? 1 : 4 / p.S);
         if (R < 1) R = 1;
         while (R > 1 && R * p.S > max_waves) --R;
         p.R = R;
@@ -127,10 +133,13 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         //   rows of eight waves (D=8192: 279.6 / 268.0)                      two rounds of workgroups: the second
         //       round starts where the first finishes, which evens out the CUs' unequal memory throughput
         // ... as long as a chunk keeps a hundred rows or so (short launches want the parallelism more).
-        if (pegn && p.fast && p.S >= 2 && p.S <= 4 && waves_per_simd == 2 && per_cu > 1 &&
+        if (pegn && p.fast && p.S >= 2 && p.S <= 4 && waves_per_simd == 2 && per_cu > 1 && !(E == 4 && p.vpt >= 3) &&
             N / ((int64_t)kCUs * (per_cu / 2)) >= 96)
             per_cu /= 2;
-        if (pegn && p.fast && p.S == 8 && N / ((int64_t)kCUs * 2) >= 32) per_cu = 2;
+        //   fp32 rows of two and four waves (lanes of four vectors; D=2048: 140.5 / 137.9, D=4096 with two row
+        //       groups: 290.8 / 273.8) also take two rounds
+        const bool wide_f32 = E == 4 && p.vpt >= 3 && p.S >= 2;
+        if (pegn && p.fast && (p.S == 8 || wide_f32) && N / ((int64_t)kCUs * 2) >= 32) per_cu = 2;
         target = kCUs * per_cu;
     }
     const int rows_min = p.fast ? 2 * p.R : 1;       // keep every row group busy

@@ -63,7 +63,29 @@ hipError_t launch_inst(const RowShape &p, const RowArgs &a, const RowLaunch &rl)
     if (!p.fast)
         return launch_row_kernel(ln_bwd_rows_generic_kernel<InstT, kInstSaved>, dim3((unsigned)p.n_slots),
                                  dim3(256), 0, rl, a);
-    // at most 16 elements per lane: 2 vectors of 8 bf16, 4 vectors of 4 fp32
+    // up to 16 elements per lane (2 vectors of 8 bf16, 4 vectors of 4 fp32) at any number of waves per row;
+    // 24 or 32 elements per lane only for rows of eight waves (D > 8192)
+    constexpr int kBase = 16 / Vec<InstT>::kElems;
+    if (p.vpt > kBase) {
+        if (p.S != 8) return hipErrorInvalidValue;
+        const bool full = p.nvec == 64 * 8 * p.vpt;
+#define LNPEGN_WIDE(V) \
+    case V: return full ? launch_variant<V, 8, true>(p, a, rl) : launch_variant<V, 8, false>(p, a, rl)
+        switch (p.vpt) {
+            LNPEGN_WIDE(kBase + 1);
+            LNPEGN_WIDE(kBase + 2);
+            default: break;
+        }
+        if constexpr (kBase == 4) {
+            switch (p.vpt) {
+                LNPEGN_WIDE(7);
+                LNPEGN_WIDE(8);
+                default: break;
+            }
+        }
+#undef LNPEGN_WIDE
+        return hipErrorInvalidValue;
+    }
     if constexpr (Vec<InstT>::kElems == 4) {
         if (p.vpt == 3) return launch_vpt<3>(p, a, rl);
         if (p.vpt == 4) return launch_vpt<4>(p, a, rl);

@@ -113,6 +113,20 @@ def test_any_D_is_correct(B, T, D, dtype):
         pu.compare_with_oracle(inp, res, ref)
 
 
+@pytest.mark.parametrize("B,T,D,dtype", [(2, 33, 12288, "bf16"), (2, 17, 16384, "bf16"), (3, 9, 10240, "bf16"),
+                                         (2, 9, 12288, "f32"), (1, 5, 16384, "f32"), (2, 7, 9216, "f32"),
+                                         (2, 6, 14336, "f32")])
+@pytest.mark.parametrize("saved", [False, True])
+def test_rows_wider_than_8192(B, T, D, dtype, saved):
+    """Rows beyond eight waves of 16 elements per lane: 24 or 32 elements per lane, still the vector kernels."""
+    inp = workloads.make_inputs(5 if dtype == "bf16" else 1, B=B, T=T, D=D, dtype=dtype)
+    ref = _oracle(inp)
+    res = pu.run_gpu(inp, saved_stats=saved)
+    pu.compare_with_oracle(inp, res, ref)
+    plain = pu.run_gpu(inp, saved_stats=saved, pegn=False)
+    pu.compare_with_oracle(inp, plain, ref, pegn=False)
+
+
 def test_gamma_fp32_with_bf16_activations():
     inp = workloads.make_inputs(2, B=2, T=40, D=768)
     ref = _oracle(inp)
