@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per row-kernel launch counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the
 # stream probe of known size); see profiles/ln_bwd_rows_workload3_rocprofv3.md.  Re-measure after any
 # change to the row kernel or its launch shape.  Workloads without a measurement report null.
-MEASURED_TRAFFIC_BYTES = {3: 407_050_000}
+MEASURED_TRAFFIC_BYTES = {3: 407_060_000}
 # The same for one whole call of linear_pegn / embedding_pegn on the named shapes (all kernels of the call;
 # profiles/linear_pegn_gpt1p3b_up_rocprofv3.md, profiles/embedding_pegn_gpt1p3b_wte_rocprofv3.md).
 MEASURED_CALL_TRAFFIC_BYTES = {"gpt1p3b_up": 3_134_000_000, "gpt1p3b_wte": 675_000_000}
@@ -262,9 +262,11 @@ def quantiles(values):
 
 
 ROTATE_BYTES = 512 << 20     # bytes touched between two uses of a buffer set in the cache-cold legs
-# HBM bytes per row-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (fused kernel), per workload;
-# the profiles/ summary of each workload has the command and the copy-kernel scale.  null = not measured.
-MEASURED_ROW_TRAFFIC = {}
+# HBM bytes per row-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (fused kernel), per workload and
+# storage type; profiles/ln_bwd_rows_workloads_1_2_4_5_rocprofv3.md has the commands and the copy-kernel scale.
+# Re-measure after any change to the row kernel or its launch shape.  A workload without a measurement reports null.
+MEASURED_ROW_TRAFFIC = {(5, "bf16"): 1_644_470_000, (4, "bf16"): 205_730_000, (2, "bf16"): 41_060_000,
+                        (1, "f32"): 1_820_000, (3, "f32"): 813_950_000}
 
 
 class ConfigBuffers:
@@ -410,8 +412,10 @@ def main():
     ap.add_argument("--linear-shape", default="gpt1p3b_up", help="a key of workloads.LINEAR_SHAPES")
     ap.add_argument("--embedding-only", action="store_true", help="run only the embedding-layer leg")
     ap.add_argument("--embedding-shape", default="gpt1p3b_wte", help="a key of workloads.EMBEDDING_SHAPES")
-    ap.add_argument("--streams", type=int, default=2,
-                    help="streams the independent layers of a step are spread over (deferred reduction only)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="streams the independent layers of the headline step are spread over (deferred reduction "
+                         "only).  1 = every launch on one stream, which is what the kernel durations of the roofline "
+                         "object and of a kernel trace refer to; the two-stream step is reported beside it")
     ap.add_argument("--tuning", default="", help="launch-shape overrides, key=value[,key=value...] "
                                                  "(lnpegn_set_tuning; for experiments, the reported defaults use none)")
     ap.add_argument("--quiet", action="store_true")
@@ -496,9 +500,10 @@ def main():
 
     # The layers are independent, so the caller may spread them over streams: with two, one layer's kernel
     # ramps up while the other's drains.  Deferred mode only (the immediate calls share one workspace).
-    lanes = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else []
+    n_side = max(args.streams, 2)      # the side figure always uses at least two
+    lanes = [torch.cuda.Stream() for _ in range(n_side)]
 
-    use_lanes = [True]
+    use_lanes = [args.streams > 1]
 
     def over_layers(call, deferred):
         if not (lanes and deferred and use_lanes[0]):
@@ -568,20 +573,24 @@ def main():
     log(f"fused : {t_fused * 1e3:.3f} ms/step  {bytes_per_step / t_fused / 1e9:.1f} GB/s")
     other = "immediate" if args.reduce == "deferred" else "deferred"
     t_plain = t_fused_o = t_plain_o = float("nan")
-    one_stream = None
+    other_streams = None
     if not args.only_fused:
         t_plain = timed(plain_step, args.warmup, args.steps, "plain")
         log(f"plain : {t_plain * 1e3:.3f} ms/step  {bytes_per_step / t_plain / 1e9:.1f} GB/s")
-        one_stream = None
-        if lanes and args.reduce == "deferred":      # the same step with every layer on the launch stream
-            use_lanes[0] = False
+        other_streams = None
+        if args.reduce == "deferred":      # the same step with the layers on one stream / spread over several
+            was = use_lanes[0]
+            use_lanes[0] = not was
             t1f = timed(fused_step, 1, max(2, args.steps // 2))
             t1p = timed(plain_step, 1, max(2, args.steps // 2))
-            use_lanes[0] = True
-            one_stream = {"fused_ms_per_step": round(t1f * 1e3, 4), "plain_ms_per_step": round(t1p * 1e3, 4),
-                          "fused_GBps": round(bytes_per_step / t1f / 1e9, 2),
-                          "pct_hbm_peak": round(100.0 * bytes_per_step / t1f / 1e9 / HBM_PEAK_GBS, 2)}
-            log(f"one stream: fused {t1f * 1e3:.3f} ms/step ({bytes_per_step / t1f / 1e9:.1f} GB/s), "
+            use_lanes[0] = was
+            other_streams = {"streams": 1 if was else len(lanes),
+                             "fused_ms_per_step": round(t1f * 1e3, 4), "plain_ms_per_step": round(t1p * 1e3, 4),
+                             "fused_GBps": round(bytes_per_step / t1f / 1e9, 2),
+                             "pct_hbm_peak": round(100.0 * bytes_per_step / t1f / 1e9 / HBM_PEAK_GBS, 2),
+                             "what": "the independent layers of a step spread over streams, so that one layer's kernel "
+                                     "ramps up while another's drains" if not was else "every launch on one stream"}
+            log(f"{other_streams['streams']} stream(s): fused {t1f * 1e3:.3f} ms/step ({bytes_per_step / t1f / 1e9:.1f} GB/s), "
                 f"plain {t1p * 1e3:.3f} ms/step")
         t_fused_o = timed(other_fused, 1, max(2, args.steps // 2))
         t_plain_o = timed(other_plain, 1, max(2, args.steps // 2))
@@ -827,10 +836,10 @@ def main():
         "config": {
             "workload": f"configs[{cfg - 1}]: {n_layers} LayerNorm layers back-to-back, B={B} T={T} D={D} "
                         f"{dtype}, ln_bwd_pegn per layer + one gns_estimate; row stats {args.stats}; "
-                        f"{args.reduce} reduction; layers spread over {max(1, len(lanes)) if args.reduce == 'deferred' else 1} "
+                        f"{args.reduce} reduction; layers spread over {len(lanes) if (args.reduce == 'deferred' and args.streams > 1) else 1} "
                         f"stream(s)",
             "B": B, "T": T, "D": D, "layers": n_layers, "stats": args.stats, "reduce": args.reduce,
-            "streams": max(1, len(lanes)) if args.reduce == "deferred" else 1,
+            "streams": len(lanes) if (args.reduce == "deferred" and args.streams > 1) else 1,
         },
         "pct_hbm_peak": round(100.0 * bytes_per_step / t_fused / 1e9 / HBM_PEAK_GBS, 2),
         "tokens_per_s": round(n_layers * N / t_fused, 1),
@@ -841,7 +850,7 @@ def main():
                                "plain_ms_per_step": round(t_plain_o * 1e3, 4),
                                "fused_GBps": round(bytes_per_step / t_fused_o / 1e9, 2)},
         "step_ms": step_quantiles,
-        "one_stream": one_stream,
+        "other_stream_count": other_streams,
         "graph_replay": graph_replay,
         "fwd_bwd_accumulate": fwd_bwd,
         "gns": {"g_small_sq": gns[0], "g_big_sq": gns[1], "G2": gns[2], "S": gns[3], "B_simple": gns[4],
