@@ -705,7 +705,6 @@ size_t embedding_pegn_workspace_bytes(int B, int T, int D, int V)
 int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, float *s, float *big_sq, int B, int T,
                    int D, int V, lnpegn_dtype dt, void *workspace, size_t workspace_bytes, unsigned flags, void *stream)
 {
-    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!emb_shape_ok(B, T, D, V) || !ids || !g || !w || !s || !workspace) return LNPEGN_EINVAL;
     if (flags & ~(unsigned)LNPEGN_ACCUMULATE) return LNPEGN_EINVAL;
     if (dt != LNPEGN_F32 && dt != LNPEGN_BF16) return LNPEGN_EUNSUPPORTED;
@@ -739,13 +738,11 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
         }
         const int64_t nw = (int64_t)V * D;
         const unsigned fb = (unsigned)(nw / 256 / 8 + 1 < 65536 ? nw / 256 / 8 + 1 : 65536);
-        emb_fill_kernel<<<dim3(fb), dim3(256), 0, fs>>>(w, nw);
-        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        if (launch(emb_fill_kernel, dim3(fb), dim3(256), 0, fs, w, nw) != hipSuccess) return LNPEGN_EHIP;
         if (side && hipEventRecord(side->join, fs) != hipSuccess) return LNPEGN_EHIP;
     }
     const unsigned nblk = (unsigned)((p.n + 255) / 256);
-    emb_prepare_kernel<<<dim3(nblk), dim3(256), 0, st>>>(ids, ids_are_int64, keys_in, vals_in, contrib, p.n, nscratch, V);
-    if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    if (launch(emb_prepare_kernel, dim3(nblk), dim3(256), 0, st, ids, ids_are_int64, keys_in, vals_in, contrib, p.n, nscratch, V) != hipSuccess) return LNPEGN_EHIP;
     size_t temp = p.temp_bytes;
     if (rocprim::radix_sort_pairs(ws + p.off_temp, temp, keys_in, keys_out, vals_in, vals_out, (size_t)p.n, 0,
                                   key_bits(V), st) != hipSuccess)
@@ -760,9 +757,9 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
     const dim3 grid_runs(grid.x < (unsigned)g_emb_run_blocks ? grid.x : (unsigned)g_emb_run_blocks, grid.y);
     float *runsum = reinterpret_cast<float *>(ws + p.off_runsum);
     const bool vec = vec_ok && D % 8 == 0;
+    hipError_t runs_status = hipSuccess;
     auto runs = [&](auto kernel, auto *gp) {
-        kernel<<<grid_runs, dim3(64 * kWavesPerBlock), 0, st>>>(gp, keys_out, vals_out, w, runsum, contrib, bigpart, multi,
-                                                                multi_run, p.n, T, D, V, accumulate);
+        runs_status = launch(kernel, grid_runs, dim3(64 * kWavesPerBlock), 0, st, gp, keys_out, vals_out, w, runsum, contrib, bigpart, multi, multi_run, p.n, T, D, V, accumulate);
     };
     if (dt == LNPEGN_BF16) {
         if (vec) runs(emb_runs_kernel<bf16_t, true>, static_cast<const bf16_t *>(g));
@@ -771,21 +768,14 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
         if (vec) runs(emb_runs_kernel<float, true>, static_cast<const float *>(g));
         else runs(emb_runs_kernel<float, false>, static_cast<const float *>(g));
     }
-    if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
-    emb_sums_kernel<false><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(keys_out, vals_out, w, runsum, contrib, bigpart,
-                                                                      multi_run, p.n, T, D, V, accumulate);
-    if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
-    emb_sums_kernel<true><<<grid, dim3(64 * kWavesPerBlock), 0, st>>>(keys_out, vals_out, w, runsum, contrib, bigpart,
-                                                                     multi, p.n, T, D, V, accumulate);
-    if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    if (runs_status != hipSuccess) return LNPEGN_EHIP;
+    if (launch(emb_sums_kernel<false>, grid, dim3(64 * kWavesPerBlock), 0, st, keys_out, vals_out, w, runsum, contrib, bigpart, multi_run, p.n, T, D, V, accumulate) != hipSuccess) return LNPEGN_EHIP;
+    if (launch(emb_sums_kernel<true>, grid, dim3(64 * kWavesPerBlock), 0, st, keys_out, vals_out, w, runsum, contrib, bigpart, multi, p.n, T, D, V, accumulate) != hipSuccess) return LNPEGN_EHIP;
     const bool wnorm = accumulate && big_sq;
     if (wnorm) {
-        emb_wnorm_kernel<<<dim3(kNormBlocks), dim3(256), 0, st>>>(w, (int64_t)V * D, wpart);
-        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        if (launch(emb_wnorm_kernel, dim3(kNormBlocks), dim3(256), 0, st, w, (int64_t)V * D, wpart) != hipSuccess) return LNPEGN_EHIP;
     }
-    emb_final_kernel<<<dim3(B + 1), dim3(1024), 0, st>>>(contrib, bigpart, wnorm ? wpart : nullptr, kNormBlocks, s,
-                                                         big_sq, B, T, p.ncb, p.n);
-    return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+    return launch(emb_final_kernel, dim3(B + 1), dim3(1024), 0, st, contrib, bigpart, wnorm ? wpart : nullptr, kNormBlocks, s, big_sq, B, T, p.ncb, p.n) == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
 }
 
 }  // extern "C"

@@ -502,7 +502,6 @@ size_t linear_pegn_workspace_bytes(int B, int T, int K, int L, lnpegn_dtype dt)
 int linear_pegn(const void *x, const void *g, float *w, float *s, float *big_sq, int B, int T, int K, int L,
                 lnpegn_dtype dt, void *workspace, size_t workspace_bytes, unsigned flags, void *stream)
 {
-    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!lin_shape_ok(B, T, K, L) || !x || !g || !w || !s || !workspace) return LNPEGN_EINVAL;
     if (flags & ~(unsigned)LNPEGN_ACCUMULATE) return LNPEGN_EINVAL;
     if (dt != LNPEGN_F32 && dt != LNPEGN_BF16) return LNPEGN_EUNSUPPORTED;
@@ -526,31 +525,25 @@ int linear_pegn(const void *x, const void *g, float *w, float *s, float *big_sq,
         a.B = B; a.T = T; a.K = K; a.L = L;
         a.tiles_k = p.tiles_k; a.tiles_l = p.tiles_l; a.nsplit = p.nsplit; a.b_per_split = p.b_per_split;
         a.accumulate = accumulate;
-        if (dt == LNPEGN_BF16)
-            linear_pegn_kernel<2><<<dim3(p.tiles_k * p.tiles_l, p.nsplit), dim3(Cfg::kThreads), 0, st>>>(a);
-        else
-            linear_pegn_kernel<4><<<dim3(p.tiles_k * p.tiles_l, p.nsplit), dim3(Cfg::kThreads), 0, st>>>(a);
-        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        const dim3 grid(p.tiles_k * p.tiles_l, p.nsplit), block(Cfg::kThreads);
+        if ((dt == LNPEGN_BF16 ? launch(linear_pegn_kernel<2>, grid, block, 0, st, a)
+                               : launch(linear_pegn_kernel<4>, grid, block, 0, st, a)) != hipSuccess)
+            return LNPEGN_EHIP;
         if (p.nsplit > 1) {
             const int64_t n = (int64_t)K * L;
-            linear_sum_splits_kernel<<<dim3((unsigned)p.nbig), dim3(256), 0, st>>>(part_w, w, part_big, n, p.nsplit,
-                                                                                  accumulate);
-            if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+            if (launch(linear_sum_splits_kernel, dim3((unsigned)p.nbig), dim3(256), 0, st, part_w, w, part_big, n, p.nsplit, accumulate) != hipSuccess) return LNPEGN_EHIP;
         }
     } else {
         const dim3 grid(p.tiles_l, p.tiles_k);
-        if (dt == LNPEGN_BF16)
-            linear_pegn_generic_kernel<bf16_t><<<grid, dim3(256), 0, st>>>(
-                static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(g), w, part_s, part_big, B, T, K, L,
-                accumulate);
-        else
-            linear_pegn_generic_kernel<float><<<grid, dim3(256), 0, st>>>(
-                static_cast<const float *>(x), static_cast<const float *>(g), w, part_s, part_big, B, T, K, L,
-                accumulate);
-        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        const hipError_t e =
+            dt == LNPEGN_BF16
+                ? launch(linear_pegn_generic_kernel<bf16_t>, grid, dim3(256), 0, st, static_cast<const bf16_t *>(x),
+                         static_cast<const bf16_t *>(g), w, part_s, part_big, B, T, K, L, accumulate)
+                : launch(linear_pegn_generic_kernel<float>, grid, dim3(256), 0, st, static_cast<const float *>(x),
+                         static_cast<const float *>(g), w, part_s, part_big, B, T, K, L, accumulate);
+        if (e != hipSuccess) return LNPEGN_EHIP;
     }
-    linear_final_kernel<<<dim3(B + 1), dim3(1024), 0, st>>>(part_s, p.nparts, part_big, p.nbig, s, big_sq, B);
-    return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+    return launch(linear_final_kernel, dim3(B + 1), dim3(1024), 0, st, part_s, p.nparts, part_big, p.nbig, s, big_sq, B) == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
 }
 
 }  // extern "C"

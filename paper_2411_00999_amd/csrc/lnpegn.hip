@@ -220,7 +220,6 @@ int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, con
             float *pe_beta_sq, float *big_sq, int B, int T, int D, int dt, int gamma_dt, float eps,
             void *workspace, size_t workspace_bytes, void *stream)
 {
-    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
     if (!dtype_ok(dt) || !dtype_ok(gamma_dt)) return LNPEGN_EUNSUPPORTED;
     if (!x || !dy || !gamma || !dx || !dgamma || (!rms && !dbeta)) return LNPEGN_EINVAL;
@@ -282,20 +281,16 @@ int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, con
     ra.n_slots = (int)p.n_slots; ra.gs = p.gs; ra.G1 = p.G1; ra.D = D; ra.ntile = p.ntile;
     ra.pe_from_groups = p.pe_from_groups;
     ra.accumulate = accumulate;
-    reduce_groups_kernel<<<dim3((unsigned)p.G1, (unsigned)p.ntile), dim3(kTile), 0, s>>>(ra);
-    if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+    if (launch(reduce_groups_kernel, dim3((unsigned)p.G1, (unsigned)p.ntile), dim3(kTile), 0, s, ra) != hipSuccess) return LNPEGN_EHIP;
     const bool need_scalars = p.pe_from_groups || ra.big_sq != nullptr;
     if (p.G1 == 1 || (int64_t)p.G1 * D <= kSmallFinal) {
         if (p.G1 > 1 || need_scalars) {
-            reduce_final_small_kernel<<<dim3(1), dim3(1024), 0, s>>>(ra);
-            if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+            if (launch(reduce_final_small_kernel, dim3(1), dim3(1024), 0, s, ra) != hipSuccess) return LNPEGN_EHIP;
         }
     } else {
-        reduce_final_tiles_kernel<<<dim3((unsigned)p.ntile), dim3(kTile), 0, s>>>(ra);
-        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        if (launch(reduce_final_tiles_kernel, dim3((unsigned)p.ntile), dim3(kTile), 0, s, ra) != hipSuccess) return LNPEGN_EHIP;
         if (need_scalars) {
-            reduce_scalars_kernel<<<dim3(1), dim3(256), 0, s>>>(ra);
-            if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+            if (launch(reduce_scalars_kernel, dim3(1), dim3(256), 0, s, ra) != hipSuccess) return LNPEGN_EHIP;
         }
     }
     return LNPEGN_OK;
@@ -353,8 +348,7 @@ hipError_t launch_fwd(FwdArgs a, bool vector_ok, hipStream_t s)
     const bool fast = vector_ok && (D % E == 0) && (D / E <= 64 * (16 / E) * 8);
     if (!fast) {
         const unsigned grid = (unsigned)(N < 4096 ? N : 4096);
-        ln_fwd_generic_kernel<T, kWriteY><<<dim3(grid), dim3(256), 0, s>>>(a);
-        return hipGetLastError();
+        return launch(ln_fwd_generic_kernel<T, kWriteY>, dim3(grid), dim3(256), 0, s, a);
     }
     a.nvec = D / E;
     if (a.nvec <= 64 * (16 / E)) {
@@ -362,10 +356,10 @@ hipError_t launch_fwd(FwdArgs a, bool vector_ok, hipStream_t s)
         const int64_t want = (N + 3) / 4;
         const dim3 grid((unsigned)(want < 4096 ? want : 4096)), block(256);
         switch (vpt) {
-            case 1: ln_fwd_kernel<T, 1, false, kWriteY><<<grid, block, 0, s>>>(a); break;
-            case 2: ln_fwd_kernel<T, 2, false, kWriteY><<<grid, block, 0, s>>>(a); break;
-            case 3: ln_fwd_kernel<T, 3, false, kWriteY><<<grid, block, 0, s>>>(a); break;
-            case 4: ln_fwd_kernel<T, 4, false, kWriteY><<<grid, block, 0, s>>>(a); break;
+            case 1: return launch(ln_fwd_kernel<T, 1, false, kWriteY>, grid, block, 0, s, a);
+            case 2: return launch(ln_fwd_kernel<T, 2, false, kWriteY>, grid, block, 0, s, a);
+            case 3: return launch(ln_fwd_kernel<T, 3, false, kWriteY>, grid, block, 0, s, a);
+            case 4: return launch(ln_fwd_kernel<T, 4, false, kWriteY>, grid, block, 0, s, a);
             default: return hipErrorInvalidValue;
         }
     } else {
@@ -376,14 +370,13 @@ hipError_t launch_fwd(FwdArgs a, bool vector_ok, hipStream_t s)
         const int64_t cap = waves <= 4 ? 4096 / waves : 4096;
         const dim3 grid((unsigned)(N < cap ? N : cap)), block(64 * waves);
         switch (vpt) {
-            case 1: ln_fwd_kernel<T, 1, true, kWriteY><<<grid, block, 0, s>>>(a); break;
-            case 2: ln_fwd_kernel<T, 2, true, kWriteY><<<grid, block, 0, s>>>(a); break;
-            case 3: ln_fwd_kernel<T, 3, true, kWriteY><<<grid, block, 0, s>>>(a); break;
-            case 4: ln_fwd_kernel<T, 4, true, kWriteY><<<grid, block, 0, s>>>(a); break;
+            case 1: return launch(ln_fwd_kernel<T, 1, true, kWriteY>, grid, block, 0, s, a);
+            case 2: return launch(ln_fwd_kernel<T, 2, true, kWriteY>, grid, block, 0, s, a);
+            case 3: return launch(ln_fwd_kernel<T, 3, true, kWriteY>, grid, block, 0, s, a);
+            case 4: return launch(ln_fwd_kernel<T, 4, true, kWriteY>, grid, block, 0, s, a);
             default: return hipErrorInvalidValue;
         }
     }
-    return hipGetLastError();
 }
 
 }  // namespace
@@ -422,7 +415,6 @@ const char *lnpegn_status_string(int status)
 int ln_fwd_stats(const void *x, float *mean, float *rstd, int B, int T, int D, lnpegn_dtype dt,
                  float eps, void *stream)
 {
-    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
     if (!dtype_ok(dt)) return LNPEGN_EUNSUPPORTED;
     if (!x || !mean || !rstd) return LNPEGN_EINVAL;
@@ -438,7 +430,6 @@ int ln_fwd_stats(const void *x, float *mean, float *rstd, int B, int T, int D, l
 int ln_fwd(const void *x, const void *gamma, const void *beta, void *y, float *mean, float *rstd, int B,
            int T, int D, lnpegn_dtype dt, lnpegn_dtype gamma_dt, float eps, void *stream)
 {
-    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
     if (!dtype_ok(dt) || !dtype_ok(gamma_dt)) return LNPEGN_EUNSUPPORTED;
     if (!x || !gamma || !beta || !y) return LNPEGN_EINVAL;
@@ -523,7 +514,6 @@ int ln_bwd_ex(const void *x, const void *dy, const void *gamma, const float *mea
 int rms_fwd(const void *x, const void *gamma, void *y, float *rstd, int B, int T, int D, lnpegn_dtype dt,
             lnpegn_dtype gamma_dt, float eps, void *stream)
 {
-    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
     if (!dtype_ok(dt) || !dtype_ok(gamma_dt)) return LNPEGN_EUNSUPPORTED;
     if (!x || !gamma || !y) return LNPEGN_EINVAL;
@@ -552,7 +542,6 @@ int rms_bwd_ex(const void *x, const void *dy, const void *gamma, const float *rs
 int lnpegn_reduce_deferred(void *const *workspaces, int n, int B, int T, int D, lnpegn_dtype dt,
                            void *stream)
 {
-    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!workspaces || n <= 0 || !shape_ok(B, T, D)) return LNPEGN_EINVAL;
     if (!dtype_ok(dt)) return LNPEGN_EUNSUPPORTED;
     for (int i = 0; i < n; ++i)
@@ -567,10 +556,8 @@ int lnpegn_reduce_deferred(void *const *workspaces, int n, int B, int T, int D, 
         b.D = D; b.ntile = p.ntile;
         b.off_grp = p.off_grp; b.off_part_s = p.off_part_s; b.off_part_big = p.off_part_big;
         b.off_part = p.off_part;
-        reduce_groups_batch_kernel<<<dim3((unsigned)g1_max, (unsigned)p.ntile, (unsigned)b.n), dim3(kTile), 0, s>>>(b);
-        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
-        reduce_final_batch_kernel<<<dim3((unsigned)b.n), dim3(1024), 0, s>>>(b);
-        if (hipGetLastError() != hipSuccess) return LNPEGN_EHIP;
+        if (launch(reduce_groups_batch_kernel, dim3((unsigned)g1_max, (unsigned)p.ntile, (unsigned)b.n), dim3(kTile), 0, s, b) != hipSuccess) return LNPEGN_EHIP;
+        if (launch(reduce_final_batch_kernel, dim3((unsigned)b.n), dim3(1024), 0, s, b) != hipSuccess) return LNPEGN_EHIP;
     }
     return LNPEGN_OK;
 }
@@ -578,28 +565,20 @@ int lnpegn_reduce_deferred(void *const *workspaces, int n, int B, int T, int D, 
 int gns_estimate(const float *pe_sq, const float *big_sq, int n_groups, int B, float pe_scale,
                  float *out, void *stream)
 {
-    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!pe_sq || !big_sq || !out || n_groups <= 0 || B <= 1) return LNPEGN_EINVAL;
-    gns_estimate_kernel<<<dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
-        pe_sq, big_sq, n_groups, B, pe_scale, out);
-    return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+    return launch(gns_estimate_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream),  pe_sq, big_sq, n_groups, B, pe_scale, out) == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
 }
 
 int gns_ema_update(double *state, const float *records, int n, double alpha, float *smoothed, void *stream)
 {
-    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!state || !records || n <= 0 || !(alpha >= 0.0 && alpha < 1.0)) return LNPEGN_EINVAL;
-    gns_ema_update_kernel<<<dim3((n + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
-        state, records, n, alpha, smoothed);
-    return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+    return launch(gns_ema_update_kernel, dim3((n + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),  state, records, n, alpha, smoothed) == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
 }
 
 int gns_offline(const float *records, int64_t n, float *out, void *stream)
 {
-    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!records || !out || n < 2) return LNPEGN_EINVAL;
-    gns_offline_kernel<<<dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(records, n, out);
-    return hipGetLastError() == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+    return launch(gns_offline_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), records, n, out) == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
 }
 
 int gns_linear_accum_steps(int64_t tokens_seen, int64_t ramp_tokens, int accum_final)
@@ -652,7 +631,6 @@ int lnpegn_set_tuning(int key, int value)
 
 int lnpegn_stream_probe(const void *a, const void *b, void *out, size_t bytes, int mode, void *stream)
 {
-    (void)hipGetLastError();   // an error left behind by earlier, unrelated HIP calls of this thread is not this call's
     if (!a || !out || (mode >= 1 && !b) || bytes == 0 || bytes % 16) return LNPEGN_EINVAL;
     if (mode < 0 || mode > 2) return LNPEGN_EINVAL;
     if (!aligned16(a) || !aligned16(out) || (mode >= 1 && !aligned16(b))) return LNPEGN_EINVAL;

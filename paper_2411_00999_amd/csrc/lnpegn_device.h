@@ -279,4 +279,19 @@ __device__ __forceinline__ double block_sum_f64(double v, double *slots)
     return t;
 }
 
+
+// Kernel launch that reports its own status: hipLaunchKernel returns the launch's error, so no
+// call here reads (or clears) the thread's last-error state, which may belong to the caller.
+template <typename T>
+struct launch_identity {
+    using type = T;
+};
+template <typename... KArgs>
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                         typename launch_identity<KArgs>::type... args)
+{
+    void *ptrs[] = {const_cast<void *>(static_cast<const void *>(&args))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, lds, stream);
+}
+
 }  // namespace lnpegn
