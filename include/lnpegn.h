@@ -282,12 +282,28 @@ int linear_pegn(const void *x, const void *g, float *w, float *s, float *big_sq,
  * reproducible).  workspace: embedding_pegn_workspace_bytes(...) bytes (0 if the shape is invalid or
  * no device is present: the sort's scratch is sized for the current device), 256-byte aligned,
  * caller-owned, contents scratch.  B*T < 2^31, V < 2^30.  Enqueued on stream, never synchronises.
- * Without LNPEGN_ACCUMULATE the zero fill of w runs on a side stream that the library creates once per
+ * Without LNPEGN_ACCUMULATE the zero fill of w (of the rows that no id selects) runs on a side stream that the library creates once per
  * device (default priority, kept until the process ends), forked from and joined back to `stream` with
  * events inside this call: to the caller the call is still one piece of work on `stream`; calls issued
  * from several streams of one device share the side stream and may serialise on it.
  */
 size_t embedding_pegn_workspace_bytes(int B, int T, int D, int V);
+/*
+ * The same computation with the sort taken off the backward pass.  The ids are known when the forward pass runs:
+ * embedding_sort_ids sorts them there (stable: by id, positions b*T+t ascending inside an id; ids outside [0,V)
+ * get the key V and sort last), and embedding_pegn_presorted takes the two sorted arrays in place of ids.  Results
+ * are bitwise those of embedding_pegn.
+ *   sorted_ids, sorted_pos [B*T] uint32 (device), the caller's: written by embedding_sort_ids, read by
+ *     embedding_pegn_presorted, which requires exactly that order (it is not checked).
+ *   workspace: embedding_pegn_workspace_bytes(B, T, D, V) for embedding_pegn_presorted,
+ *     embedding_pegn_workspace_bytes(B, T, 1, V) suffices for embedding_sort_ids.
+ * Without the sort in front of it the zero fill of the rows that no id selects runs beside the kernels that read g.
+ */
+int embedding_sort_ids(const void *ids, int ids_are_int64, int B, int T, int V, uint32_t *sorted_ids,
+                       uint32_t *sorted_pos, void *workspace, size_t workspace_bytes, void *stream);
+int embedding_pegn_presorted(const uint32_t *sorted_ids, const uint32_t *sorted_pos, const void *g, float *w, float *s,
+                             float *big_sq, int B, int T, int D, int V, lnpegn_dtype dt, void *workspace,
+                             size_t workspace_bytes, unsigned flags, void *stream);
 int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, float *s, float *big_sq, int B, int T,
                    int D, int V, lnpegn_dtype dt, void *workspace, size_t workspace_bytes, unsigned flags, void *stream);
 

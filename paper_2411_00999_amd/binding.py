@@ -22,7 +22,8 @@ EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "lnpegn_last_hip_er
            "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred",
            "ln_fwd", "ln_bwd_ex", "rms_fwd", "rms_bwd_ex",
            "gns_ema_update", "gns_offline", "gns_linear_accum_steps",
-           "linear_pegn_workspace_bytes", "linear_pegn", "embedding_pegn_workspace_bytes", "embedding_pegn")
+           "linear_pegn_workspace_bytes", "linear_pegn", "embedding_pegn_workspace_bytes", "embedding_pegn",
+           "embedding_sort_ids", "embedding_pegn_presorted")
 PER_EXAMPLE, DEFER, ACCUMULATE = 1, 2, 4
 
 _lib = None
@@ -79,6 +80,8 @@ def load() -> ctypes.CDLL:
     lib.embedding_pegn_workspace_bytes.argtypes = [i, i, i, i]
     lib.embedding_pegn_workspace_bytes.restype = sz
     lib.embedding_pegn.argtypes = [vp, i, vp, fp, fp, fp, i, i, i, i, i, vp, sz, ctypes.c_uint, vp]
+    lib.embedding_sort_ids.argtypes = [vp, i, i, i, i, vp, vp, vp, sz, vp]
+    lib.embedding_pegn_presorted.argtypes = [vp, vp, vp, fp, fp, fp, i, i, i, i, i, vp, sz, ctypes.c_uint, vp]
     lib.rms_fwd.argtypes = [vp, vp, vp, fp, i, i, i, i, i, f, vp]
     lib.rms_bwd_ex.argtypes = [vp, vp, vp, fp, vp, fp, fp, fp, i, i, i, i, i, f, vp, sz, ctypes.c_uint, vp]
     lib.gns_estimate.argtypes = [fp, fp, i, i, f, fp, vp]
@@ -89,7 +92,7 @@ def load() -> ctypes.CDLL:
                  "lnpegn_set_profile_events", "lnpegn_stream_probe", "ln_bwd_deferred",
                  "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred", "ln_fwd", "ln_bwd_ex",
                  "rms_fwd", "rms_bwd_ex", "gns_ema_update", "gns_offline", "gns_linear_accum_steps",
-                 "linear_pegn", "embedding_pegn"):
+                 "linear_pegn", "embedding_pegn", "embedding_sort_ids", "embedding_pegn_presorted"):
         getattr(lib, name).restype = i
     _lib = lib
     return lib
@@ -220,6 +223,49 @@ def embedding_pegn(ids, g, V: int, w=None, accumulate=False, s=None, big_sq=None
                                ACCUMULATE if accumulate else 0, _stream(stream))
     if rc:
         raise LnpegnError("embedding_pegn", rc)
+    return w, s, big_sq
+
+
+def embedding_sort_ids(ids, V: int, workspace=None, stream=None):
+    """ids [B,T] int32/int64 -> (sorted_ids [B*T] int32 bit patterns of uint32, sorted_pos [B*T]): what
+    embedding_pegn_presorted takes in place of ids (sort once at forward time)."""
+    torch = _torch()
+    if ids.dim() != 2 or not ids.is_contiguous() or ids.dtype not in (torch.int32, torch.int64):
+        raise ValueError("ids must be a contiguous [B,T] int32 or int64 tensor")
+    B, T = ids.shape
+    n = B * T
+    sorted_ids = torch.empty(n, dtype=torch.int32, device=ids.device)
+    sorted_pos = torch.empty(n, dtype=torch.int32, device=ids.device)
+    if workspace is None:
+        workspace = torch.empty(load().embedding_pegn_workspace_bytes(B, T, 1, V), dtype=torch.uint8, device=ids.device)
+    rc = load().embedding_sort_ids(_ptr(ids), 1 if ids.dtype == torch.int64 else 0, B, T, V, _ptr(sorted_ids),
+                                   _ptr(sorted_pos), _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise LnpegnError("embedding_sort_ids", rc)
+    return sorted_ids, sorted_pos
+
+
+def embedding_pegn_presorted(sorted_ids, sorted_pos, g, V: int, w=None, accumulate=False, s=None, big_sq=None,
+                             workspace=None, stream=None):
+    """embedding_pegn with the ids sorted beforehand by embedding_sort_ids -> (w [V,D], s [B], big_sq [1])."""
+    torch = _torch()
+    B, T, D = _check3(g)
+    if sorted_ids.numel() != B * T or sorted_pos.numel() != B * T:
+        raise ValueError("sorted_ids and sorted_pos must hold B*T entries")
+    f32 = dict(dtype=torch.float32, device=g.device)
+    if w is None:
+        if accumulate:
+            raise ValueError("accumulate needs the buffer to add to")
+        w = torch.empty((V, D), **f32)
+    s = torch.empty(B, **f32) if s is None else s
+    big_sq = torch.empty(1, **f32) if big_sq is None else big_sq
+    if workspace is None:
+        workspace = torch.empty(load().embedding_pegn_workspace_bytes(B, T, D, V), dtype=torch.uint8, device=g.device)
+    rc = load().embedding_pegn_presorted(_ptr(sorted_ids), _ptr(sorted_pos), _ptr(g), _ptr(w), _ptr(s), _ptr(big_sq),
+                                         B, T, D, V, _dt(g), _ptr(workspace), workspace.numel(),
+                                         ACCUMULATE if accumulate else 0, _stream(stream))
+    if rc:
+        raise LnpegnError("embedding_pegn_presorted", rc)
     return w, s, big_sq
 
 

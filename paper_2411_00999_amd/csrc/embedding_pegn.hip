@@ -44,20 +44,44 @@ __global__ __launch_bounds__(256) void emb_prepare_kernel(const void *ids, int i
     for (int64_t j = i; j < nscratch; j += (int64_t)gridDim.x * 256) scratch[j] = 0.f;
 }
 
-// Zero fill with streaming stores: the zeros are not wanted in any cache (the rows read next are g's), and
-// lines left dirty in the memory-side cache would be written back one by one under the reads that follow.
-__global__ __launch_bounds__(256) void emb_fill_kernel(float *p, int64_t n)
+// present[v] = 1 for every id that occurs (out-of-range ids carry the key V and are left out).  Plain byte
+// stores of the same value: the result does not depend on the order.  `present` was cleared by the launch before.
+__global__ __launch_bounds__(256) void emb_mark_kernel(const uint32_t *keys, int64_t n, int V, uint8_t *present)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) {
+        const uint32_t k = keys[i];
+        if (k < (uint32_t)V) present[k] = 1;
+    }
+}
+
+// Clears the scratch arrays of a call whose keys are already sorted (the sorting call's prepare kernel does it
+// otherwise).
+__global__ __launch_bounds__(256) void emb_clear_kernel(float *scratch, int64_t nscratch)
+{
+    for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < nscratch; j += (int64_t)gridDim.x * 256) scratch[j] = 0.f;
+}
+
+// Zero fill of the rows of w' that no id selects (the rows of ids that occur are written, whole, by the run and
+// id kernels, so the fill and those kernels touch different rows and may run side by side).  Streaming stores:
+// the zeros are not wanted in any cache (the rows read next are g's), and lines left dirty in the memory-side
+// cache would be written back one by one under the reads that follow.
+__global__ __launch_bounds__(256) void emb_fill_kernel(float *p, int64_t V, int D, const uint8_t *present)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
+    const int64_t n = V * D;
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if ((reinterpret_cast<uintptr_t>(p) & 15u) == 0) {
+    if ((reinterpret_cast<uintptr_t>(p) & 15u) == 0 && D % 4 == 0) {
         typedef __attribute__((ext_vector_type(4))) float f32x4;
         f32x4 *p4 = reinterpret_cast<f32x4 *>(p);
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-        for (; i < n / 4; i += stride) __builtin_nontemporal_store(zero, p4 + i);
-        i = (n / 4) * 4 + (int64_t)blockIdx.x * 256 + threadIdx.x;
+        const int d4 = D / 4;
+        for (; i < n / 4; i += stride)
+            if (!present[i / d4]) __builtin_nontemporal_store(zero, p4 + i);
+        return;
     }
-    for (; i < n; i += stride) p[i] = 0.f;
+    for (; i < n; i += stride)
+        if (!present[i / D]) p[i] = 0.f;
 }
 
 // eight columns of one row, added into sub: 16-byte loads when the row allows, element loads otherwise
@@ -652,7 +676,7 @@ int key_bits(int V)
 struct EmbPlan {
     int64_t n;
     int ncb;
-    size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_contrib, off_bigpart, off_multi, off_multi_run, off_wpart, off_temp, off_runsum;
+    size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_contrib, off_bigpart, off_multi, off_multi_run, off_present, off_wpart, off_temp, off_runsum;
     size_t temp_bytes, bytes;
 };
 
@@ -680,7 +704,8 @@ hipError_t make_emb_plan(int B, int T, int D, int V, EmbPlan &p)
     p.off_bigpart = p.off_contrib + f;            // directly behind contrib, the marks behind that: one fill
     p.off_multi = p.off_bigpart + f;              // clears all three
     p.off_multi_run = p.off_multi + arr;
-    p.off_wpart = p.off_multi_run + arr;
+    p.off_present = p.off_multi_run + arr;        // one byte per vocabulary row, cleared with the rest
+    p.off_wpart = p.off_present + align256((size_t)V);
     p.off_temp = p.off_wpart + align256(kNormBlocks * sizeof(double));
     p.temp_bytes = temp;
     p.off_runsum = p.off_temp + align256(temp);
@@ -702,10 +727,15 @@ size_t embedding_pegn_workspace_bytes(int B, int T, int D, int V)
     return make_emb_plan(B, T, D, V, p) == hipSuccess ? p.bytes : 0;
 }
 
-int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, float *s, float *big_sq, int B, int T,
-                   int D, int V, lnpegn_dtype dt, void *workspace, size_t workspace_bytes, unsigned flags, void *stream)
+// The call behind embedding_pegn and embedding_pegn_presorted.  With `ids`: keys are made and sorted here (the
+// zero fill runs beside the sort).  With sorted_ids / sorted_pos: the caller sorted them earlier
+// (embedding_sort_ids), the scratch is cleared here and the fill runs beside the run and id kernels.
+static int run_embedding(const void *ids, int ids_are_int64, const uint32_t *sorted_ids, const uint32_t *sorted_pos,
+                         const void *g, float *w, float *s, float *big_sq, int B, int T, int D, int V, lnpegn_dtype dt,
+                         void *workspace, size_t workspace_bytes, unsigned flags, void *stream)
 {
-    if (!emb_shape_ok(B, T, D, V) || !ids || !g || !w || !s || !workspace) return LNPEGN_EINVAL;
+    if (!emb_shape_ok(B, T, D, V) || !g || !w || !s || !workspace) return LNPEGN_EINVAL;
+    if (!ids && (!sorted_ids || !sorted_pos)) return LNPEGN_EINVAL;
     if (flags & ~(unsigned)LNPEGN_ACCUMULATE) return LNPEGN_EINVAL;
     if (dt != LNPEGN_F32 && dt != LNPEGN_BF16) return LNPEGN_EUNSUPPORTED;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return LNPEGN_EINVAL;
@@ -716,20 +746,31 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
     const int accumulate = (flags & LNPEGN_ACCUMULATE) ? 1 : 0;
     char *ws = static_cast<char *>(workspace);
     uint32_t *keys_in = reinterpret_cast<uint32_t *>(ws + p.off_keys_in);
-    uint32_t *keys_out = reinterpret_cast<uint32_t *>(ws + p.off_keys_out);
     uint32_t *vals_in = reinterpret_cast<uint32_t *>(ws + p.off_vals_in);
-    uint32_t *vals_out = reinterpret_cast<uint32_t *>(ws + p.off_vals_out);
+    const uint32_t *keys_out = ids ? reinterpret_cast<uint32_t *>(ws + p.off_keys_out) : sorted_ids;
+    const uint32_t *vals_out = ids ? reinterpret_cast<uint32_t *>(ws + p.off_vals_out) : sorted_pos;
     float *contrib = reinterpret_cast<float *>(ws + p.off_contrib);
     float *bigpart = reinterpret_cast<float *>(ws + p.off_bigpart);
     uint32_t *multi = reinterpret_cast<uint32_t *>(ws + p.off_multi);
     uint32_t *multi_run = reinterpret_cast<uint32_t *>(ws + p.off_multi_run);
+    uint8_t *present = reinterpret_cast<uint8_t *>(ws + p.off_present);
     double *wpart = reinterpret_cast<double *>(ws + p.off_wpart);
     const int64_t nscratch = (int64_t)((p.off_wpart - p.off_contrib) / sizeof(float));
-    // fork: the fill starts now on the side stream (on the caller's stream if there is none)
+    const unsigned nblk = (unsigned)((p.n + 255) / 256);
+
+    // 1. scratch cleared (and keys made), then the ids that occur marked: from here the fill knows its rows
+    if (ids) {
+        if (launch(emb_prepare_kernel, dim3(nblk), dim3(256), 0, st, ids, ids_are_int64, keys_in, vals_in, contrib, p.n, nscratch, V) != hipSuccess) return LNPEGN_EHIP;
+    } else {
+        const unsigned cb = (unsigned)(nscratch / 256 / 4 + 1 < 4096 ? nscratch / 256 / 4 + 1 : 4096);
+        if (launch(emb_clear_kernel, dim3(cb), dim3(256), 0, st, contrib, nscratch) != hipSuccess) return LNPEGN_EHIP;
+    }
+    // 2. fork: the fill of the rows no id selects, on the side stream (on the caller's stream if there is none)
     SideStream *side = accumulate ? nullptr : side_stream();
     std::unique_lock<std::mutex> side_lock;
     if (side) side_lock = std::unique_lock<std::mutex>(side->in_use);
     if (!accumulate) {
+        if (launch(emb_mark_kernel, dim3(nblk), dim3(256), 0, st, ids ? keys_in : keys_out, p.n, V, present) != hipSuccess) return LNPEGN_EHIP;
         hipStream_t fs = st;
         if (side) {
             if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
@@ -738,18 +779,17 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
         }
         const int64_t nw = (int64_t)V * D;
         const unsigned fb = (unsigned)(nw / 256 / 8 + 1 < 65536 ? nw / 256 / 8 + 1 : 65536);
-        if (launch(emb_fill_kernel, dim3(fb), dim3(256), 0, fs, w, nw) != hipSuccess) return LNPEGN_EHIP;
+        if (launch(emb_fill_kernel, dim3(fb), dim3(256), 0, fs, w, (int64_t)V, D, present) != hipSuccess) return LNPEGN_EHIP;
         if (side && hipEventRecord(side->join, fs) != hipSuccess) return LNPEGN_EHIP;
     }
-    const unsigned nblk = (unsigned)((p.n + 255) / 256);
-    if (launch(emb_prepare_kernel, dim3(nblk), dim3(256), 0, st, ids, ids_are_int64, keys_in, vals_in, contrib, p.n, nscratch, V) != hipSuccess) return LNPEGN_EHIP;
-    size_t temp = p.temp_bytes;
-    if (rocprim::radix_sort_pairs(ws + p.off_temp, temp, keys_in, keys_out, vals_in, vals_out, (size_t)p.n, 0,
-                                  key_bits(V), st) != hipSuccess)
-        return LNPEGN_EHIP;
-    // join: the rows of w' are written from here on
-    if (side && hipStreamWaitEvent(st, side->join, 0) != hipSuccess) return LNPEGN_EHIP;
-    if (side) side_lock.unlock();
+    // 3. the sort, unless the caller did it
+    if (ids) {
+        size_t temp = p.temp_bytes;
+        if (rocprim::radix_sort_pairs(ws + p.off_temp, temp, keys_in, const_cast<uint32_t *>(keys_out), vals_in,
+                                      const_cast<uint32_t *>(vals_out), (size_t)p.n, 0, key_bits(V), st) != hipSuccess)
+            return LNPEGN_EHIP;
+    }
+    // 4. runs, then the marked runs and ids: these write the rows of the ids that occur, the fill the others
     const int esz = dt == LNPEGN_BF16 ? 2 : 4;
     // 8 columns per lane: 16 bytes of bf16, 32 bytes of fp32; rows must keep that alignment
     const int vec_ok = ((reinterpret_cast<uintptr_t>(g) & 15u) == 0 && ((int64_t)D * esz) % 16 == 0) ? 1 : 0;
@@ -771,11 +811,54 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
     if (runs_status != hipSuccess) return LNPEGN_EHIP;
     if (launch(emb_sums_kernel<false>, grid, dim3(64 * kWavesPerBlock), 0, st, keys_out, vals_out, w, runsum, contrib, bigpart, multi_run, p.n, T, D, V, accumulate) != hipSuccess) return LNPEGN_EHIP;
     if (launch(emb_sums_kernel<true>, grid, dim3(64 * kWavesPerBlock), 0, st, keys_out, vals_out, w, runsum, contrib, bigpart, multi, p.n, T, D, V, accumulate) != hipSuccess) return LNPEGN_EHIP;
+    // 5. join: w' is complete on the caller's stream from here
+    if (side && hipStreamWaitEvent(st, side->join, 0) != hipSuccess) return LNPEGN_EHIP;
+    if (side) side_lock.unlock();
     const bool wnorm = accumulate && big_sq;
     if (wnorm) {
         if (launch(emb_wnorm_kernel, dim3(kNormBlocks), dim3(256), 0, st, w, (int64_t)V * D, wpart) != hipSuccess) return LNPEGN_EHIP;
     }
     return launch(emb_final_kernel, dim3(B + 1), dim3(1024), 0, st, contrib, bigpart, wnorm ? wpart : nullptr, kNormBlocks, s, big_sq, B, T, p.ncb, p.n) == hipSuccess ? LNPEGN_OK : LNPEGN_EHIP;
+}
+
+int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, float *s, float *big_sq, int B, int T,
+                   int D, int V, lnpegn_dtype dt, void *workspace, size_t workspace_bytes, unsigned flags, void *stream)
+{
+    if (!ids) return LNPEGN_EINVAL;
+    return run_embedding(ids, ids_are_int64, nullptr, nullptr, g, w, s, big_sq, B, T, D, V, dt, workspace,
+                         workspace_bytes, flags, stream);
+}
+
+int embedding_sort_ids(const void *ids, int ids_are_int64, int B, int T, int V, uint32_t *sorted_ids,
+                       uint32_t *sorted_pos, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!emb_shape_ok(B, T, 1, V) || !ids || !sorted_ids || !sorted_pos || !workspace) return LNPEGN_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return LNPEGN_EINVAL;
+    EmbPlan p;
+    if (make_emb_plan(B, T, 1, V, p) != hipSuccess) return LNPEGN_EHIP;
+    if (workspace_bytes < p.bytes) return LNPEGN_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    uint32_t *keys_in = reinterpret_cast<uint32_t *>(ws + p.off_keys_in);
+    uint32_t *vals_in = reinterpret_cast<uint32_t *>(ws + p.off_vals_in);
+    const unsigned nblk = (unsigned)((p.n + 255) / 256);
+    if (launch(emb_prepare_kernel, dim3(nblk), dim3(256), 0, st, ids, ids_are_int64, keys_in, vals_in,
+               static_cast<float *>(nullptr), p.n, (int64_t)0, V) != hipSuccess)
+        return LNPEGN_EHIP;
+    size_t temp = p.temp_bytes;
+    return rocprim::radix_sort_pairs(ws + p.off_temp, temp, keys_in, sorted_ids, vals_in, sorted_pos, (size_t)p.n, 0,
+                                     key_bits(V), st) == hipSuccess
+               ? LNPEGN_OK
+               : LNPEGN_EHIP;
+}
+
+int embedding_pegn_presorted(const uint32_t *sorted_ids, const uint32_t *sorted_pos, const void *g, float *w, float *s,
+                             float *big_sq, int B, int T, int D, int V, lnpegn_dtype dt, void *workspace,
+                             size_t workspace_bytes, unsigned flags, void *stream)
+{
+    if (!sorted_ids || !sorted_pos) return LNPEGN_EINVAL;
+    return run_embedding(nullptr, 0, sorted_ids, sorted_pos, g, w, s, big_sq, B, T, D, V, dt, workspace,
+                         workspace_bytes, flags, stream);
 }
 
 }  // extern "C"

@@ -741,6 +741,53 @@ def test_embedding_pegn_against_oracle(dtype, B, T, D, V):
     _check_embedding(ids, g, V, _run_embedding(ids, g, V, dtype, w0=w0), w0=w0)
 
 
+@pytest.mark.parametrize("dtype,B,T,D,V", [("bf16", 4, 128, 768, 1000), ("bf16", 3, 70, 2048, 50257), ("f32", 2, 33, 264, 97),
+                                           ("bf16", 2, 9, 100, 7), ("bf16", 16, 64, 512, 31)])
+def test_embedding_pegn_presorted_matches_the_sorting_call(dtype, B, T, D, V):
+    """ids sorted beforehand (embedding_sort_ids, as a forward pass would): the same kernels on the same order, so
+    the results are bitwise those of embedding_pegn, overwrite and accumulate; out-of-range ids included."""
+    import torch
+    from oracle import embedding_pegn_oracle as emb
+    from paper_2411_00999_amd import binding
+    ids, g = workloads.make_embedding_inputs(B * 100 + T + 7, B, T, D, V, dtype)
+    gd = pu.to_device(g, dtype)
+    idd = torch.from_numpy(ids).cuda()
+    sk, sp = binding.embedding_sort_ids(idd, V)
+    torch.cuda.synchronize()
+    # the order itself: stable sort by id of the positions 0..n-1
+    order = np.argsort(ids.reshape(-1), kind="stable")
+    np.testing.assert_array_equal(sp.cpu().numpy(), order.astype(np.int32))
+    np.testing.assert_array_equal(sk.cpu().numpy(), ids.reshape(-1)[order].astype(np.int32))
+    for rep in range(2):                        # twice on one workspace: nothing is left behind
+        want = binding.embedding_pegn(idd, gd, V)
+        got = binding.embedding_pegn_presorted(sk, sp, gd, V)
+        torch.cuda.synchronize()
+        for a, b, name in zip(got, want, ("w", "s", "big_sq")):
+            assert torch.equal(a, b), name
+    _check_embedding(ids, g, V, tuple(pu.to_host64(t) for t in got))
+    w0 = torch.from_numpy(np.random.default_rng(3).normal(0, 1e-2, (V, D)).astype(np.float32)).cuda()
+    want = binding.embedding_pegn(idd, gd, V, w=w0.clone(), accumulate=True)
+    got = binding.embedding_pegn_presorted(sk, sp, gd, V, w=w0.clone(), accumulate=True)
+    torch.cuda.synchronize()
+    for a, b in zip(got, want):
+        assert torch.equal(a, b)
+    # ids outside [0, V) are skipped by both calls
+    bad = ids.copy()
+    bad[0, 0], bad[-1, -1] = V, -3
+    bd = torch.from_numpy(bad).cuda()
+    sk2, sp2 = binding.embedding_sort_ids(bd, V)
+    want = binding.embedding_pegn(bd, gd, V)
+    got = binding.embedding_pegn_presorted(sk2, sp2, gd, V)
+    torch.cuda.synchronize()
+    for a, b in zip(got, want):
+        assert torch.equal(a, b)
+    keep = np.ones(ids.shape, bool)
+    keep[0, 0] = keep[-1, -1] = False
+    ref = emb.embedding_pegn(np.where(keep, ids, 0), g * keep[..., None], V)
+    pu.check_close("w", pu.to_host64(got[0]), ref["w"], pu.TOL_SUMS)
+    np.testing.assert_allclose(pu.to_host64(got[1]), ref["s"], rtol=pu.TOL_SUMS)
+
+
 def test_embedding_pegn_special_cases():
     import torch
     from paper_2411_00999_amd import binding
