@@ -316,8 +316,8 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
  * key 5: cap on 16-byte vectors per lane and array of the row kernel (0 = automatic, else 1..4: fewer
  * means more waves share a row); key 6: workgroups (per group of four column blocks) of
  * embedding_pegn's run kernel, 1..65535 (default 4096; with fewer than one per 16 positions each
- * workgroup loops); key 7: dx stores of the row kernel (0 automatic: write-back while dx is at most
- * 96 MiB, streaming above; 1 always streaming; 2 always write-back).
+ * workgroup loops); key 7: dx stores of the row kernel (0 automatic: write-through while dx is at most
+ * 96 MiB, streaming above; 1 always streaming; 2 always write-through).
  * Returns LNPEGN_EINVAL for an unknown key or a value out of range.  Not thread-safe against concurrent launches.
  */
 int lnpegn_set_tuning(int key, int value);

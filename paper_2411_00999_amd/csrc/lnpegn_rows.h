@@ -111,7 +111,7 @@ constexpr int rows_kernel_min_blocks(int kS, int elems)
 
 // kPlain: the plain backward (one partition "example" spanning the whole tensor, never any
 // per-example output); it is a kernel of its own name so that a kernel trace tells the two apart.
-// kDxCached: dx is stored write-back (cached) instead of streaming.
+// kDxCached: dx is small enough for the memory-side cache: write-through stores instead of streaming ones.
 template <typename T, int kVpt, bool kSaved, int kS, bool kFull, bool kPlain, bool kDxCached>
 __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
 {
@@ -119,18 +119,16 @@ __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
     using Raw = typename V::Raw;
     constexpr int E = V::kElems;
     constexpr bool kSync = kS != 1;
-    // x and dy are read once: streaming loads (measured faster than cached loads at every row width once
-    // the loop no longer waits for its stores; D=8192: 291 -> 276 us, D=4096: 145 -> 139 us)
-#ifndef LNPEGN_LD_AUX
-#define LNPEGN_LD_AUX 2
-#endif
-#ifndef LNPEGN_ST_AUX
-#define LNPEGN_ST_AUX 2
-#endif
-#ifndef LNPEGN_ST_AUX_SMALL
-#define LNPEGN_ST_AUX_SMALL 0
-#endif
-    constexpr int kLoadAux = LNPEGN_LD_AUX;
+    // Cache policy of the row accesses (bits of the buffer instructions: 1 = sc0, 2 = nt, 16 = sc1), every one
+    // of them from measurements on B*T = 32768 rows:
+    //   x, dy   streaming loads at every row width (they are read once; cached loads: D=8192 291 against 276 us,
+    //           D=4096 145 against 139 us)
+    //   dx      streaming stores when dx is larger than what the memory-side cache takes next to the reads;
+    //           system-scope write-through stores (sc0 sc1) when it is not (B=512 T=64 D=1024: streaming 41.6,
+    //           plain write-back 37.3, sc0 sc1 35.6 us; at B=16 T=2048 D=2048 streaming wins, 70.6 against 77.5 us)
+    constexpr int kLoadAux = 2;
+    constexpr int kStoreAuxLarge = 2;
+    constexpr int kStoreAuxSmall = 17;
     constexpr bool kDrainStores = kS == 2;
     constexpr int NF = 2 * kVpt * E;  // accumulator floats per lane
     constexpr int KL = kVpt - 1;      // only a lane's last vector slot can be padding
@@ -355,7 +353,7 @@ __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
             // because a branch around a store makes the compiler wait for every store at the loop head
 #pragma unroll
             for (int k = 0; k < kVpt; ++k)
-                V::template store_buf<kDxCached ? LNPEGN_ST_AUX_SMALL : LNPEGN_ST_AUX>(
+                V::template store_buf<kDxCached ? kStoreAuxSmall : kStoreAuxLarge>(
                     ro, vidx[k] * (int)sizeof(Raw), packed[k]);
         }
         parity ^= 1;
