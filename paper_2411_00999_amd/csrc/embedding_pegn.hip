@@ -44,6 +44,96 @@ __global__ __launch_bounds__(256) void emb_prepare_kernel(const void *ids, int i
     for (int64_t j = i; j < nscratch; j += (int64_t)gridDim.x * 256) scratch[j] = 0.f;
 }
 
+// ---------------------------------------------------------------------------------------
+// Sort of the (id, position) pairs for batches of up to kSortTiles * kSortTile positions, in two launches.
+// A pair travels as one 64-bit word, id in the upper half and position in the lower: the words are distinct, so
+// any correct sort of them is the stable sort by id.  (1) Every workgroup sorts one tile of kSortTile words in LDS
+// (bitonic network).  (2) The place of a word in the whole order is the number of words below it: its index in
+// its own tile plus one binary search in each other tile; each thread places one word.
+// ---------------------------------------------------------------------------------------
+constexpr int kSortTile = 2048;
+constexpr int kSortTiles = 64;
+constexpr uint64_t kSortPad = ~(uint64_t)0;
+
+constexpr int kSortThreads = kSortTile / 2;   // one compare-exchange per thread and stage
+
+__global__ __launch_bounds__(kSortThreads) void emb_tile_sort_kernel(const void *ids, int ids_i64, int64_t n, int V,
+                                                                     uint64_t *tiles, float *scratch, int64_t nscratch)
+{
+    __shared__ uint64_t a[kSortTile];
+    const int tid = threadIdx.x;
+    const int64_t base = (int64_t)blockIdx.x * kSortTile;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int i = tid + h * kSortThreads;
+        const int64_t p = base + i;
+        uint64_t word = kSortPad;
+        if (p < n) {
+            const int64_t id = ids_i64 ? static_cast<const int64_t *>(ids)[p] : (int64_t) static_cast<const int32_t *>(ids)[p];
+            const uint32_t key = (id >= 0 && id < V) ? (uint32_t)id : (uint32_t)V;   // out of range: sorted behind, skipped
+            word = ((uint64_t)key << 32) | (uint32_t)p;
+        }
+        a[i] = word;
+    }
+    // the scratch arrays of the call are cleared here too (grid-stride), which saves a launch
+    for (int64_t j = (int64_t)blockIdx.x * kSortThreads + tid; j < nscratch; j += (int64_t)gridDim.x * kSortThreads)
+        scratch[j] = 0.f;
+    for (int k = 2; k <= kSortTile; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            __syncthreads();
+            const int lo = ((tid & ~(j - 1)) << 1) | (tid & (j - 1)), hi = lo + j;   // j is a power of two
+            const uint64_t x = a[lo], y = a[hi];
+            const bool ascending = (lo & k) == 0;
+            if ((x > y) == ascending) {
+                a[lo] = y;
+                a[hi] = x;
+            }
+        }
+    }
+    __syncthreads();
+    tiles[base + tid] = a[tid];
+    tiles[base + tid + kSortThreads] = a[tid + kSortThreads];
+}
+
+// Each thread places one word: sixteen binary searches (one per other tile) advance together, step by step, so
+// that sixteen independent loads are in flight instead of one chain of twelve dependent ones after another.
+__global__ __launch_bounds__(256) void emb_rank_kernel(const uint64_t *tiles, int ntiles, int64_t n, int V,
+                                                       uint32_t *sorted_ids, uint32_t *sorted_pos, uint8_t *present)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;     // index into the tiles array
+    if (i >= (int64_t)ntiles * kSortTile) return;
+    const uint64_t word = tiles[i];
+    if (word == kSortPad) return;
+    const int mine = (int)(i / kSortTile);
+    int64_t rank = i - (int64_t)mine * kSortTile;
+    constexpr int kGroup = 16;
+    for (int t0 = 0; t0 < ntiles; t0 += kGroup) {
+        const uint64_t *tile[kGroup];
+        int pos[kGroup];
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            const int t = t0 + u < ntiles ? t0 + u : mine;          // a tile that does not exist: searched, not counted
+            tile[u] = tiles + (int64_t)t * kSortTile;
+            pos[u] = 0;
+        }
+        // words of each tile below `word` (the tiles are sorted, kSortTile long): branch-free lower bound
+#pragma unroll
+        for (int step = kSortTile / 2; step > 0; step >>= 1) {
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) pos[u] += tile[u][pos[u] + step - 1] < word ? step : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            const int below = pos[u] + (tile[u][pos[u]] < word ? 1 : 0);
+            rank += (t0 + u < ntiles && t0 + u != mine) ? below : 0;
+        }
+    }
+    const uint32_t key = (uint32_t)(word >> 32);
+    sorted_ids[rank] = key;
+    sorted_pos[rank] = (uint32_t)word;
+    if (present && key < (uint32_t)V) present[key] = 1;
+}
+
 // present[v] = 1 for every id that occurs (out-of-range ids carry the key V and are left out).  Plain byte
 // stores of the same value: the result does not depend on the order.  `present` was cleared by the launch before.
 __global__ __launch_bounds__(256) void emb_mark_kernel(const uint32_t *keys, int64_t n, int V, uint8_t *present)
@@ -676,7 +766,7 @@ int key_bits(int V)
 struct EmbPlan {
     int64_t n;
     int ncb;
-    size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_contrib, off_bigpart, off_multi, off_multi_run, off_present, off_wpart, off_temp, off_runsum;
+    size_t off_keys_in, off_keys_out, off_vals_in, off_vals_out, off_contrib, off_bigpart, off_multi, off_multi_run, off_present, off_wpart, off_tiles, off_temp, off_runsum;
     size_t temp_bytes, bytes;
 };
 
@@ -706,7 +796,9 @@ hipError_t make_emb_plan(int B, int T, int D, int V, EmbPlan &p)
     p.off_multi_run = p.off_multi + arr;
     p.off_present = p.off_multi_run + arr;        // one byte per vocabulary row, cleared with the rest
     p.off_wpart = p.off_present + align256((size_t)V);
-    p.off_temp = p.off_wpart + align256(kNormBlocks * sizeof(double));
+    p.off_tiles = p.off_wpart + align256(kNormBlocks * sizeof(double));
+    const int64_t ntiles = (p.n + kSortTile - 1) / kSortTile;
+    p.off_temp = p.off_tiles + (ntiles <= kSortTiles ? align256((size_t)ntiles * kSortTile * sizeof(uint64_t)) : 0);
     p.temp_bytes = temp;
     p.off_runsum = p.off_temp + align256(temp);
     p.bytes = p.off_runsum + align256((size_t)p.n * D * sizeof(float));
@@ -758,8 +850,17 @@ static int run_embedding(const void *ids, int ids_are_int64, const uint32_t *sor
     const int64_t nscratch = (int64_t)((p.off_wpart - p.off_contrib) / sizeof(float));
     const unsigned nblk = (unsigned)((p.n + 255) / 256);
 
-    // 1. scratch cleared (and keys made), then the ids that occur marked: from here the fill knows its rows
-    if (ids) {
+    const int ntiles = (int)((p.n + kSortTile - 1) / kSortTile);
+    const bool own_sort = ids && ntiles <= kSortTiles;
+    uint64_t *tiles = reinterpret_cast<uint64_t *>(ws + p.off_tiles);
+    // 1. scratch cleared, the ids sorted (two launches of our own for up to kSortTiles * kSortTile positions; the
+    //    library's radix sort beyond that, after the fork), and the ids that occur marked for the fill
+    if (own_sort) {
+        if (launch(emb_tile_sort_kernel, dim3(ntiles), dim3(kSortThreads), 0, st, ids, ids_are_int64, p.n, V, tiles, contrib, nscratch) != hipSuccess) return LNPEGN_EHIP;
+        if (launch(emb_rank_kernel, dim3(ntiles * (kSortTile / 256)), dim3(256), 0, st, tiles, ntiles, p.n, V,
+                   const_cast<uint32_t *>(keys_out), const_cast<uint32_t *>(vals_out), accumulate ? nullptr : present) != hipSuccess)
+            return LNPEGN_EHIP;
+    } else if (ids) {
         if (launch(emb_prepare_kernel, dim3(nblk), dim3(256), 0, st, ids, ids_are_int64, keys_in, vals_in, contrib, p.n, nscratch, V) != hipSuccess) return LNPEGN_EHIP;
     } else {
         const unsigned cb = (unsigned)(nscratch / 256 / 4 + 1 < 4096 ? nscratch / 256 / 4 + 1 : 4096);
@@ -770,7 +871,9 @@ static int run_embedding(const void *ids, int ids_are_int64, const uint32_t *sor
     std::unique_lock<std::mutex> side_lock;
     if (side) side_lock = std::unique_lock<std::mutex>(side->in_use);
     if (!accumulate) {
-        if (launch(emb_mark_kernel, dim3(nblk), dim3(256), 0, st, ids ? keys_in : keys_out, p.n, V, present) != hipSuccess) return LNPEGN_EHIP;
+        if (!own_sort &&
+            launch(emb_mark_kernel, dim3(nblk), dim3(256), 0, st, ids ? keys_in : keys_out, p.n, V, present) != hipSuccess)
+            return LNPEGN_EHIP;
         hipStream_t fs = st;
         if (side) {
             if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
@@ -782,8 +885,8 @@ static int run_embedding(const void *ids, int ids_are_int64, const uint32_t *sor
         if (launch(emb_fill_kernel, dim3(fb), dim3(256), 0, fs, w, (int64_t)V, D, present) != hipSuccess) return LNPEGN_EHIP;
         if (side && hipEventRecord(side->join, fs) != hipSuccess) return LNPEGN_EHIP;
     }
-    // 3. the sort, unless the caller did it
-    if (ids) {
+    // 3. the library's sort for batches beyond our own
+    if (ids && !own_sort) {
         size_t temp = p.temp_bytes;
         if (rocprim::radix_sort_pairs(ws + p.off_temp, temp, keys_in, const_cast<uint32_t *>(keys_out), vals_in,
                                       const_cast<uint32_t *>(vals_out), (size_t)p.n, 0, key_bits(V), st) != hipSuccess)
@@ -841,6 +944,17 @@ int embedding_sort_ids(const void *ids, int ids_are_int64, int B, int T, int V, 
     char *ws = static_cast<char *>(workspace);
     uint32_t *keys_in = reinterpret_cast<uint32_t *>(ws + p.off_keys_in);
     uint32_t *vals_in = reinterpret_cast<uint32_t *>(ws + p.off_vals_in);
+    const int ntiles = (int)((p.n + kSortTile - 1) / kSortTile);
+    if (ntiles <= kSortTiles) {
+        uint64_t *tiles = reinterpret_cast<uint64_t *>(ws + p.off_tiles);
+        if (launch(emb_tile_sort_kernel, dim3(ntiles), dim3(kSortThreads), 0, st, ids, ids_are_int64, p.n, V, tiles,
+                   static_cast<float *>(nullptr), (int64_t)0) != hipSuccess)
+            return LNPEGN_EHIP;
+        return launch(emb_rank_kernel, dim3(ntiles * (kSortTile / 256)), dim3(256), 0, st, tiles, ntiles, p.n, V, sorted_ids,
+                      sorted_pos, static_cast<uint8_t *>(nullptr)) == hipSuccess
+                   ? LNPEGN_OK
+                   : LNPEGN_EHIP;
+    }
     const unsigned nblk = (unsigned)((p.n + 255) / 256);
     if (launch(emb_prepare_kernel, dim3(nblk), dim3(256), 0, st, ids, ids_are_int64, keys_in, vals_in,
                static_cast<float *>(nullptr), p.n, (int64_t)0, V) != hipSuccess)

@@ -348,7 +348,7 @@ hipError_t launch_fwd(FwdArgs a, bool vector_ok, hipStream_t s)
     constexpr int E = Vec<T>::kElems;
     const int D = a.D;
     const int64_t N = a.N;
-    const bool fast = vector_ok && (D % E == 0) && (D / E <= 64 * (16 / E) * 8);
+    const bool fast = vector_ok && (D % E == 0) && (D / E <= 64 * (16 / E) * 16);   // up to 16 waves share a row
     if (!fast) {
         const unsigned grid = (unsigned)(N < 4096 ? N : 4096);
         return launch(ln_fwd_generic_kernel<T, kWriteY>, dim3(grid), dim3(256), 0, s, a);

@@ -256,7 +256,8 @@ def test_deferred_reduction_matches_immediate_calls_bitwise(cfg, B, T, D):
 
 # ------------------------------------------------------------------ forward, accumulation
 @pytest.mark.parametrize("cfg,B,T,D", [(1, 4, 128, 256), (2, 3, 37, 768), (3, 2, 50, 2048), (5, 2, 9, 8192),
-                                      (1, 2, 7, 257), (2, 2, 5, 1001)])
+                                      (1, 2, 7, 257), (2, 2, 5, 1001), (5, 2, 7, 12288), (5, 1, 5, 16384),
+                                      (1, 2, 5, 12288), (1, 1, 3, 16384), (5, 1, 3, 20480)])
 def test_forward_against_oracle(cfg, B, T, D):
     import torch
     from paper_2411_00999_amd import binding
@@ -786,6 +787,35 @@ def test_embedding_pegn_presorted_matches_the_sorting_call(dtype, B, T, D, V):
     ref = emb.embedding_pegn(np.where(keep, ids, 0), g * keep[..., None], V)
     pu.check_close("w", pu.to_host64(got[0]), ref["w"], pu.TOL_SUMS)
     np.testing.assert_allclose(pu.to_host64(got[1]), ref["s"], rtol=pu.TOL_SUMS)
+
+
+@pytest.mark.parametrize("B,T", [(1, 2048), (3, 2049), (16, 2048), (5, 5000), (64, 2048), (70, 2048)])
+def test_embedding_sort_sizes_around_the_tile_boundaries(B, T):
+    """One tile, a ragged second tile, the benchmark's 16 tiles, the largest batch our own sort takes (64 tiles)
+    and one beyond it (the library's sort): the order is the stable sort by id, and the whole call matches."""
+    import torch
+    from paper_2411_00999_amd import binding
+    V, D = 1000, 8
+    ids, g = workloads.make_embedding_inputs(B + T, B, T, D, V, "f32")
+    ids[0, : min(T, 7)] = [V, -1, 0, V - 1, 2 ** 31 - 1, -2 ** 31, 5][: min(T, 7)]      # out of range and the edges
+    for int32 in (False, True):
+        idd = torch.from_numpy(ids.astype(np.int32 if int32 else np.int64)).cuda()
+        sk, sp = binding.embedding_sort_ids(idd, V)
+        torch.cuda.synchronize()
+        key = np.where((ids >= 0) & (ids < V), ids, V).reshape(-1)
+        order = np.argsort(key, kind="stable")
+        np.testing.assert_array_equal(sp.cpu().numpy(), order.astype(np.int32))
+        np.testing.assert_array_equal(sk.cpu().numpy(), key[order].astype(np.int32))
+    gd = pu.to_device(g, "f32")
+    w, s, big = binding.embedding_pegn(idd, gd, V)
+    w2, s2, big2 = binding.embedding_pegn_presorted(sk, sp, gd, V)
+    torch.cuda.synchronize()
+    assert torch.equal(w, w2) and torch.equal(s, s2) and torch.equal(big, big2)
+    from oracle import embedding_pegn_oracle as emb
+    keep = (ids >= 0) & (ids < V)
+    ref = emb.embedding_pegn(np.where(keep, ids, 0), g * keep[..., None], V)
+    pu.check_close("w", pu.to_host64(w), ref["w"], pu.TOL_SUMS)
+    np.testing.assert_allclose(pu.to_host64(s), ref["s"], rtol=pu.TOL_SUMS)
 
 
 def test_embedding_pegn_special_cases():
