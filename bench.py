@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 MEASURED_TRAFFIC_BYTES = {3: 407_060_000}
 # The same for one whole call of linear_pegn / embedding_pegn on the named shapes (all kernels of the call;
 # profiles/linear_pegn_gpt1p3b_up_rocprofv3.md, profiles/embedding_pegn_gpt1p3b_wte_rocprofv3.md).
-MEASURED_CALL_TRAFFIC_BYTES = {"gpt1p3b_up": 3_134_000_000, "gpt1p3b_wte": 675_000_000}
+MEASURED_CALL_TRAFFIC_BYTES = {"gpt1p3b_up": 3_134_000_000, "gpt1p3b_wte": 611_800_000}
 
 
 # ----------------------------------------------------------------------------- HIP events
@@ -272,7 +272,7 @@ ROTATE_BYTES = 512 << 20     # bytes touched between two uses of a buffer set in
 # HBM bytes per row-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (fused kernel), per workload and
 # storage type; profiles/ln_bwd_rows_workloads_1_2_4_5_rocprofv3.md has the commands and the copy-kernel scale.
 # Re-measure after any change to the row kernel or its launch shape.  A workload without a measurement reports null.
-MEASURED_ROW_TRAFFIC = {(5, "bf16"): 1_644_470_000, (4, "bf16"): 205_730_000, (2, "bf16"): 41_060_000,
+MEASURED_ROW_TRAFFIC = {(5, "bf16"): 1_644_470_000, (4, "bf16"): 205_780_000, (2, "bf16"): 41_110_000,
                         (1, "f32"): 1_820_000, (3, "f32"): 813_950_000}
 
 
@@ -419,10 +419,11 @@ def main():
     ap.add_argument("--linear-shape", default="gpt1p3b_up", help="a key of workloads.LINEAR_SHAPES")
     ap.add_argument("--embedding-only", action="store_true", help="run only the embedding-layer leg")
     ap.add_argument("--embedding-shape", default="gpt1p3b_wte", help="a key of workloads.EMBEDDING_SHAPES")
-    ap.add_argument("--streams", type=int, default=1,
+    ap.add_argument("--streams", type=int, default=2,
                     help="streams the independent layers of the headline step are spread over (deferred reduction "
-                         "only).  1 = every launch on one stream, which is what the kernel durations of the roofline "
-                         "object and of a kernel trace refer to; the two-stream step is reported beside it")
+                         "only): with two, one layer's kernel ramps up while another's drains.  The step with every "
+                         "launch on one stream is reported beside it (other_stream_count), and the kernel durations of "
+                         "the roofline object are always taken on one stream, where a kernel's duration is its own")
     ap.add_argument("--tuning", default="", help="launch-shape overrides, key=value[,key=value...] "
                                                  "(lnpegn_set_tuning; for experiments, the reported defaults use none)")
     ap.add_argument("--quiet", action="store_true")
