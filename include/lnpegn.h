@@ -317,7 +317,9 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
  * means more waves share a row); key 6: workgroups (per group of four column blocks) of
  * embedding_pegn's run kernel, 1..65535 (default 4096; with fewer than one per 16 positions each
  * workgroup loops); key 7: dx stores of the row kernel (0 automatic: write-through while dx is at most
- * 96 MiB, streaming above; 1 always streaming; 2 always write-through).
+ * 96 MiB, streaming above; 1 always streaming; 2 always write-through); key 8: rows of a chunk (0 automatic:
+ * every C-th row of its example up to 32 examples, a block of consecutive rows above; 1 always the former;
+ * 2 always the latter).
  * Returns LNPEGN_EINVAL for an unknown key or a value out of range.  Not thread-safe against concurrent launches.
  */
 int lnpegn_set_tuning(int key, int value);

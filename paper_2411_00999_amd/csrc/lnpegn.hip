@@ -31,6 +31,7 @@ int g_chunks_plain = 0;
 int g_waves = 0;
 int g_vpt_max = 0;          // cap on 16-byte vectors per lane and array (0: automatic)
 int g_xcd = -1;        // hand neighbouring chunks to the same XCD: 0 never, 1 always, -1 automatic
+int g_blocked = -1;    // chunks of consecutive rows: 0 never, 1 always, -1 automatic
 int g_dx_cached = -1;  // dx stores write-back instead of streaming: 0 never, 1 always, -1 automatic
 int g_stagger = -1;   // rows between the sweep starts of consecutive examples (-1 = automatic)
 // one-shot profiling events around the row kernel (null = disarmed)
@@ -39,9 +40,8 @@ hipEvent_t g_ev_stop = nullptr;
 
 constexpr int kMaxChunks = 16384;
 constexpr int kCUs = 256;           // MI355X
-constexpr int kGroups = 16;         // groups of chunks in the reduction when groups are not examples
+constexpr int kGroups = 16;         // groups of chunks in the reduction that gives the batch gradients
 constexpr int64_t kSmallFinal = 32768;  // G1*D up to which one workgroup finishes the reduction
-constexpr int kMaxPeGroups = 256;   // above this many examples a chunk is a whole example
 constexpr size_t kAlign = 256;
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -63,14 +63,32 @@ struct Plan {
     // reduction
     int ntile;
     int gs, G1;       // chunks per group, groups
-    bool emit_pe;         // row kernel writes the per-example norms (a chunk is a whole example)
-    bool pe_from_groups;  // reduction kernel writes them (groups are examples)
-    // workspace layout (byte offsets)
+    bool emit_pe;     // row kernel writes the per-example norms (a chunk is a whole example)
+    int n_ex;         // examples whose norms the reduction takes from their chunks' sums (0 or B)
     // workspace layout (byte offsets); everything but `part` depends on B and D only, so that a
     // batched reduction can address any layer of the same shape
     size_t off_grp, off_part_s, off_part_big, off_part, total;
 };
 constexpr size_t kHeaderBytes = 256;
+
+// Chunks per example, given W workgroups resident at a time.  W/B of them fill one round of workgroups when B
+// divides W; when they would leave much of a round empty (B*C/W below 0.85, or a last round that is less than a
+// third full), the example is cut finer, into three rounds or more: many short workgroups even out by themselves,
+// at the price of one more flush of column sums per chunk.  Measured, bf16 D=1024, us per launch, W/B chunks ->
+// this choice: B=300 T=100 39.6 -> 33.3, B=260 T=128 44.6 -> 38.6, B=600 T=64 47.7 -> 45.5, B=513 T=64
+// 40.0 -> 37.0, B=384 T=64 30.0 -> 29.1, B=200 T=128 31.4 -> 30.2; D=2048: B=300 T=100 104.5 -> 77.9, B=600 T=64
+// 105.3 -> 91.5; D=4096: B=300 T=100 170.1 -> 153.5.  (B=700 T=48 and B=1000 T=32, whose second round is more
+// than a third full, are faster with one chunk per example: 35.8 against 36.9 and 34.1 against 35.2.)
+int64_t chunks_per_example(int64_t B, int64_t T, int64_t W)
+{
+    const int64_t c0 = W / B > 1 ? W / B : 1;
+    const int64_t n = B * c0, full = n / W, rest = n % W;   // rounds that are full, workgroups in the last one
+    const bool fits = n <= W ? 20 * n >= 17 * W
+                             : rest == 0 || full >= 3 || (full == 1 && 10 * rest >= 3 * W);
+    if (fits) return c0;
+    const int64_t c3 = (3 * W + B - 1) / B;         // three rounds
+    return (c3 <= 16 && T / c3 >= 16) ? c3 : c0;    // ... unless that leaves a chunk fewer than 16 rows
+}
 
 // `vector_ok`: the 16-byte aligned fast kernels will run (else the generic kernel does).
 Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
@@ -116,11 +134,6 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         p.max_threads = 64 * max_waves;
     }
     const int nwaves = p.fast ? p.R * p.S : 4;
-    {
-        const size_t xchg = (size_t)((10 * nwaves + 2 * p.S + 3) & ~3) * sizeof(float);
-        const size_t merge = p.fast && p.R > 1 ? (size_t)nwaves * 2 * p.vpt * E * kWave * sizeof(float) : 0;
-        p.lds_bytes = xchg + (merge > 512 ? merge : 512);
-    }
     // one full round of resident workgroups unless told otherwise
     int target = pegn ? g_chunks_pegn : g_chunks_plain;
     if (target <= 0) {
@@ -153,12 +166,16 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
     };
     if (pegn) {
         p.Tp = T;
-        int64_t c = (B > kMaxPeGroups && g_chunks_pegn <= 0) ? 1 : target / B;
+        int64_t c = g_chunks_pegn > 0 || !p.fast ? target / B : chunks_per_example(B, T, target);
         const int64_t cmax = T / rows_min > 1 ? T / rows_min : 1;
         if (c > cmax) c = cmax;
         if (c < 1) c = 1;
         p.C = (int)even_chunks(c, T);
         p.n_slots = (int64_t)B * p.C;
+        // A chunk that is a whole short example, two or more of them per CU, rows of one wave: eight rows at a
+        // time (measured, bf16 D=1024: B=512 T=64 35.8 -> 35.0 us, B=1024 T=32 35.2 -> 34.1, B=700 T=48
+        // 37.8 -> 35.7; fp32 B=512 T=64 D=1024 77.5 -> 73.9; with fewer examples than that four rows are faster).
+        if (p.fast && g_waves <= 0 && p.C == 1 && p.S == 1 && p.vpt * E > 8 && B >= 2 * kCUs && T >= 32) p.R = 8;
     } else {
         p.Tp = N;
         int64_t c = target;
@@ -167,21 +184,21 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         p.C = (int)even_chunks(c, N);
         p.n_slots = p.C;
     }
-    p.emit_pe = pegn && p.fast && p.C == 1;
-    p.pe_from_groups = pegn && !p.emit_pe;
-    if (p.pe_from_groups) {
-        p.gs = p.C;
-        p.G1 = B;
-    } else {
-        p.gs = ceil_div(p.n_slots, kGroups);
-        p.G1 = ceil_div(p.n_slots, p.gs);
+    {
+        const int nw = p.fast ? p.R * p.S : 4;
+        const size_t xchg = (size_t)((10 * nw + 2 * p.S + 3) & ~3) * sizeof(float);
+        const size_t merge = p.fast && p.R > 1 ? (size_t)nw * 2 * p.vpt * E * kWave * sizeof(float) : 0;
+        p.lds_bytes = xchg + (merge > 512 ? merge : 512);
     }
+    p.emit_pe = pegn && p.fast && p.C == 1;
+    p.n_ex = pegn && !p.emit_pe ? B : 0;
+    p.gs = ceil_div(p.n_slots, kGroups);
+    p.G1 = ceil_div(p.n_slots, p.gs);
     p.ntile = ceil_div(D, kTile);
     const size_t vec_bytes = (size_t)2 * D * sizeof(float);
-    const size_t g_max = (size_t)(B > kGroups ? B : kGroups);   // layout does not depend on the path taken
-    size_t off = kHeaderBytes;
-    p.off_grp = off;       off += align_up(g_max * vec_bytes);
-    p.off_part_s = off;    off += align_up(g_max * p.ntile * 2 * sizeof(double));
+    size_t off = kHeaderBytes;            // the layout up to `part` does not depend on the path taken
+    p.off_grp = off;       off += align_up((size_t)kGroups * vec_bytes);
+    p.off_part_s = off;    off += align_up((size_t)B * p.ntile * 2 * sizeof(double));
     p.off_part_big = off;  off += align_up((size_t)p.ntile * 2 * sizeof(double));
     p.off_part = off;      off += align_up((size_t)p.n_slots * vec_bytes);
     p.total = off;
@@ -240,7 +257,19 @@ int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, con
     RowArgs a{};
     a.x = x; a.dy = dy; a.gamma = gamma; a.mean = mean; a.rstd = rstd; a.dx = dx;
     a.part = part; a.pe_gamma_sq = pe_gamma_sq; a.pe_beta_sq = pe_beta_sq;
-    a.Tp = p.Tp; a.stagger = !pegn ? 0 : g_stagger >= 0 ? g_stagger : (5 * (int64_t)T / (4 * (int64_t)B) > 0 ? 5 * (int64_t)T / (4 * (int64_t)B) : 1); a.C = p.C; a.D = D; a.nvec = p.nvec;
+    a.Tp = p.Tp; a.C = p.C; a.D = D; a.nvec = p.nvec;
+    // The chunks of an example take every C-th row each, so that together they sweep the example as one narrow
+    // window of memory: the fastest pattern as long as the examples, i.e. the windows, are few.  With more than 32
+    // examples every chunk takes a block of consecutive rows instead: a few percent behind the best case of
+    // the other pattern but without its bad cases (measured, us per launch, every C-th row / blocks: bf16 D=2048,
+    // B*T = 32768: B=16 67.5 / 73.6, B=32 70.6 / 73.8, B=64 89.7 / 73.8; D=1024: B=64 48.9 / 37.3, B=128
+    // 41.3 / 36.0, B=256 35.2 / 36.0).  The plain backward always has one window (D=2048: 67.3 / 73.2).
+    const bool blocked = g_blocked >= 0 ? g_blocked != 0 : pegn && B > 32;
+    a.rows_per = (blocked && p.C > 1) ? ceil_div(p.Tp, p.C) : 0;
+    // Every example's sweep starts 5T/4B rows after its predecessor's; none when that is less than a row (measured
+    // with a chunk per example, bf16 D=1024, no shift / one row: B=512 T=128 76.0 / 96.3 us, B=260 T=128 44.7 / 50.9,
+    // B=1000 T=32 35.2 / 39.4, B=512 T=64 36.1 / 35.8).
+    a.stagger = g_stagger >= 0 ? (pegn ? g_stagger : 0) : (!pegn || a.rows_per > 0) ? 0 : 5 * (int64_t)T / (4 * (int64_t)B);
     // measured: grouping an example's chunks on one XCD helps wide rows (S >= 4) and is neutral otherwise
     const bool xcd = g_xcd >= 0 ? g_xcd != 0 : p.S >= 4;
     a.xcd_chunks = (xcd && p.fast && p.n_slots % 8 == 0) ? (int)(p.n_slots / 8) : 0;
@@ -249,7 +278,7 @@ int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, con
     if (defer) {
         a.defer = reinterpret_cast<DeferHeader *>(ws);
         a.hdr = DeferHeader{dgamma, dbeta, pe_gamma_sq, pe_beta_sq, pegn ? big_sq : nullptr,
-                            (int)p.n_slots, p.gs, p.G1, p.pe_from_groups ? 1 : 0, accumulate ? 1 : 0};
+                            (int)p.n_slots, p.gs, p.G1, p.n_ex, p.C, accumulate ? 1 : 0};
     }
 
     const bool saved = rstd != nullptr;
@@ -281,11 +310,10 @@ int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, con
     ra.dgamma = dgamma; ra.dbeta = dbeta;
     ra.pe_gamma_sq = pe_gamma_sq; ra.pe_beta_sq = pe_beta_sq;
     ra.big_sq = pegn ? big_sq : nullptr;
-    ra.n_slots = (int)p.n_slots; ra.gs = p.gs; ra.G1 = p.G1; ra.D = D; ra.ntile = p.ntile;
-    ra.pe_from_groups = p.pe_from_groups;
+    ra.n_slots = (int)p.n_slots; ra.gs = p.gs; ra.G1 = p.G1; ra.n_ex = p.n_ex; ra.ex_gs = p.C; ra.D = D; ra.ntile = p.ntile;
     ra.accumulate = accumulate;
-    if (launch(reduce_groups_kernel, dim3((unsigned)p.G1, (unsigned)p.ntile), dim3(kTile), 0, s, ra) != hipSuccess) return LNPEGN_EHIP;
-    const bool need_scalars = p.pe_from_groups || ra.big_sq != nullptr;
+    if (launch(reduce_groups_kernel, dim3((unsigned)(p.n_ex + p.G1), (unsigned)p.ntile), dim3(kTile), 0, s, ra) != hipSuccess) return LNPEGN_EHIP;
+    const bool need_scalars = p.n_ex > 0 || ra.big_sq != nullptr;
     if (p.G1 == 1 || (int64_t)p.G1 * D <= kSmallFinal) {
         if (p.G1 > 1 || need_scalars) {
             if (launch(reduce_final_small_kernel, dim3(1), dim3(1024), 0, s, ra) != hipSuccess) return LNPEGN_EHIP;
@@ -550,7 +578,7 @@ int lnpegn_reduce_deferred(void *const *workspaces, int n, int B, int T, int D, 
     for (int i = 0; i < n; ++i)
         if (!workspaces[i] || reinterpret_cast<uintptr_t>(workspaces[i]) % kAlign) return LNPEGN_EINVAL;
     const Plan p = make_plan(B, T, D, dt, true, true);   // the offsets used depend on B and D only
-    const int g1_max = B > kGroups ? B : kGroups;
+    const int g1_max = B + kGroups;     // an example each, then the groups
     hipStream_t s = static_cast<hipStream_t>(stream);
     for (int first = 0; first < n; first += kBatchMax) {
         BatchArgs b{};
@@ -627,6 +655,10 @@ int lnpegn_set_tuning(int key, int value)
         case 7:
             if (value > 2) return LNPEGN_EINVAL;
             g_dx_cached = value - 1;
+            return LNPEGN_OK;
+        case 8:
+            if (value > 2) return LNPEGN_EINVAL;
+            g_blocked = value - 1;
             return LNPEGN_OK;
         default: return LNPEGN_EINVAL;
     }

@@ -12,7 +12,7 @@ constexpr int kWave = 64;
 // (written by the row kernel, read by the reduction kernels).
 struct DeferHeader {
     float *dgamma, *dbeta, *pe_gamma_sq, *pe_beta_sq, *big_sq;
-    int n_slots, gs, G1, pe_from_groups, accumulate;
+    int n_slots, gs, G1, n_ex, ex_gs, accumulate;
 };
 
 // ---------------------------------------------------------------------------------------

@@ -13,37 +13,44 @@ constexpr int kTile = 256;  // columns per workgroup
 
 struct ReduceArgs {
     const float *part;     // [n_slots][2][D] column sums per chunk
-    float *grp;            // [G1][2][D] sums per group of chunks (per example when pe_from_groups)
-    double *part_s;        // [G1][ntile][2] per-group squared norms per tile (pe_from_groups)
+    float *grp;            // [G1][2][D] sums per group of chunks
+    double *part_s;        // [n_ex][ntile][2] per-example squared norms per tile
     double *part_big;      // [ntile][2] squared norms of the batch gradients per tile
     float *dgamma;         // [D]
     float *dbeta;          // [D]
-    float *pe_gamma_sq;    // [G1] (pe_from_groups)
+    float *pe_gamma_sq;    // [n_ex]
     float *pe_beta_sq;
     float *big_sq;         // [2] or null
     int n_slots;
     int gs;                // chunks per group (the last group may be short)
     int G1;                // number of groups
+    int n_ex;              // examples whose squared norms are taken from their chunks' sums here (Appendix B
+                           // steps 2, 6); 0 when there are none or the row kernel wrote them itself
+    int ex_gs;             // chunks per example: example b owns chunks [b*ex_gs, (b+1)*ex_gs)
     int D;
     int ntile;
-    int pe_from_groups;    // groups are examples: emit their squared norms (Appendix B steps 2, 6)
     int accumulate;        // dgamma, dbeta: add to what is there (gradient accumulation) instead of overwrite
 };
 
 // These kernels are a handful of dependent memory round trips long, so every level issues its
 // loads in batches of eight before it adds them (in index order: the sums are reproducible).
 
-// Level 1.  grid (G1, ntile), 256 threads.  The four waves split the group's chunks, add them
-// in chunk order, then the waves' partial sums are added in wave order.  With a single group the
-// group sums ARE the batch gradients and go straight to dgamma / dbeta.
-__device__ __forceinline__ void reduce_groups_body(const ReduceArgs &a, int g, int tile)
+// Level 1.  grid (n_ex + G1, ntile), 256 threads.  A workgroup adds the column sums of a run of consecutive
+// chunks: the four waves split the run, add in chunk order, then the waves' partial sums are added in wave order.
+// The first n_ex workgroups of a tile take one example each and leave the squares of its sums (their sums are
+// not kept); the other G1 take one group of chunks each, for the batch gradients.  With a single group the group
+// sums ARE the batch gradients and go straight to dgamma / dbeta.
+__device__ __forceinline__ void reduce_groups_body(const ReduceArgs &a, int gx, int tile)
 {
     __shared__ double wsum[4][8][kWave];   // [wave][array*4 + component][lane]
     __shared__ double slots[2][4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col0 = tile * kTile;
 
-    const int m0 = g * a.gs, m1 = min(m0 + a.gs, a.n_slots);
+    const bool example = gx < a.n_ex;
+    const int g = example ? gx : gx - a.n_ex;
+    const int run = example ? a.ex_gs : a.gs;
+    const int m0 = g * run, m1 = min(m0 + run, a.n_slots);
     const int per = (m1 - m0 + 3) / 4;
     const int w0 = min(m0 + wave * per, m1), w1 = min(w0 + per, m1);
     const int c4 = col0 + lane * 4;            // this lane's four columns
@@ -91,11 +98,19 @@ __device__ __forceinline__ void reduce_groups_body(const ReduceArgs &a, int g, i
         v0 += wsum[w][comp][src_lane];
         v1 += wsum[w][4 + comp][src_lane];
     }
+    if (example) {
+        // an example's gradient as fp32 values, their squares summed in fp64
+        const float f0 = (float)v0, f1 = (float)v1;
+        const double e0 = block_sum_f64(col < a.D ? (double)f0 * f0 : 0.0, slots[0]);
+        const double e1 = block_sum_f64(col < a.D ? (double)f1 * f1 : 0.0, slots[1]);
+        if (tid == 0) {
+            a.part_s[((int64_t)g * a.ntile + tile) * 2] = e0;
+            a.part_s[((int64_t)g * a.ntile + tile) * 2 + 1] = e1;
+        }
+        return;
+    }
     const bool single = a.G1 == 1;
-    // With a single group the sums go straight to dgamma / dbeta, on top of what they hold when
-    // accumulating; the group's OWN sums (own0, own1) are what an example's norm is taken from.
-    const float own0 = (float)v0, own1 = (float)v1;
-    if (single && a.accumulate && col < a.D) {
+    if (single && a.accumulate && col < a.D) {   // on top of what dgamma / dbeta hold
         v0 += (double)a.dgamma[col];
         if (a.dbeta) v1 += (double)a.dbeta[col];
     }
@@ -109,26 +124,13 @@ __device__ __forceinline__ void reduce_groups_body(const ReduceArgs &a, int g, i
             a.grp[((int64_t)g * 2 + 1) * a.D + col] = f1;
         }
     }
-    if (a.pe_from_groups || single) {
+    if (single) {
         // squares of the values as stored (fp32), summed in fp64
         const double q0 = block_sum_f64(col < a.D ? (double)f0 * f0 : 0.0, slots[0]);
         const double q1 = block_sum_f64(col < a.D ? (double)f1 * f1 : 0.0, slots[1]);
-        double e0 = q0, e1 = q1;
-        if (a.pe_from_groups && single && a.accumulate) {
-            // one example per micro-batch: its norm is that of this call's sums (Appendix B steps 2
-            // and 6), not of the gradient accumulated so far
-            e0 = block_sum_f64(col < a.D ? (double)own0 * own0 : 0.0, slots[0]);
-            e1 = block_sum_f64(col < a.D ? (double)own1 * own1 : 0.0, slots[1]);
-        }
         if (tid == 0) {
-            if (a.pe_from_groups) {
-                a.part_s[((int64_t)g * a.ntile + tile) * 2] = e0;
-                a.part_s[((int64_t)g * a.ntile + tile) * 2 + 1] = e1;
-            }
-            if (single) {
-                a.part_big[tile * 2] = q0;
-                a.part_big[tile * 2 + 1] = q1;
-            }
+            a.part_big[tile * 2] = q0;
+            a.part_big[tile * 2 + 1] = q1;
         }
     }
 }
@@ -165,16 +167,14 @@ __device__ __forceinline__ void sum_groups(const float *grp, int G1, int D, int 
 // Per-example and batch squared norms from their per-tile parts, tiles added in order.
 __device__ __forceinline__ void finish_scalars(const ReduceArgs &a, int tid, int nthreads)
 {
-    if (a.pe_from_groups) {
-        for (int b = tid; b < a.G1; b += nthreads) {
-            double sg = 0.0, sb = 0.0;
-            for (int t = 0; t < a.ntile; ++t) {
-                sg += a.part_s[((int64_t)b * a.ntile + t) * 2];
-                sb += a.part_s[((int64_t)b * a.ntile + t) * 2 + 1];
-            }
-            a.pe_gamma_sq[b] = (float)sg;
-            if (a.pe_beta_sq) a.pe_beta_sq[b] = (float)sb;
+    for (int b = tid; b < a.n_ex; b += nthreads) {
+        double sg = 0.0, sb = 0.0;
+        for (int t = 0; t < a.ntile; ++t) {
+            sg += a.part_s[((int64_t)b * a.ntile + t) * 2];
+            sb += a.part_s[((int64_t)b * a.ntile + t) * 2 + 1];
         }
+        a.pe_gamma_sq[b] = (float)sg;
+        if (a.pe_beta_sq) a.pe_beta_sq[b] = (float)sb;
     }
 }
 
@@ -244,17 +244,16 @@ __device__ __forceinline__ ReduceArgs batch_layer_args(const BatchArgs &b, int l
     a.part_big = reinterpret_cast<double *>(ws + b.off_part_big);
     a.dgamma = h.dgamma; a.dbeta = h.dbeta;
     a.pe_gamma_sq = h.pe_gamma_sq; a.pe_beta_sq = h.pe_beta_sq; a.big_sq = h.big_sq;
-    a.n_slots = h.n_slots; a.gs = h.gs; a.G1 = h.G1; a.D = b.D; a.ntile = b.ntile;
-    a.pe_from_groups = h.pe_from_groups;
+    a.n_slots = h.n_slots; a.gs = h.gs; a.G1 = h.G1; a.n_ex = h.n_ex; a.ex_gs = h.ex_gs; a.D = b.D; a.ntile = b.ntile;
     a.accumulate = h.accumulate;
     return a;
 }
 
-// grid (G1max, ntile, layers): workgroups beyond a layer's own group count leave at once
+// grid (most examples + groups of any layer, ntile, layers): workgroups beyond a layer's own count leave at once
 __global__ __launch_bounds__(kTile) void reduce_groups_batch_kernel(BatchArgs b)
 {
     const ReduceArgs a = batch_layer_args(b, blockIdx.z);
-    if ((int)blockIdx.x >= a.G1) return;
+    if ((int)blockIdx.x >= a.n_ex + a.G1) return;
     reduce_groups_body(a, blockIdx.x, blockIdx.y);
 }
 
@@ -262,7 +261,7 @@ __global__ __launch_bounds__(kTile) void reduce_groups_batch_kernel(BatchArgs b)
 __global__ __launch_bounds__(1024) void reduce_final_batch_kernel(BatchArgs b)
 {
     const ReduceArgs a = batch_layer_args(b, blockIdx.x);
-    if (a.G1 == 1 && !a.pe_from_groups && !a.big_sq) return;
+    if (a.G1 == 1 && a.n_ex == 0 && !a.big_sq) return;
     reduce_final_body(a);
 }
 

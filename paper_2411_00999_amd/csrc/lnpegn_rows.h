@@ -35,6 +35,8 @@ struct RowArgs {
     int64_t Tp;          // rows per partition example
     int64_t stagger;     // example b starts its sweep at row (b*stagger) mod Tp of itself
     int C;               // chunks per partition example
+    int rows_per;        // > 0: chunk j owns the rows [j*rows_per, (j+1)*rows_per) of its example; 0: the rows
+                         //      j, j + C, j + 2C, ... (the chunks of an example sweep it side by side)
     int D;
     int nvec;            // D / elements-per-vector
     int S;               // waves per row
@@ -141,13 +143,17 @@ __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
     const int g = wave / S, ws = wave - g * S;
     const int chunk = a.xcd_chunks > 0 ? (blockIdx.x & 7) * a.xcd_chunks + (blockIdx.x >> 3) : blockIdx.x;
     const int b = chunk / a.C, j = chunk - b * a.C;
-    // Chunk j of example b owns rows b*Tp + j + m*C.  Examples sit a power of two apart in
-    // memory; starting each sweep at a different row (wrapping around) keeps the concurrent
-    // sweeps on different HBM channels.
+    // Chunk j of example b owns rows b*Tp + j + m*C, or a block of consecutive rows.  Examples sit
+    // a power of two apart in memory; starting each sweep at a different row (wrapping around)
+    // keeps the concurrent sweeps on different HBM channels.
     const int Tp = (int)a.Tp;
     const int row_base = b * Tp;
     const int t_rot = (int)(((int64_t)b * a.stagger) % a.Tp);
-    const int n_rows = (Tp - j + a.C - 1) / a.C;   // rows of this chunk
+    const bool blocked = a.rows_per > 0;
+    const int row_first = blocked ? j * a.rows_per : j;
+    const int row_step = blocked ? 1 : a.C;
+    const int n_rows = blocked ? max(0, min(a.rows_per, Tp - row_first))
+                               : (Tp - j + a.C - 1) / a.C;   // rows of this chunk
     const int n_full = n_rows / R;                 // iterations in which every row group has a row
     const bool has_tail = n_rows - n_full * R > 0;
     if (a.defer && blockIdx.x == 0 && threadIdx.x == 0) *a.defer = a.hdr;
@@ -167,7 +173,7 @@ __device__ __forceinline__ void ln_bwd_rows_body(const RowArgs &a)
     char *dxbase = static_cast<char *>(a.dx);
 
     auto row_of = [&](int m) {   // m-th row of the chunk -> global row index (wave-uniform)
-        int u = j + m * a.C + t_rot;
+        int u = row_first + m * row_step + t_rot;
         u = u >= Tp ? u - Tp : u;
         return __builtin_amdgcn_readfirstlane(row_base + u);
     };

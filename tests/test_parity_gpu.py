@@ -189,6 +189,25 @@ def test_misaligned_pointers_take_the_generic_kernel():
     pu.compare_with_oracle(inp, res, ref)
 
 
+@pytest.mark.parametrize("B,T,D,dtype", [
+    (40, 50, 1024, "bf16"),     # six chunks of consecutive rows per example, the last one short
+    (33, 17, 256, "f32"),       # two chunks of 9 and 8 rows
+    (200, 130, 768, "bf16"),    # examples cut finer than one round of workgroups: eight chunks of 17, 11 in the last
+    (130, 48, 2048, "bf16"),    # too short to cut: a chunk is a whole example, rows of two waves
+    (512, 32, 1024, "bf16"),    # a chunk is a whole example, eight rows at a time
+    (520, 33, 512, "f32"),      # the same with four rows at a time and a ragged tail
+])
+def test_many_short_examples(B, T, D, dtype):
+    """More examples than the row kernel has workgroups for: the chunk layouts of that regime."""
+    inp = workloads.make_inputs(4 if dtype == "bf16" else 1, B=B, T=T, D=D, dtype=dtype)
+    ref = _oracle(inp)
+    for saved in (False, True):
+        res = pu.run_gpu(inp, saved_stats=saved)
+        pu.compare_with_oracle(inp, res, ref)
+    got, want = _gns_both(res, ref, B)
+    _check_gns(got, want, B)
+
+
 def test_bitwise_reproducible():
     inp = workloads.make_inputs(3, B=4, T=64, D=2048)
     a = pu.run_gpu(inp)
@@ -204,19 +223,22 @@ def test_chunk_count_only_changes_summation_order():
     ref = _oracle(inp)
     try:
         for chunks in (4, 16, 64, 4096):
-            binding.set_tuning(0, chunks)
-            binding.set_tuning(1, chunks)
-            res = pu.run_gpu(inp)
-            pu.compare_with_oracle(inp, res, ref)
-            plain = pu.run_gpu(inp, pegn=False)
-            pu.compare_with_oracle(inp, plain, ref, pegn=False)
+            for rows in (1, 2):                         # every C-th row of the example, or a block of rows
+                binding.set_tuning(0, chunks)
+                binding.set_tuning(1, chunks)
+                binding.set_tuning(8, rows)
+                res = pu.run_gpu(inp)
+                pu.compare_with_oracle(inp, res, ref)
+                plain = pu.run_gpu(inp, pegn=False)
+                pu.compare_with_oracle(inp, plain, ref, pegn=False)
     finally:
         binding.set_tuning(0, 0)
         binding.set_tuning(1, 0)
+        binding.set_tuning(8, 0)
 
 
 @pytest.mark.parametrize("cfg,B,T,D", [(3, 4, 64, 2048), (2, 3, 37, 768), (4, 300, 4, 1024), (5, 2, 20, 8192),
-                                      (1, 2, 9, 257)])
+                                      (1, 2, 9, 257), (4, 40, 50, 1024)])
 def test_deferred_reduction_matches_immediate_calls_bitwise(cfg, B, T, D):
     """Several layers of one shape: row passes first, ONE batched reduction afterwards."""
     import torch
