@@ -124,8 +124,13 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         // (rows that one wave covers stay at four row groups: six made the short kernels of B=8 T=1024 D=768 and
         // B=512 T=64 D=1024 3-10 % slower)
         // (fp32 rows of four waves: two row groups, measured with the per-example sweeps, 288.7 -> 273.8 us)
+        // (rows of two waves with lanes left over, D=1280, 1536 or 1600 in bf16, have fewer bytes in flight per
+        // wave and take four row groups: D=1280 64.5 -> 52.0 us, D=1536 65.0 -> 55.3; rows of three waves take two:
+        // bf16 D=3072 147.7 -> 111.5 per-example and 107.6 -> 100.3 plain, fp32 D=3072 216.3 -> 205.1)
+        const bool full = p.nvec == 64 * p.S * p.vpt;
         int R = g_waves > 0 ? g_waves / p.S
-                : (elems > 8 && p.S == 2) ? 3
+                : (elems > 8 && p.S == 2) ? (full ? 3 : 4)
+                : p.S == 3 ? 2
                 : (pegn && E == 4 && p.S == 4 && p.vpt >= 3) ? 2
                 : (p.S >= 4 ? 1 : 4 / p.S);
         if (R < 1) R = 1;
@@ -146,13 +151,14 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         //   rows of eight waves (D=8192: 279.6 / 268.0)                      two rounds of workgroups: the second
         //       round starts where the first finishes, which evens out the CUs' unequal memory throughput
         // ... as long as a chunk keeps a hundred rows or so (short launches want the parallelism more).
-        if (pegn && p.fast && p.S >= 2 && p.S <= 4 && waves_per_simd == 2 && per_cu > 1 && !(E == 4 && p.vpt >= 3) &&
+        if (pegn && p.fast && p.S == 4 && waves_per_simd == 2 && per_cu > 1 && !(E == 4 && p.vpt >= 3) &&
             N / ((int64_t)kCUs * (per_cu / 2)) >= 96)
             per_cu /= 2;
         //   fp32 rows of two and four waves (lanes of four vectors; D=2048: 140.5 / 137.9, D=4096 with two row
         //       groups: 290.8 / 273.8) also take two rounds
         const bool wide_f32 = E == 4 && p.vpt >= 3 && p.S >= 2;
-        if (pegn && p.fast && (p.S == 8 || wide_f32) && N / ((int64_t)kCUs * 2) >= 32) per_cu = 2;
+        //   rows of six and seven waves likewise (bf16 D=6144: 224.6 / 216.9)
+        if (pegn && p.fast && (p.S >= 6 || wide_f32) && N / ((int64_t)kCUs * 2) >= 32) per_cu = 2;
         target = kCUs * per_cu;
     }
     const int rows_min = p.fast ? 2 * p.R : 1;       // keep every row group busy
@@ -167,6 +173,18 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
     if (pegn) {
         p.Tp = T;
         int64_t c = g_chunks_pegn > 0 || !p.fast ? target / B : chunks_per_example(B, T, target);
+        // Long launches over fp32 rows of 16 elements per lane: several rounds of shorter workgroups, which even
+        // out the CUs' unequal progress (measured, us per launch, one round -> this: B=16 T=2048 D=2048
+        // 138.3 -> 134.3, B=8 T=4096 D=2048 137.2 -> 134.2, B=16 T=4096 D=2048 280.9 -> 265.9, B=16 T=2048 D=1024
+        // 75.2 -> 72.0, B=16 T=2048 D=4096 279.6 -> 265.1 with two rounds and 283.3 with four; half as many rows,
+        // B=16 T=1024 D=2048, are faster in one round, 72.8 against 74.0, and so are bf16 rows: D=2048 68.8 -> 71.2
+        // with two rounds).
+        // (fp32 D=1280 96.4 -> 93.1, D=1536 112.3 -> 109.2)
+        if (g_chunks_pegn <= 0 && p.fast && E == 4 && p.vpt >= 3 && p.S <= 4 && N >= 32768 && B * c <= target) {
+            int64_t rounds = p.S == 4 ? 2 : 4;
+            while (rounds > 1 && T / (c * rounds) < 16) rounds /= 2;
+            c *= rounds;
+        }
         const int64_t cmax = T / rows_min > 1 ? T / rows_min : 1;
         if (c > cmax) c = cmax;
         if (c < 1) c = 1;
