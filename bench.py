@@ -821,10 +821,13 @@ def main():
         layers.clear()
         sh.clear()
         torch.cuda.empty_cache()
-        workload_legs = per_config_legs()
+        f32_leg = None
         if cfg == 3 and not args.config_dtype:       # the headline shape with fp32 storage, one layer
-            workload_legs["workload3_f32"] = config_leg(3, 100, log, dtype="f32", stats_mode=args.stats)
+            f32_leg = config_leg(3, 100, log, dtype="f32", stats_mode=args.stats)
             torch.cuda.empty_cache()
+        workload_legs = per_config_legs()
+        if f32_leg is not None:
+            workload_legs["workload3_f32"] = f32_leg
     if not (args.no_linear or args.only_fused):
         layers.clear()
         sh.clear()
