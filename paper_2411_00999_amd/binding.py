@@ -16,7 +16,7 @@ from . import build as _build
 F32, BF16 = 0, 1
 STATUS = {0: "LNPEGN_OK", 1: "LNPEGN_EINVAL", 2: "LNPEGN_EUNSUPPORTED", 3: "LNPEGN_EWORKSPACE",
           4: "LNPEGN_EHIP"}
-STATIC_SCRATCH_BYTES = 32 << 20     # LNPEGN_STATIC_SCRATCH_BYTES of the header
+STATIC_SCRATCH_BYTES = 64 << 20     # LNPEGN_STATIC_SCRATCH_BYTES of the header
 EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "lnpegn_last_hip_error", "ln_fwd_stats", "ln_bwd",
            "ln_bwd_pegn", "ln_bwd_pegn_static", "gns_estimate", "lnpegn_set_tuning", "lnpegn_set_profile_events",
            "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred",

@@ -518,7 +518,8 @@ int ln_bwd_pegn_static(const void *x, const void *dy, const void *gamma, const f
     // validate the shape against the fixed scratch before touching the device
     if (!shape_ok(B, T, D) || !(eps >= 0.f)) return LNPEGN_EINVAL;
     if (!dtype_ok(dt) || !dtype_ok(gamma_dt)) return LNPEGN_EUNSUPPORTED;
-    if (lnpegn_workspace_bytes(B, T, D, dt) > kStaticScratchBytes) return LNPEGN_EWORKSPACE;
+    const bool vector_ok = aligned16(x) && aligned16(dy) && aligned16(dx) && aligned16(gamma);
+    if (make_plan(B, T, D, dt, true, vector_ok).total > kStaticScratchBytes) return LNPEGN_EWORKSPACE;
     void *ws = nullptr;
     const hipError_t e = static_scratch(&ws);
     if (e != hipSuccess) {

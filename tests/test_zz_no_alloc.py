@@ -77,6 +77,25 @@ def test_full_size_benchmark_shapes_fit_and_match():
             assert torch.equal(g, w)
 
 
+def test_largest_benchmark_shape_fits_the_fixed_scratch():
+    """B=8 T=4096 D=8192 bf16 needs 33 MiB of chunk sums; inputs drawn on the device, results compared bit for bit
+    with the workspace call (the oracle comparison of this shape is test_full_size_workloads)."""
+    import torch
+    from paper_2411_00999_amd import binding
+    B, T, D = 8, 4096, 8192
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    x = torch.randn((B, T, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    dy = torch.randn((B, T, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    gamma = (1.0 + 0.1 * torch.randn(D, generator=gen, device="cuda")).to(torch.bfloat16)
+    want = binding.ln_bwd_pegn(x, dy, gamma, 1e-5)
+    out = _buffers(B, T, D, "bf16")
+    got = binding.ln_bwd_pegn_static(x, dy, gamma, 1e-5, **out)
+    torch.cuda.synchronize()
+    for name, g, w in zip(("dx", "dgamma", "dbeta", "pe_gamma_sq", "pe_beta_sq", "big_sq"), got, want):
+        assert torch.equal(g, w), name
+    assert torch.isfinite(got[3]).all() and float(got[5][0]) > 0.0
+
+
 def test_shape_beyond_the_fixed_scratch_is_refused():
     """Host validation only: nothing is launched, the fake pointers are never dereferenced."""
     import ctypes
