@@ -272,8 +272,8 @@ ROTATE_BYTES = 512 << 20     # bytes touched between two uses of a buffer set in
 # HBM bytes per row-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (fused kernel), per workload and
 # storage type; profiles/ln_bwd_rows_workloads_1_2_4_5_rocprofv3.md has the commands and the copy-kernel scale.
 # Re-measure after any change to the row kernel or its launch shape.  A workload without a measurement reports null.
-MEASURED_ROW_TRAFFIC = {(5, "bf16"): 1_644_470_000, (4, "bf16"): 205_780_000, (2, "bf16"): 41_110_000,
-                        (1, "f32"): 1_820_000, (3, "f32"): 813_950_000}
+MEASURED_ROW_TRAFFIC = {(5, "bf16"): 1_644_480_000, (4, "bf16"): 205_780_000, (2, "bf16"): 41_120_000,
+                        (1, "f32"): 1_820_000, (3, "f32"): 839_100_000}
 
 
 class ConfigBuffers:

@@ -330,7 +330,7 @@ int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, con
     ra.big_sq = pegn ? big_sq : nullptr;
     ra.n_slots = (int)p.n_slots; ra.gs = p.gs; ra.G1 = p.G1; ra.n_ex = p.n_ex; ra.ex_gs = p.C; ra.D = D; ra.ntile = p.ntile;
     ra.accumulate = accumulate;
-    if (launch(reduce_groups_kernel, dim3((unsigned)(p.n_ex + p.G1), (unsigned)p.ntile), dim3(kTile), 0, s, ra) != hipSuccess) return LNPEGN_EHIP;
+    if (launch(reduce_groups_kernel, dim3((unsigned)reduce_groups_count(ra), (unsigned)p.ntile), dim3(kTile), 0, s, ra) != hipSuccess) return LNPEGN_EHIP;
     const bool need_scalars = p.n_ex > 0 || ra.big_sq != nullptr;
     if (p.G1 == 1 || (int64_t)p.G1 * D <= kSmallFinal) {
         if (p.G1 > 1 || need_scalars) {

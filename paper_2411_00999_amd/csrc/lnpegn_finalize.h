@@ -32,10 +32,18 @@ struct ReduceArgs {
     int accumulate;        // dgamma, dbeta: add to what is there (gradient accumulation) instead of overwrite
 };
 
+// An example's chunks are also one of the groups (as many groups as examples, of as many chunks): one workgroup
+// then serves as both, and level 1 takes n_ex workgroups per tile instead of n_ex + G1.
+__host__ __device__ inline bool examples_are_groups(const ReduceArgs &a) { return a.n_ex == a.G1 && a.ex_gs == a.gs; }
+__host__ __device__ inline int reduce_groups_count(const ReduceArgs &a)
+{
+    return examples_are_groups(a) ? a.n_ex : a.n_ex + a.G1;
+}
+
 // These kernels are a handful of dependent memory round trips long, so every level issues its
 // loads in batches of eight before it adds them (in index order: the sums are reproducible).
 
-// Level 1.  grid (n_ex + G1, ntile), 256 threads.  A workgroup adds the column sums of a run of consecutive
+// Level 1.  grid (reduce_groups_count, ntile), 256 threads.  A workgroup adds the column sums of a run of consecutive
 // chunks: the four waves split the run, add in chunk order, then the waves' partial sums are added in wave order.
 // The first n_ex workgroups of a tile take one example each and leave the squares of its sums (their sums are
 // not kept); the other G1 take one group of chunks each, for the batch gradients.  With a single group the group
@@ -107,7 +115,7 @@ __device__ __forceinline__ void reduce_groups_body(const ReduceArgs &a, int gx, 
             a.part_s[((int64_t)g * a.ntile + tile) * 2] = e0;
             a.part_s[((int64_t)g * a.ntile + tile) * 2 + 1] = e1;
         }
-        return;
+        if (!examples_are_groups(a)) return;
     }
     const bool single = a.G1 == 1;
     if (single && a.accumulate && col < a.D) {   // on top of what dgamma / dbeta hold
@@ -253,7 +261,7 @@ __device__ __forceinline__ ReduceArgs batch_layer_args(const BatchArgs &b, int l
 __global__ __launch_bounds__(kTile) void reduce_groups_batch_kernel(BatchArgs b)
 {
     const ReduceArgs a = batch_layer_args(b, blockIdx.z);
-    if ((int)blockIdx.x >= a.n_ex + a.G1) return;
+    if ((int)blockIdx.x >= reduce_groups_count(a)) return;
     reduce_groups_body(a, blockIdx.x, blockIdx.y);
 }
 
