@@ -305,7 +305,7 @@ class ConfigBuffers:
 
 
 def config_leg(cfg, iters, log, sets=None, dtype=None, stats_mode="recompute", buffers=None):
-    """One workload of the benchmark's configs, one layer: ln_bwd_pegn and the plain ln_bwd interleaved on one
+    """One of the benchmark workloads, one layer: ln_bwd_pegn and the plain ln_bwd interleaved on one
     stream, every call with HIP events on its row kernel's own dispatch and a second pair around the whole call
     (row kernel + reduction launches).  Cache-cold: the calls rotate over enough buffer sets that at least
     ROTATE_BYTES are touched before a set is used again (the 256 MB memory-side cache cannot hold them); the

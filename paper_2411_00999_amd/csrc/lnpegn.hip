@@ -161,7 +161,9 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         if (pegn && p.fast && (p.S >= 6 || wide_f32) && N / ((int64_t)kCUs * 2) >= 32) per_cu = 2;
         target = kCUs * per_cu;
     }
-    const int rows_min = p.fast ? 2 * p.R : 1;       // keep every row group busy
+    // rows per chunk at least: two per row group, and four in all -- a chunk ends with a write of its 2*D column
+    // sums, which is as many bytes as four bf16 rows carry
+    const int rows_min = p.fast ? (2 * p.R > 4 ? 2 * p.R : 4) : 4;
     const int R = p.fast ? p.R : 1;
     // Prefer a chunk count that gives every chunk the same number of rows, a multiple of R: no
     // partial last iteration.  Searched downwards, never below 3/4 of the first choice.

@@ -41,6 +41,21 @@ def test_workspace_bytes_is_a_pure_host_function():
     assert lib.lnpegn_workspace_bytes(16, 2048, 2048, 1) < 0.1 * 3 * 16 * 2048 * 2048 * 2
 
 
+def test_workspace_stays_a_fraction_of_the_streamed_bytes():
+    """A chunk ends with a write of 2*D fp32 column sums, so a chunk must keep a few rows: whatever the launch
+    heuristics choose, the workspace of a launch that streams 32 MiB or more in examples of 64 rows or more stays
+    below 0.4 of the bytes streamed (the worst cases are a handful of very wide rows per chunk)."""
+    lib = binding.load()
+    for dt, esz in ((binding.BF16, 2), (binding.F32, 4)):
+        for B in (1, 2, 3, 8, 16, 33, 64, 100, 128, 200, 260, 300, 384, 512, 513, 600, 1000, 4096):
+            for T in (64, 100, 128, 512, 2048):
+                for D in (64, 256, 768, 1024, 1600, 2048, 4096, 8192, 12288, 1001):
+                    streamed = 3 * B * T * D * esz
+                    if streamed >= (32 << 20):
+                        ws = lib.lnpegn_workspace_bytes(B, T, D, dt)
+                        assert 0 < ws <= 0.4 * streamed, (B, T, D, dt, ws, streamed)
+
+
 def test_status_strings():
     lib = binding.load()
     seen = {lib.lnpegn_status_string(i) for i in range(5)}
