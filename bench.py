@@ -651,12 +651,25 @@ def main():
             binding.reduce_deferred(all_ws, B, T, D, sh["dt_code"])
             binding.gns_estimate(sh["pe_all"], sh["big_all"], float(B), out=sh["gns"])
 
-        t_fb = timed(fwd_bwd_step, 1, max(2, args.steps // 2))
+        def fwd_bwd_plain_step():                # the same without the per-example norms
+            for L in layers:
+                binding.ln_fwd(L["x"], L["gamma"], beta, eps, y=y_buf, mean=st_mean, rstd=st_rstd)
+                binding.ln_bwd_ex(L["x"], L["dy"], L["gamma"], eps, binding.ACCUMULATE | binding.DEFER, L["dgamma"],
+                                  L["dbeta"], mean=st_mean, rstd=st_rstd, dx=L["dx"], workspace=L["ws"])
+            binding.reduce_deferred(all_ws, B, T, D, sh["dt_code"])
+
+        n_fb = max(2, args.steps // 2)
+        t_fb = timed(fwd_bwd_step, 1, n_fb)
+        t_fb_plain = timed(fwd_bwd_plain_step, 1, n_fb)
         fb_bytes = (5 * N * D * esz + 16 * N) * n_layers      # fwd: read x, write y, 8N stats; bwd: 3ND + 8N
         fwd_bwd = {"ms_per_step": round(t_fb * 1e3, 4), "GBps": round(fb_bytes / t_fb / 1e9, 2),
                    "algorithmic_bytes_per_step": fb_bytes,
-                   "what": "ln_fwd + ln_bwd_ex(per-example, accumulate, deferred) per layer, saved statistics"}
-        log(f"fwd+bwd with accumulation: {t_fb * 1e3:.3f} ms/step  {fb_bytes / t_fb / 1e9:.1f} GB/s")
+                   "plain_ms_per_step": round(t_fb_plain * 1e3, 4),
+                   "overhead_vs_plain_pct": round((t_fb / t_fb_plain - 1.0) * 100, 2),
+                   "what": "ln_fwd + ln_bwd_ex(per-example, accumulate, deferred) per layer, saved statistics; plain: "
+                           "the same without the per-example norms"}
+        log(f"fwd+bwd with accumulation: {t_fb * 1e3:.3f} ms/step  {fb_bytes / t_fb / 1e9:.1f} GB/s "
+            f"(without the per-example norms {t_fb_plain * 1e3:.3f} ms/step)")
         for L in layers:                 # accumulation left sums of several steps behind: start clean
             L["dgamma"].zero_()
             L["dbeta"].zero_()
