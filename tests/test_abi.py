@@ -126,6 +126,9 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert lib.lnpegn_set_tuning(0, -1) == EINVAL
     assert lib.lnpegn_set_tuning(0, 1 << 30) == EINVAL
     assert lib.lnpegn_set_tuning(2, 17) == EINVAL
+    assert lib.lnpegn_set_tuning(7, 3) == EINVAL
+    assert lib.lnpegn_set_tuning(8, 3) == EINVAL
+    assert lib.lnpegn_set_tuning(8, 2) == 0 and lib.lnpegn_set_tuning(8, 0) == 0
     assert lib.lnpegn_set_tuning(0, 0) == 0
 
 
