@@ -326,6 +326,24 @@ int embedding_pegn(const void *ids, int ids_are_int64, const void *g, float *w, 
 int lnpegn_set_tuning(int key, int value);
 
 /*
+ * Benchmarking and testing aid, host only (touches no device): the launch plan that ln_bwd (per_example = 0) or
+ * ln_bwd_pegn (per_example = 1) would use for this shape under the tuning in force, with 16-byte aligned pointers
+ * (aligned = 1: the vector kernels where the row width allows) or without (aligned = 0: the generic kernel).
+ * Writes min(n_out, LNPEGN_PLAN_FIELDS) values to the HOST array out, in this order:
+ *    0 vector kernel (1) or generic kernel (0)      1 waves per row                2 row groups per workgroup
+ *    3 16-byte vectors per lane and array           4 chunks per example (of the whole tensor for ln_bwd)
+ *    5 chunks in all = workgroups of the row kernel 6 rows of a chunk when they are consecutive, else 0 (every
+ *      C-th row)                                    7 rows between the sweep starts of consecutive examples
+ *    8 chunks per XCD when an example's chunks are kept on one XCD, else 0
+ *    9 bytes of LDS per workgroup                  10 the row kernel finishes the per-example norms itself (1/0)
+ *   11 examples whose norms the reduction finishes 12 groups of chunks in the reduction   13 chunks per group
+ *   14 workspace bytes of this plan                15 rows per example (B*T for ln_bwd)
+ * Returns LNPEGN_EINVAL for an invalid shape or a null out, LNPEGN_EUNSUPPORTED for an unknown dtype.
+ */
+#define LNPEGN_PLAN_FIELDS 16
+int lnpegn_plan_query(int B, int T, int D, lnpegn_dtype dt, int per_example, int aligned, int64_t *out, int n_out);
+
+/*
  * Benchmarking aid, one-shot.  The next ln_bwd or ln_bwd_pegn call attaches the two hipEvent_t
  * to the dispatch of its row-streaming kernel (start of execution, end of execution), so that
  * hipEventElapsedTime(start, stop) is that kernel's own duration; then it forgets both.  The

@@ -18,8 +18,8 @@ STATUS = {0: "LNPEGN_OK", 1: "LNPEGN_EINVAL", 2: "LNPEGN_EUNSUPPORTED", 3: "LNPE
           4: "LNPEGN_EHIP"}
 STATIC_SCRATCH_BYTES = 64 << 20     # LNPEGN_STATIC_SCRATCH_BYTES of the header
 EXPORTS = ("lnpegn_workspace_bytes", "lnpegn_status_string", "lnpegn_last_hip_error", "ln_fwd_stats", "ln_bwd",
-           "ln_bwd_pegn", "ln_bwd_pegn_static", "gns_estimate", "lnpegn_set_tuning", "lnpegn_set_profile_events",
-           "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred",
+           "ln_bwd_pegn", "ln_bwd_pegn_static", "gns_estimate", "lnpegn_set_tuning", "lnpegn_plan_query",
+           "lnpegn_set_profile_events", "lnpegn_stream_probe", "ln_bwd_deferred", "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred",
            "ln_fwd", "ln_bwd_ex", "rms_fwd", "rms_bwd_ex",
            "gns_ema_update", "gns_offline", "gns_linear_accum_steps",
            "linear_pegn_workspace_bytes", "linear_pegn", "embedding_pegn_workspace_bytes", "embedding_pegn",
@@ -86,9 +86,11 @@ def load() -> ctypes.CDLL:
     lib.rms_bwd_ex.argtypes = [vp, vp, vp, fp, vp, fp, fp, fp, i, i, i, i, i, f, vp, sz, ctypes.c_uint, vp]
     lib.gns_estimate.argtypes = [fp, fp, i, i, f, fp, vp]
     lib.lnpegn_set_tuning.argtypes = [i, i]
+    lib.lnpegn_plan_query.argtypes = [i, i, i, i, i, i, ctypes.POINTER(ctypes.c_int64), i]
     lib.lnpegn_set_profile_events.argtypes = [vp, vp]
     lib.lnpegn_stream_probe.argtypes = [vp, vp, vp, sz, i, vp]
     for name in ("ln_fwd_stats", "ln_bwd", "ln_bwd_pegn", "ln_bwd_pegn_static", "gns_estimate", "lnpegn_set_tuning",
+                 "lnpegn_plan_query",
                  "lnpegn_set_profile_events", "lnpegn_stream_probe", "ln_bwd_deferred",
                  "ln_bwd_pegn_deferred", "lnpegn_reduce_deferred", "ln_fwd", "ln_bwd_ex",
                  "rms_fwd", "rms_bwd_ex", "gns_ema_update", "gns_offline", "gns_linear_accum_steps",
@@ -273,6 +275,20 @@ def set_tuning(key: int, value: int) -> None:
     rc = load().lnpegn_set_tuning(key, value)
     if rc:
         raise LnpegnError("lnpegn_set_tuning", rc)
+
+
+PLAN_FIELDS = ("vector_kernel", "waves_per_row", "row_groups", "vectors_per_lane", "chunks_per_example", "chunks",
+               "rows_per_block", "stagger", "chunks_per_xcd", "lds_bytes", "row_kernel_emits_norms", "examples_in_reduction",
+               "groups", "chunks_per_group", "workspace_bytes", "rows_per_example")
+
+
+def plan_query(B: int, T: int, D: int, dt: int, per_example: bool = True, aligned: bool = True) -> dict:
+    """The launch plan of ln_bwd_pegn (or ln_bwd) for a shape, by field name (host only, no device needed)."""
+    out = (ctypes.c_int64 * len(PLAN_FIELDS))()
+    rc = load().lnpegn_plan_query(B, T, D, dt, 1 if per_example else 0, 1 if aligned else 0, out, len(PLAN_FIELDS))
+    if rc:
+        raise LnpegnError("lnpegn_plan_query", rc)
+    return dict(zip(PLAN_FIELDS, (int(v) for v in out)))
 
 
 def set_profile_events(start_event, stop_event) -> None:

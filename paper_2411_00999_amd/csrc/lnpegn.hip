@@ -59,6 +59,9 @@ struct Plan {
     int64_t Tp;       // rows per partition example
     int C;            // chunks per partition example
     int64_t n_slots;  // chunks in all
+    int rows_per;     // > 0: a chunk is a block of that many consecutive rows; 0: every C-th row of its example
+    int64_t stagger;  // rows between the sweep starts of consecutive examples
+    int xcd_chunks;   // > 0: chunks per XCD (an example's chunks share an L2); 0: chunks in launch order
     size_t lds_bytes;
     // reduction
     int ntile;
@@ -204,6 +207,21 @@ Plan make_plan(int B, int T, int D, lnpegn_dtype dt, bool pegn, bool vector_ok)
         p.C = (int)even_chunks(c, N);
         p.n_slots = p.C;
     }
+    // The chunks of an example take every C-th row each, so that together they sweep the example as one narrow
+    // window of memory: the fastest pattern as long as the examples, i.e. the windows, are few.  With more than 32
+    // examples every chunk takes a block of consecutive rows instead: a few percent behind the best case of
+    // the other pattern but without its bad cases (measured, us per launch, every C-th row / blocks: bf16 D=2048,
+    // B*T = 32768: B=16 67.5 / 73.6, B=32 70.6 / 73.8, B=64 89.7 / 73.8; D=1024: B=64 48.9 / 37.3, B=128
+    // 41.3 / 36.0, B=256 35.2 / 36.0).  The plain backward always has one window (D=2048: 67.3 / 73.2).
+    const bool blocked = g_blocked >= 0 ? g_blocked != 0 : pegn && B > 32;
+    p.rows_per = (blocked && p.C > 1) ? ceil_div(p.Tp, p.C) : 0;
+    // Every example's sweep starts 5T/4B rows after its predecessor's; none when that is less than a row (measured
+    // with a chunk per example, bf16 D=1024, no shift / one row: B=512 T=128 76.0 / 96.3 us, B=260 T=128 44.7 / 50.9,
+    // B=1000 T=32 35.2 / 39.4, B=512 T=64 36.1 / 35.8).
+    p.stagger = g_stagger >= 0 ? (pegn ? g_stagger : 0) : (!pegn || p.rows_per > 0) ? 0 : 5 * (int64_t)T / (4 * (int64_t)B);
+    // measured: grouping an example's chunks on one XCD helps wide rows (S >= 4) and is neutral otherwise
+    const bool xcd = g_xcd >= 0 ? g_xcd != 0 : p.S >= 4;
+    p.xcd_chunks = (xcd && p.fast && p.n_slots % 8 == 0 && p.n_slots / 8 <= INT32_MAX) ? (int)(p.n_slots / 8) : 0;
     {
         const int nw = p.fast ? p.R * p.S : 4;
         const size_t xchg = (size_t)((10 * nw + 2 * p.S + 3) & ~3) * sizeof(float);
@@ -278,21 +296,7 @@ int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, con
     a.x = x; a.dy = dy; a.gamma = gamma; a.mean = mean; a.rstd = rstd; a.dx = dx;
     a.part = part; a.pe_gamma_sq = pe_gamma_sq; a.pe_beta_sq = pe_beta_sq;
     a.Tp = p.Tp; a.C = p.C; a.D = D; a.nvec = p.nvec;
-    // The chunks of an example take every C-th row each, so that together they sweep the example as one narrow
-    // window of memory: the fastest pattern as long as the examples, i.e. the windows, are few.  With more than 32
-    // examples every chunk takes a block of consecutive rows instead: a few percent behind the best case of
-    // the other pattern but without its bad cases (measured, us per launch, every C-th row / blocks: bf16 D=2048,
-    // B*T = 32768: B=16 67.5 / 73.6, B=32 70.6 / 73.8, B=64 89.7 / 73.8; D=1024: B=64 48.9 / 37.3, B=128
-    // 41.3 / 36.0, B=256 35.2 / 36.0).  The plain backward always has one window (D=2048: 67.3 / 73.2).
-    const bool blocked = g_blocked >= 0 ? g_blocked != 0 : pegn && B > 32;
-    a.rows_per = (blocked && p.C > 1) ? ceil_div(p.Tp, p.C) : 0;
-    // Every example's sweep starts 5T/4B rows after its predecessor's; none when that is less than a row (measured
-    // with a chunk per example, bf16 D=1024, no shift / one row: B=512 T=128 76.0 / 96.3 us, B=260 T=128 44.7 / 50.9,
-    // B=1000 T=32 35.2 / 39.4, B=512 T=64 36.1 / 35.8).
-    a.stagger = g_stagger >= 0 ? (pegn ? g_stagger : 0) : (!pegn || a.rows_per > 0) ? 0 : 5 * (int64_t)T / (4 * (int64_t)B);
-    // measured: grouping an example's chunks on one XCD helps wide rows (S >= 4) and is neutral otherwise
-    const bool xcd = g_xcd >= 0 ? g_xcd != 0 : p.S >= 4;
-    a.xcd_chunks = (xcd && p.fast && p.n_slots % 8 == 0) ? (int)(p.n_slots / 8) : 0;
+    a.rows_per = p.rows_per; a.stagger = p.stagger; a.xcd_chunks = p.xcd_chunks;
     a.S = p.S; a.gamma_is_f32 = gamma_dt == LNPEGN_F32; a.emit_pe = p.emit_pe; a.rms = rms;
     a.eps = eps; a.inv_D = 1.0f / (float)D;
     if (defer) {
@@ -447,6 +451,18 @@ size_t lnpegn_workspace_bytes(int B, int T, int D, lnpegn_dtype dt)
             if (t > need) need = t;
         }
     return need;
+}
+
+int lnpegn_plan_query(int B, int T, int D, lnpegn_dtype dt, int per_example, int aligned, int64_t *out, int n_out)
+{
+    if (!shape_ok(B, T, D) || !out || n_out < 0) return LNPEGN_EINVAL;
+    if (!dtype_ok(dt)) return LNPEGN_EUNSUPPORTED;
+    const Plan p = make_plan(B, T, D, dt, per_example != 0, aligned != 0);
+    const int64_t v[LNPEGN_PLAN_FIELDS] = {
+        p.fast ? 1 : 0, p.S, p.fast ? p.R : 1, p.vpt, p.C, p.n_slots, p.rows_per, p.stagger, p.xcd_chunks,
+        (int64_t)p.lds_bytes, p.emit_pe ? 1 : 0, p.n_ex, p.G1, p.gs, (int64_t)p.total, p.Tp};
+    for (int i = 0; i < n_out && i < LNPEGN_PLAN_FIELDS; ++i) out[i] = v[i];
+    return LNPEGN_OK;
 }
 
 int lnpegn_last_hip_error(void) { return g_last_hip_error; }

@@ -52,6 +52,13 @@ int main(void)
                  NULL) == LNPEGN_EINVAL);
     CHECK(gns_estimate((const float *)x, (const float *)dy, 1, 1, 1.0f, (float *)dx, NULL) == LNPEGN_EINVAL);
     CHECK(lnpegn_set_tuning(99, 1) == LNPEGN_EINVAL);
+    {
+        int64_t plan[LNPEGN_PLAN_FIELDS];
+        CHECK(lnpegn_plan_query(16, 2048, 2048, LNPEGN_BF16, 1, 1, plan, LNPEGN_PLAN_FIELDS) == LNPEGN_OK);
+        CHECK(plan[0] == 1 && plan[5] == 16 * plan[4] && plan[15] == 2048);
+        CHECK((size_t)plan[14] <= lnpegn_workspace_bytes(16, 2048, 2048, LNPEGN_BF16));
+        CHECK(lnpegn_plan_query(16, 2048, 0, LNPEGN_BF16, 1, 1, plan, LNPEGN_PLAN_FIELDS) == LNPEGN_EINVAL);
+    }
 
     printf(failures ? "%d check(s) failed\n" : "all checks passed (%d failures)\n", failures);
     return failures ? 1 : 0;
