@@ -557,6 +557,29 @@ __device__ __forceinline__ int64_t lower_bound_pair(const uint32_t *keys, const 
     return lo;
 }
 
+// The same for one target that the whole wave shares: every round the 64 lanes probe 64 positions that cut the
+// range into 65 parts, and the number of probes below the target says which part to keep: three rounds of
+// loads for 32768 positions instead of fifteen.  [lo, hi) is wave-uniform; every lane must be active.
+__device__ __forceinline__ int64_t wave_lower_bound_pair(const uint32_t *keys, const uint32_t *vals, int64_t lo,
+                                                         int64_t hi, uint32_t v, uint32_t target, int lane)
+{
+    while (hi > lo) {
+        const int64_t len = hi - lo;
+        // probe j sits at lo + floor((j + 1) * len / 65), below hi; when len < 65 some probes repeat a position or
+        // sit at lo, which keeps the count monotone
+        const int64_t at = len <= 64 ? lo + (lane < len ? lane : len - 1) : lo + ((int64_t)(lane + 1) * len) / 65;
+        const uint32_t k = keys[at], p = vals[at];
+        const bool below = k < v || (k == v && p < target);
+        const int c = __builtin_popcountll(__ballot(below));        // probes are in order, so these are the first c
+        if (len <= 64) return lo + (c < len ? c : len);
+        const int64_t new_lo = c == 0 ? lo : lo + ((int64_t)c * len) / 65 + 1;
+        const int64_t new_hi = c == 64 ? hi : lo + ((int64_t)(c + 1) * len) / 65;
+        lo = new_lo;
+        hi = new_hi;
+    }
+    return lo;
+}
+
 // Kernel B, two launches.  First per run (kIds = false): a wave looks after the runs of long ids whose first
 // sorted position is among its kChunk positions and that kernel A marked as having several pieces; it adds
 // the run's parked piece sums in sorted order, squares the result (the run's share of s[b]) and parks it in
@@ -627,10 +650,12 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void emb_sums_kernel(
             }
         };
         if constexpr (kIds) {
+            // the id's positions end where (v + 1, 0) would go; the examples' runs are searched for inside them
+            const int64_t seg_end = wave_lower_bound_pair(keys, vals, i, n, v + 1u, 0u, lane);
             for (int b0 = 0; b0 < Bn; b0 += 64) {
                 const int b = b0 + lane;
                 const uint32_t target = (uint32_t)(b < Bn ? b : 0) * (uint32_t)Tn;
-                const int64_t at = lower_bound_pair(keys, vals, i, n, v, target);
+                const int64_t at = lower_bound_pair(keys, vals, i, seg_end, v, target);
                 const uint32_t k = at < n ? keys[at] : 0xffffffffu, pos = at < n ? vals[at] : 0u;
                 add_parked(__ballot(b < Bn && k == v && pos - target < (uint32_t)Tn), pos);
             }
@@ -640,7 +665,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void emb_sums_kernel(
                 if (lane == 0) bigpart[(int64_t)cb * n + p0] = wsq;
             }
         } else {
-            const int64_t end = lower_bound_pair(keys, vals, i, n, v, (ex0 + 1u) * (uint32_t)Tn);
+            const int64_t end = wave_lower_bound_pair(keys, vals, i, n, v, (ex0 + 1u) * (uint32_t)Tn, lane);
             const int64_t h1 = (i / kPiece + 1) * kPiece;        // the run's second piece, if it gets that far
             const int64_t npieces = 1 + (end > h1 ? (end - h1 + kPiece - 1) / kPiece : 0);
             for (int64_t u0 = 0; u0 < npieces; u0 += 64) {
@@ -700,16 +725,23 @@ __global__ __launch_bounds__(1024) void emb_final_kernel(const float *contrib, c
         if (wpart) {
             for (int i = threadIdx.x; i < nwpart; i += 1024) t += wpart[i];
         } else {
-            double part[16];                                     // sixteen loads in flight; the order stays fixed
+            // sixteen 16-byte loads in flight per thread; every thread's order of additions is fixed
+            double part[16];
 #pragma unroll
             for (int u = 0; u < 16; ++u) part[u] = 0.0;
-            const int64_t m = (int64_t)ncb * n;
+            const int64_t m = (int64_t)ncb * n, m4 = m / 4;       // bigpart is 256-byte aligned
+            const float4 *big4 = reinterpret_cast<const float4 *>(bigpart);
+            auto sum4 = [](const float4 &q) { return ((double)q.x + (double)q.y) + ((double)q.z + (double)q.w); };
             int64_t i = threadIdx.x;
-            for (; i + 15 * 1024 < m; i += 16 * 1024) {
+            for (; i + 15 * 1024 < m4; i += 16 * 1024) {
+                float4 q[16];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) part[u] += (double)bigpart[i + u * 1024];
+                for (int u = 0; u < 16; ++u) q[u] = big4[i + u * 1024];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) part[u] += sum4(q[u]);
             }
-            for (; i < m; i += 1024) part[0] += (double)bigpart[i];
+            for (; i < m4; i += 1024) part[0] += sum4(big4[i]);
+            for (i = m4 * 4 + threadIdx.x; i < m; i += 1024) part[1] += (double)bigpart[i];
 #pragma unroll
             for (int u = 0; u < 16; ++u) t += part[u];
         }
