@@ -13,7 +13,7 @@ SHAPES_D = (1, 8, 64, 256, 257, 576, 768, 960, 1001, 1024, 1280, 1536, 1600, 204
             9216, 12288, 16384, 20480)
 
 
-def _check(B, T, D, dt, per_example, aligned):
+def _check(B, T, D, dt, per_example, aligned, tuned=False):
     p = binding.plan_query(B, T, D, dt, per_example, aligned)
     E = 8 if dt == binding.BF16 else 4
     tag = (B, T, D, dt, per_example, aligned, p)
@@ -25,7 +25,9 @@ def _check(B, T, D, dt, per_example, aligned):
     if p["vector_kernel"]:
         S, R, vpt = p["waves_per_row"], p["row_groups"], p["vectors_per_lane"]
         assert aligned and D % E == 0, tag
-        assert 1 <= S <= 8 and R >= 1 and S * R <= 8, tag     # a workgroup has at most 512 threads
+        assert 1 <= S <= 8 and R >= 1 and S * R <= 8, tag     # a workgroup has at most 512 threads ...
+        if S <= 2 and vpt * E <= 8:
+            assert S * R <= 4, tag                            # ... 256 for the instantiations built with that bound
         assert 1 <= vpt <= 32 // E and 64 * S * vpt * E >= D, tag
         assert 64 * S * (vpt - 1) * E < D or vpt == 1, tag    # no lane slot that is all padding
         assert rows < 2 * R or C <= max(1, rows // (2 * R)), tag   # every row group gets two rows or more
@@ -34,12 +36,12 @@ def _check(B, T, D, dt, per_example, aligned):
     assert 0 < p["lds_bytes"] <= 160 * 1024, tag
     if p["rows_per_block"]:
         assert C > 1 and p["rows_per_block"] * C >= rows and p["rows_per_block"] * (C - 1) <= rows + C, tag
-        assert p["stagger"] == 0, tag
+        assert tuned or p["stagger"] == 0, tag
     if not per_example:
-        assert p["stagger"] == 0 and p["rows_per_block"] == 0, tag
+        assert p["stagger"] == 0 and (tuned or p["rows_per_block"] == 0), tag
         assert p["row_kernel_emits_norms"] == 0 and p["examples_in_reduction"] == 0, tag
     else:
-        assert 0 <= p["stagger"] < max(rows, 1) * 2, tag
+        assert tuned or 0 <= p["stagger"] < max(rows, 1) * 2, tag
         if p["row_kernel_emits_norms"]:
             assert C == 1 and p["examples_in_reduction"] == 0 and p["vector_kernel"], tag
         else:
@@ -63,6 +65,23 @@ def test_every_plan_is_runnable(dt):
             _check(B, T, D, dt, per_example, aligned)
             n += 1
     assert n > 10000
+
+
+@pytest.mark.parametrize("tuning", [((0, 7),), ((0, 16384), (1, 16384)), ((1, 3),), ((2, 1),), ((2, 16),), ((2, 6), (5, 1)),
+                                    ((5, 1),), ((5, 3),), ((8, 2),), ((8, 1), (3, 1000)), ((4, 2),), ((0, 513), (2, 8), (8, 2))])
+def test_every_plan_is_runnable_under_the_tuning_overrides(tuning):
+    keys = sorted({k for k, _ in tuning})
+    try:
+        for k, v in tuning:
+            binding.set_tuning(k, v)
+        for dt in (binding.BF16, binding.F32):
+            for B, T, D in itertools.product((1, 3, 16, 33, 300, 512, 1000), (1, 5, 33, 64, 130, 2048),
+                                             (8, 257, 768, 1024, 1600, 2048, 3072, 8192, 12288)):
+                for per_example, aligned in ((True, True), (False, True), (True, False)):
+                    _check(B, T, D, dt, per_example, aligned, tuned=True)
+    finally:
+        for k in keys:
+            binding.set_tuning(k, 0)
 
 
 def test_plans_of_the_benchmark_workloads():
