@@ -113,6 +113,31 @@ def test_any_D_is_correct(B, T, D, dtype):
         pu.compare_with_oracle(inp, res, ref)
 
 
+@pytest.mark.parametrize("B,T,D,dtype", [
+    (3, 70, 1280, "bf16"),      # two waves per row, lanes left over: four row groups
+    (2, 90, 1536, "bf16"),
+    (2, 41, 1600, "bf16"),
+    (3, 50, 2560, "bf16"),      # three waves per row (run-time wave count), two row groups, padded
+    (2, 64, 3072, "bf16"),      # ... full rows
+    (2, 33, 5120, "bf16"),      # five waves
+    (2, 40, 6144, "bf16"),      # six waves
+    (2, 21, 7168, "bf16"),      # seven waves
+    (3, 37, 1280, "f32"),       # fp32: two waves of three vectors, padded
+    (2, 50, 1536, "f32"),
+    (2, 33, 3072, "f32"),       # three waves of four vectors
+    (2, 18, 5120, "f32"),       # beyond eight waves of four vectors: five to eight vectors per lane
+])
+@pytest.mark.parametrize("saved", [False, True])
+def test_row_widths_between_the_powers_of_two(B, T, D, dtype, saved):
+    """Every launch shape that the row widths between the benchmark's choose."""
+    inp = workloads.make_inputs(3 if dtype == "bf16" else 1, B=B, T=T, D=D, dtype=dtype)
+    ref = _oracle(inp)
+    res = pu.run_gpu(inp, saved_stats=saved)
+    pu.compare_with_oracle(inp, res, ref)
+    plain = pu.run_gpu(inp, saved_stats=saved, pegn=False)
+    pu.compare_with_oracle(inp, plain, ref, pegn=False)
+
+
 @pytest.mark.parametrize("B,T,D,dtype", [(2, 33, 12288, "bf16"), (2, 17, 16384, "bf16"), (3, 9, 10240, "bf16"),
                                          (2, 9, 12288, "f32"), (1, 5, 16384, "f32"), (2, 7, 9216, "f32"),
                                          (2, 6, 14336, "f32")])
