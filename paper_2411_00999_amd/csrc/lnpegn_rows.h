@@ -2,16 +2,16 @@
 // column sums  A_gamma[k] = sum_t dy*xhat,  A_beta[k] = sum_t dy  over one chunk of rows.
 //
 // Work partition.  The N = B*T rows are cut into `n_slots` chunks, one workgroup each.  For the
-// per-example path chunks never straddle an example: example b owns chunks [b*C, (b+1)*C) and
-// chunk j of it takes rows j, j+C, j+2C, ... of that example, so the per-example sums of
-// Appendix B steps 1 and 5 are sums of whole chunks and the workgroups of an example sweep one
-// moving window of memory together.  The plain backward uses the same kernels with the whole
-// tensor declared as one "example" (Tp = N).
+// per-example path chunks never straddle an example: example b owns chunks [b*C, (b+1)*C), so the
+// per-example sums of Appendix B steps 1 and 5 are sums of whole chunks.  Chunk j takes rows
+// j, j+C, j+2C, ... of its example (the workgroups of an example then sweep one moving window of
+// memory together) or, when the host says so, a block of consecutive rows.  The plain backward
+// uses the same kernels with the whole tensor declared as one "example" (Tp = N).
 //
 // Lane mapping.  A lane owns the same columns for every row it touches, so the sums over t
 // live in registers and never move between lanes; only the per-row scalars cross lanes, on the
 // DPP network.  A workgroup is R row groups of S waves: the S waves of a group share a row
-// (each owns different columns, at most 16 per lane), the R groups take different rows and
+// (each owns different columns, 16 per lane and up to 32 for the widest rows), the R groups take different rows and
 // merge their column sums through LDS in group order when the chunk is done.
 #pragma once
 #include <type_traits>
