@@ -510,6 +510,20 @@ def test_full_size_workloads(cfg):
         assert got[3] == pytest.approx(closed, rel=pu.TOL_GNS)
 
 
+def test_full_size_headline_shape_in_fp32():
+    """B=16 T=2048 D=2048 with fp32 storage, the launch configuration bench.py times (2048 chunks, several rounds
+    of workgroups)."""
+    from paper_2411_00999_amd import binding
+    inp = workloads.make_inputs(3, dtype="f32")
+    assert binding.plan_query(inp.B, inp.T, inp.D, binding.F32)["chunks"] == 2048
+    ref = _oracle(inp, want_dx=False)
+    res = pu.run_gpu(inp)
+    pu.compare_with_oracle(inp, res, ref)
+    _sampled_dx_check(inp, res, seed=33)
+    got, want = _gns_both(res, ref, inp.B)
+    _check_gns(got, want, inp.B)
+
+
 # ------------------------------------------------------------------ GNS tracker: EMA, offline jackknife, schedule
 def _records(g2, s):
     """[n,5] fp32 records with G2 and S in the places gns_estimate writes them."""
