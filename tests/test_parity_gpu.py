@@ -221,6 +221,9 @@ def test_misaligned_pointers_take_the_generic_kernel():
     (130, 48, 2048, "bf16"),    # too short to cut: a chunk is a whole example, rows of two waves
     (512, 32, 1024, "bf16"),    # a chunk is a whole example, eight rows at a time
     (520, 33, 512, "f32"),      # the same with four rows at a time and a ragged tail
+    (300, 100, 1024, "bf16"),   # shapes of the measurements: five blocks of 20 rows per example, three rounds
+    (64, 512, 1024, "bf16"),    # eight blocks of 64 rows
+    (600, 64, 2048, "bf16"),    # two waves per row, two blocks per example
 ])
 def test_many_short_examples(B, T, D, dtype):
     """More examples than the row kernel has workgroups for: the chunk layouts of that regime."""
