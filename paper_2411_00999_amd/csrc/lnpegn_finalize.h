@@ -232,7 +232,7 @@ __global__ __launch_bounds__(1024) void reduce_final_small_kernel(ReduceArgs a)
 
 // Many layers at once (deferred reduction).  Every layer's workspace starts with a DeferHeader
 // and has the same layout, because the layers have the same shape.
-constexpr int kBatchMax = 32;
+constexpr int kBatchMax = 64;
 struct BatchArgs {
     char *ws[kBatchMax];
     int n;
