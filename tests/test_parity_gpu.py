@@ -305,6 +305,26 @@ def test_deferred_reduction_matches_immediate_calls_bitwise(cfg, B, T, D):
 
 
 # ------------------------------------------------------------------ forward, accumulation
+def test_deferred_reduction_of_more_layers_than_one_launch_takes():
+    """70 layers: lnpegn_reduce_deferred finishes them in two rounds of launches (64 + 6)."""
+    import torch
+    from paper_2411_00999_amd import binding
+    B, T, D, n_layers = 3, 20, 256, 70
+    immediate, deferred, wss = [], [], []
+    for l in range(n_layers):
+        inp = workloads.make_inputs(1, layer=l, B=B, T=T, D=D)
+        x, dy, gamma = (pu.to_device(a, inp.dtype) for a in (inp.x, inp.dy, inp.gamma))
+        immediate.append(binding.ln_bwd_pegn(x, dy, gamma, inp.eps))
+        ws = binding.alloc_workspace(B, T, D, binding.F32)
+        wss.append(ws)
+        deferred.append(binding.ln_bwd_pegn(x, dy, gamma, inp.eps, workspace=ws, deferred=True))
+    binding.reduce_deferred(wss, B, T, D, binding.F32)
+    torch.cuda.synchronize()
+    for l, (a, b) in enumerate(zip(immediate, deferred)):
+        for u, v in zip(a, b):
+            assert torch.equal(u, v), l
+
+
 @pytest.mark.parametrize("cfg,B,T,D", [(1, 4, 128, 256), (2, 3, 37, 768), (3, 2, 50, 2048), (5, 2, 9, 8192),
                                       (1, 2, 7, 257), (2, 2, 5, 1001), (5, 2, 7, 12288), (5, 1, 5, 16384),
                                       (1, 2, 5, 12288), (1, 1, 3, 16384), (5, 1, 3, 20480)])
