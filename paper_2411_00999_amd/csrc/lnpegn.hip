@@ -336,7 +336,7 @@ int run_bwd(bool pegn, bool defer, bool accumulate, bool rms, const void *x, con
     ra.big_sq = pegn ? big_sq : nullptr;
     ra.n_slots = (int)p.n_slots; ra.gs = p.gs; ra.G1 = p.G1; ra.n_ex = p.n_ex; ra.ex_gs = p.C; ra.D = D; ra.ntile = p.ntile;
     ra.accumulate = accumulate;
-    if (launch(reduce_groups_kernel, dim3((unsigned)reduce_groups_count(ra), (unsigned)p.ntile), dim3(kTile), 0, s, ra) != hipSuccess) return LNPEGN_EHIP;
+    if (launch(reduce_groups_kernel, dim3((unsigned)p.ntile, (unsigned)reduce_groups_count(ra)), dim3(kTile), 0, s, ra) != hipSuccess) return LNPEGN_EHIP;
     const bool need_scalars = p.n_ex > 0 || ra.big_sq != nullptr;
     if (p.G1 == 1 || (int64_t)p.G1 * D <= kSmallFinal) {
         if (p.G1 > 1 || need_scalars) {
@@ -624,7 +624,7 @@ int lnpegn_reduce_deferred(void *const *workspaces, int n, int B, int T, int D, 
         b.D = D; b.ntile = p.ntile;
         b.off_grp = p.off_grp; b.off_part_s = p.off_part_s; b.off_part_big = p.off_part_big;
         b.off_part = p.off_part;
-        if (launch(reduce_groups_batch_kernel, dim3((unsigned)g1_max, (unsigned)p.ntile, (unsigned)b.n), dim3(kTile), 0, s, b) != hipSuccess) return LNPEGN_EHIP;
+        if (launch(reduce_groups_batch_kernel, dim3((unsigned)p.ntile, (unsigned)g1_max, (unsigned)b.n), dim3(kTile), 0, s, b) != hipSuccess) return LNPEGN_EHIP;
         if (launch(reduce_final_batch_kernel, dim3((unsigned)b.n), dim3(1024), 0, s, b) != hipSuccess) return LNPEGN_EHIP;
     }
     return LNPEGN_OK;

@@ -43,8 +43,11 @@ __host__ __device__ inline int reduce_groups_count(const ReduceArgs &a)
 // These kernels are a handful of dependent memory round trips long, so every level issues its
 // loads in batches of eight before it adds them (in index order: the sums are reproducible).
 
-// Level 1.  grid (reduce_groups_count, ntile), 256 threads.  A workgroup adds the column sums of a run of consecutive
-// chunks: the four waves split the run, add in chunk order, then the waves' partial sums are added in wave order.
+// Level 1.  grid (ntile, reduce_groups_count), 256 threads: the column tiles of a run of chunks are neighbours in
+// launch order, so that the 1 KiB pieces they read of the same chunk vectors are fetched together (with the tiles
+// as the slow grid index the batched launch of the 48-layer step took 57 us instead of 35).  A workgroup adds
+// the column sums of a run of consecutive chunks: the four waves split the run, add in chunk order, then the
+// waves' partial sums are added in wave order.
 // The first n_ex workgroups of a tile take one example each and leave the squares of its sums (their sums are
 // not kept); the other G1 take one group of chunks each, for the batch gradients.  With a single group the group
 // sums ARE the batch gradients and go straight to dgamma / dbeta.
@@ -145,7 +148,7 @@ __device__ __forceinline__ void reduce_groups_body(const ReduceArgs &a, int gx, 
 
 __global__ __launch_bounds__(kTile) void reduce_groups_kernel(ReduceArgs a)
 {
-    reduce_groups_body(a, blockIdx.x, blockIdx.y);
+    reduce_groups_body(a, blockIdx.y, blockIdx.x);
 }
 
 // Sum over the groups for one column (Appendix B steps 3, 7), groups added in order.
@@ -257,12 +260,12 @@ __device__ __forceinline__ ReduceArgs batch_layer_args(const BatchArgs &b, int l
     return a;
 }
 
-// grid (most examples + groups of any layer, ntile, layers): workgroups beyond a layer's own count leave at once
+// grid (ntile, most examples + groups of any layer, layers): workgroups beyond a layer's own count leave at once
 __global__ __launch_bounds__(kTile) void reduce_groups_batch_kernel(BatchArgs b)
 {
     const ReduceArgs a = batch_layer_args(b, blockIdx.z);
-    if ((int)blockIdx.x >= reduce_groups_count(a)) return;
-    reduce_groups_body(a, blockIdx.x, blockIdx.y);
+    if ((int)blockIdx.y >= reduce_groups_count(a)) return;
+    reduce_groups_body(a, blockIdx.y, blockIdx.x);
 }
 
 // grid (layers)
