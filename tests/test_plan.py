@@ -98,6 +98,22 @@ def test_plans_of_the_benchmark_workloads():
     assert (p["waves_per_row"], p["row_groups"], p["vectors_per_lane"], p["chunks"]) == (2, 3, 4, 2048)
     p = q(300, 100, 1024, binding.BF16)                      # examples cut finer than one round of workgroups
     assert p["chunks_per_example"] == 5 and p["rows_per_block"] == 20
+    # the other rules of the planning, one shape each (figures of the measurements they came from: the source)
+    for shape, want in {
+        (600, 64, 1024): (1, 4, 3, 22),      # a last round that would be a sixth full: three rounds of blocks instead
+        (513, 64, 1024): (1, 4, 3, 22),
+        (260, 128, 1024): (1, 4, 6, 22),     # half a round: three rounds
+        (700, 48, 1024): (1, 8, 1, 0),       # a second round more than a third full: whole examples, eight rows at a time
+        (1000, 32, 1024): (1, 8, 1, 0),
+        (64, 512, 1024): (1, 4, 8, 64),      # more than 32 examples: blocks of rows
+        (32, 1024, 2048): (2, 3, 8, 0),      # up to 32: every C-th row
+        (16, 2048, 1280): (2, 4, 16, 0),     # two waves per row with lanes left over: four row groups
+        (16, 2048, 3072): (3, 2, 16, 0),     # three waves per row: two row groups
+        (16, 2048, 6144): (6, 1, 32, 0),     # six waves per row: two rounds
+    }.items():
+        p = q(*shape, binding.BF16)
+        got = (p["waves_per_row"], p["row_groups"], p["chunks_per_example"], p["rows_per_block"])
+        assert got == want, (shape, got, want)
 
 
 def test_plan_follows_the_tuning_and_rejects_bad_arguments():
