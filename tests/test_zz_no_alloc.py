@@ -96,6 +96,46 @@ def test_largest_benchmark_shape_fits_the_fixed_scratch():
     assert torch.isfinite(got[3]).all() and float(got[5][0]) > 0.0
 
 
+def test_static_scratch_call_replays_from_a_graph():
+    """What the entry point is for: a caller under HIP graph capture, which cannot allocate.  The first call on
+    the device is made outside the capture (it looks the scratch address up); the captured step then allocates
+    nothing, and every replay gives the eager results bit for bit, with eager work in between."""
+    import torch
+    from paper_2411_00999_amd import binding
+    B, T, D = 4, 96, 2048
+    inp = workloads.make_inputs(3, B=B, T=T, D=D)
+    x, dy, gamma = (pu.to_device(a, inp.dtype) for a in (inp.x, inp.dy, inp.gamma))
+    out = _buffers(B, T, D, "bf16")
+    pe = torch.empty((2, B), dtype=torch.float32, device="cuda")
+    gns = torch.empty(5, dtype=torch.float32, device="cuda")
+
+    def step():
+        binding.ln_bwd_pegn_static(x, dy, gamma, inp.eps, out["dx"], out["dgamma"], out["dbeta"], pe[0], pe[1],
+                                   out["big_sq"])
+        binding.gns_estimate(pe, out["big_sq"], float(B), out=gns)
+
+    step()
+    torch.cuda.synchronize()
+    tensors = [out[k] for k in ("dx", "dgamma", "dbeta", "big_sq")] + [pe, gns]
+    want = [t.clone() for t in tensors]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for replay in range(3):
+        for t in tensors:
+            t.fill_(-1.0)
+        a = torch.randn(1 << 20, device="cuda")
+        float((a * a).sum())                     # eager work and a synchronisation between the replays
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(g, w) for g, w in zip(tensors, want)), f"replay {replay}"
+
+
 def test_shape_beyond_the_fixed_scratch_is_refused():
     """Host validation only: nothing is launched, the fake pointers are never dereferenced."""
     import ctypes
